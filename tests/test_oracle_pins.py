@@ -1,0 +1,357 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix, none of which is the
+oracle's own formula retyped.  A dropped term, wrong sign, wrong index or transposed operand
+in ``oracle/dlrt_oracle.c`` fails at least one of these.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2207_08820_amd import inputs
+
+UNSIGNED, TWOS, BIPOLAR = 0, 1, 2
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def rand_values(r, shape, bits, enc):
+    if enc == BIPOLAR:
+        return (2 * r.integers(0, 2, size=shape) - 1).astype(np.int8)
+    lo, hi = inputs.value_bounds(bits, enc)
+    return r.integers(lo, hi + 1, size=shape).astype(np.int8)
+
+
+# ---- independent brute force of Section V's equation, in pure Python ints -----------------------
+def planes_of(values, bits, enc):
+    """One Python int per plane; bit k of plane p = bit p of element k's pattern."""
+    planes = [0] * bits
+    for k, v in enumerate(int(x) for x in values):
+        pattern = (1 if v > 0 else 0) if enc == BIPOLAR else v & ((1 << bits) - 1)
+        for p in range(bits):
+            if (pattern >> p) & 1:
+                planes[p] |= 1 << k
+    return planes
+
+
+def plane_sign(p, bits, enc):
+    return -1 if (enc == TWOS and p == bits - 1) else 1
+
+
+def bitserial_dot(a, w, abits, wbits, enc_a, enc_w):
+    """sum_i sum_j +-popcount(W[i] & A[j]) << (i + j); bipolar weights via 2*pc(a&w) - pc(a)."""
+    A = planes_of(a, abits, enc_a)
+    W = planes_of(w, wbits, enc_w)
+    total = 0
+    for j in range(abits):
+        sa = plane_sign(j, abits, enc_a)
+        if enc_w == BIPOLAR:
+            total += sa * (1 << j) * (2 * bin(A[j] & W[0]).count("1") - bin(A[j]).count("1"))
+        else:
+            for i in range(wbits):
+                total += sa * plane_sign(i, wbits, enc_w) * (bin(W[i] & A[j]).count("1") << (i + j))
+    return total
+
+
+ENCODING_CASES = [(a, w, ea, ew)
+                  for a, w in itertools.product(range(1, 5), repeat=2)
+                  for ea in (UNSIGNED, TWOS) for ew in (UNSIGNED, TWOS)] + \
+                 [(a, 1, ea, BIPOLAR) for a in range(1, 5) for ea in (UNSIGNED, TWOS)]
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 64, 100])
+def test_gemm_equals_bitplane_identity_brute_force(oracle, K):
+    r = rng(1000 + K)
+    for abits, wbits, ea, ew in ENCODING_CASES:
+        a = rand_values(r, (3, K), abits, ea)
+        w = rand_values(r, (4, K), wbits, ew)
+        c = oracle.gemm_i32(a, w)
+        for m in range(3):
+            for n in range(4):
+                assert c[m, n] == bitserial_dot(a[m], w[n], abits, wbits, ea, ew), (abits, wbits, ea, ew)
+
+
+def test_gemm_hand_example_from_fixture(oracle):
+    vals = {}
+    with open(os.path.join(GOLDEN, "section5_hand_example.txt")) as f:
+        for line in f:
+            if line.startswith("#") or "=" not in line:
+                continue
+            key, rhs = line.split("=")
+            vals[key.strip()] = [int(t) for t in rhs.split()]
+    a = np.array([vals["a"]], dtype=np.int8)
+    w = np.array([vals["w"]], dtype=np.int8)
+    assert oracle.gemm_i32(a, w)[0, 0] == vals["dot"][0]
+    assert oracle.pack_bitplanes(a, 2, UNSIGNED).ravel().tolist() == vals["packed_a"]
+    assert oracle.pack_bitplanes(w, 2, TWOS).ravel().tolist() == vals["packed_w"]
+    assert bitserial_dot(a[0], w[0], 2, 2, UNSIGNED, TWOS) == vals["dot"][0]
+
+
+@pytest.mark.parametrize("abits,wbits", list(itertools.product(range(1, 5), repeat=2)))
+def test_gemm_closed_forms(oracle, abits, wbits):
+    M, N, K = 5, 7, 77
+    amax, wmax = (1 << abits) - 1, (1 << wbits) - 1
+    a = np.full((M, K), amax, np.int8)
+    assert np.all(oracle.gemm_i32(a, np.full((N, K), wmax, np.int8)) == K * amax * wmax)
+    assert np.all(oracle.gemm_i32(a, np.zeros((N, K), np.int8)) == 0)
+    assert np.all(oracle.gemm_i32(np.zeros((M, K), np.int8), np.full((N, K), wmax, np.int8)) == 0)
+    wmin = -(1 << (wbits - 1))
+    assert np.all(oracle.gemm_i32(a, np.full((N, K), wmin, np.int8)) == -K * amax * (1 << (wbits - 1)))
+    # bipolar: all +1 weights give +sum(a), all -1 give -sum(a)
+    r = rng(7)
+    av = rand_values(r, (M, K), abits, UNSIGNED)
+    s = av.astype(np.int64).sum(axis=1)
+    assert np.array_equal(oracle.gemm_i32(av, np.ones((N, K), np.int8)), np.tile(s[:, None], (1, N)))
+    assert np.array_equal(oracle.gemm_i32(av, -np.ones((N, K), np.int8)), np.tile(-s[:, None], (1, N)))
+
+
+def test_gemm_linear_in_each_bitplane(oracle):
+    r = rng(11)
+    M, N, K = 4, 6, 50
+    for abits, enc_a in ((2, UNSIGNED), (3, TWOS), (4, UNSIGNED)):
+        w = rand_values(r, (N, K), 3, TWOS)
+        a = rand_values(r, (M, K), abits, enc_a)
+        base = oracle.gemm_i32(a, w)
+        for _ in range(20):
+            m, k, p = int(r.integers(M)), int(r.integers(K)), int(r.integers(abits))
+            pattern = int(a[m, k]) & ((1 << abits) - 1)
+            flipped = pattern ^ (1 << p)
+            # decode the flipped pattern back to a value
+            val = flipped - (1 << abits) if (enc_a == TWOS and flipped >> (abits - 1)) else flipped
+            a2 = a.copy()
+            a2[m, k] = val
+            went_up = (flipped >> p) & 1
+            delta = plane_sign(p, abits, enc_a) * (1 << p) * (1 if went_up else -1)
+            expect = base.copy()
+            expect[m, :] += delta * w[:, k].astype(np.int32)
+            assert np.array_equal(oracle.gemm_i32(a2, w), expect)
+
+
+def test_gemm_matches_numpy_int64_matmul_and_is_not_transposed(oracle):
+    r = rng(5)
+    a = rand_values(r, (37, 201), 4, UNSIGNED)
+    w = rand_values(r, (53, 201), 4, TWOS)
+    ref = a.astype(np.int64) @ w.astype(np.int64).T
+    got = oracle.gemm_i32(a, w)
+    assert got.shape == (37, 53) and np.array_equal(got, ref)
+
+
+# ---- convolution -------------------------------------------------------------------------------
+def torch_conv(x, w, stride, pad):
+    xt = torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2)
+    y = torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad)
+    return y.permute(0, 2, 3, 1).numpy().round().astype(np.int64)
+
+
+@pytest.mark.parametrize("H,W,Ci,Co,k,stride,pad", [
+    (9, 7, 5, 6, 3, 1, 1), (10, 10, 33, 4, 3, 2, 1), (9, 9, 8, 3, 3, 2, 1), (8, 6, 16, 8, 1, 2, 0),
+    (6, 6, 4, 4, 1, 1, 0), (7, 7, 3, 2, 5, 1, 2), (5, 8, 7, 3, 3, 1, 0)])
+def test_conv_matches_torch_float64(oracle, H, W, Ci, Co, k, stride, pad):
+    r = rng(H * 100 + W)
+    x = rand_values(r, (2, H, W, Ci), 2, UNSIGNED)
+    w = rand_values(r, (Co, k, k, Ci), 2, TWOS)
+    got = oracle.conv2d_i32(x, w, (stride, stride), (pad, pad))
+    assert np.array_equal(got, torch_conv(x, w, stride, pad))
+
+
+def test_conv_rectangular_stride_and_pad_match_torch(oracle):
+    r = rng(77)
+    x = rand_values(r, (1, 11, 9, 6), 3, UNSIGNED)
+    w = rand_values(r, (5, 3, 3, 6), 4, TWOS)
+    got = oracle.conv2d_i32(x, w, (2, 1), (0, 1))
+    assert np.array_equal(got, torch_conv(x, w, (2, 1), (0, 1)))
+
+
+def test_conv_1x1_is_gemm(oracle):
+    r = rng(21)
+    x = rand_values(r, (2, 6, 5, 40), 2, UNSIGNED)
+    w = rand_values(r, (9, 1, 1, 40), 2, TWOS)
+    y = oracle.conv2d_i32(x, w)
+    assert np.array_equal(y.reshape(-1, 9), oracle.gemm_i32(x.reshape(-1, 40), w.reshape(9, 40)))
+
+
+def im2col(x, k, stride, pad):
+    N, H, W, C = x.shape
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    xp = np.zeros((N, H + 2 * pad, W + 2 * pad, C), x.dtype)
+    xp[:, pad:pad + H, pad:pad + W] = x
+    cols = np.empty((N, Ho, Wo, k, k, C), x.dtype)
+    for kh in range(k):
+        for kw in range(k):
+            cols[:, :, :, kh, kw] = xp[:, kh:kh + stride * Ho:stride, kw:kw + stride * Wo:stride]
+    return cols.reshape(N * Ho * Wo, k * k * C)
+
+
+def test_conv_is_im2col_plus_gemm(oracle):
+    r = rng(22)
+    x = rand_values(r, (1, 12, 12, 16), 2, UNSIGNED)
+    w = rand_values(r, (8, 3, 3, 16), 2, TWOS)
+    for stride in (1, 2):
+        y = oracle.conv2d_i32(x, w, (stride, stride), (1, 1))
+        assert np.array_equal(y.reshape(-1, 8), oracle.gemm_i32(im2col(x, 3, stride, 1), w.reshape(8, -1)))
+
+
+def test_conv_delta_kernel_shifts_input_with_zero_border(oracle):
+    r = rng(23)
+    H, W, Ci, Co = 8, 7, 3, 4
+    x = rand_values(r, (1, H, W, Ci), 2, UNSIGNED)
+    for kh, kw, ci, co, stride in [(0, 0, 1, 2, 1), (2, 1, 0, 3, 1), (1, 2, 2, 0, 2), (0, 2, 1, 1, 2)]:
+        w = np.zeros((Co, 3, 3, Ci), np.int8)
+        w[co, kh, kw, ci] = 1
+        y = oracle.conv2d_i32(x, w, (stride, stride), (1, 1))
+        Ho, Wo = y.shape[1:3]
+        expect = np.zeros((Ho, Wo), np.int32)
+        for oh in range(Ho):
+            for ow in range(Wo):
+                ih, iw = oh * stride - 1 + kh, ow * stride - 1 + kw
+                if 0 <= ih < H and 0 <= iw < W:
+                    expect[oh, ow] = x[0, ih, iw, ci]
+        assert np.array_equal(y[0, :, :, co], expect)
+        other = [c for c in range(Co) if c != co]
+        assert not y[0, :, :, other].any()
+
+
+def test_conv_all_ones_counts_in_image_taps(oracle):
+    Ci = 5
+    x = np.ones((1, 6, 6, Ci), np.int8)
+    w = np.ones((2, 3, 3, Ci), np.int8)
+    y = oracle.conv2d_i32(x, w, (1, 1), (1, 1))
+    assert y[0, 2, 3, 0] == 9 * Ci and y[0, 0, 0, 1] == 4 * Ci and y[0, 0, 3, 0] == 6 * Ci and y[0, 5, 5, 0] == 4 * Ci
+
+
+def test_conv_bipolar_padding_contributes_zero(oracle):
+    """A padded tap is activation 0 times +-1 = 0: the oracle must not count it as -1 * a."""
+    r = rng(24)
+    x = rand_values(r, (1, 5, 5, 4), 2, UNSIGNED)
+    w = rand_values(r, (3, 3, 3, 4), 1, BIPOLAR)
+    y = oracle.conv2d_i32(x, w, (1, 1), (1, 1))
+    assert np.array_equal(y, torch_conv(x, w, 1, 1))
+    # corner output by hand: taps (kh,kw) in {1,2}x{1,2} only
+    manual = sum(int(x[0, kh - 1, kw - 1, c]) * int(w[2, kh, kw, c])
+                 for kh in (1, 2) for kw in (1, 2) for c in range(4))
+    assert y[0, 0, 0, 2] == manual
+
+
+# ---- packing -----------------------------------------------------------------------------------
+def unpack(words, K, bits, enc):
+    rows = words.shape[0]
+    out = np.zeros((rows, K), np.int64)
+    for k in range(K):
+        pattern = np.zeros(rows, np.int64)
+        for p in range(bits):
+            pattern |= ((words[:, p, k // 32].astype(np.int64) >> (k % 32)) & 1) << p
+        out[:, k] = pattern
+    if enc == TWOS:
+        out = np.where(out >> (bits - 1) == 1, out - (1 << bits), out)
+    elif enc == BIPOLAR:
+        out = 2 * out - 1
+    return out
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 64, 100])
+def test_pack_round_trip_popcounts_and_size(oracle, K):
+    r = rng(300 + K)
+    for bits, enc in [(1, UNSIGNED), (2, UNSIGNED), (2, TWOS), (3, TWOS), (4, UNSIGNED), (4, TWOS), (1, BIPOLAR), (1, TWOS)]:
+        q = rand_values(r, (5, K), bits, enc)
+        words = oracle.pack_bitplanes(q, bits, enc)
+        assert words.shape == (5, bits, (K + 31) // 32) and words.dtype == np.uint32
+        assert words.size == oracle.packed_words(5, K, bits)
+        assert np.array_equal(unpack(words, K, bits, enc), q.astype(np.int64))
+        for p in range(bits):
+            pattern = np.where(q > 0, 1, 0) if enc == BIPOLAR else q.astype(np.int64) & ((1 << bits) - 1)
+            expect = ((pattern >> p) & 1).sum(axis=1)
+            got = np.array([sum(bin(int(x)).count("1") for x in words[row, p]) for row in range(5)])
+            assert np.array_equal(got, expect)
+
+
+def test_pack_k33_puts_one_bit_in_second_word_and_size_is_bits_over_8_bytes(oracle):
+    q = np.zeros((1, 33), np.int8)
+    q[0, 32] = 1
+    words = oracle.pack_bitplanes(q, 2, UNSIGNED)
+    assert words.tolist() == [[[0, 1], [0, 0]]]
+    # Section VIII's "16x compression with 2-bit": 2 bits per element versus 32
+    K = 4096
+    assert oracle.packed_words(1, K, 2) * 4 * 16 == K * 4
+
+
+def test_pack_conv_weights_pads_every_tap_to_whole_words(oracle):
+    r = rng(31)
+    Co, k, Ci = 3, 3, 40
+    w = rand_values(r, (Co, k, k, Ci), 2, TWOS)
+    got = oracle.pack_conv_weights(w, 2, TWOS)
+    Cw = 2
+    assert got.shape == (Co, 2, k * k * Cw)
+    # each tap packed on its own as a row of Ci values
+    per_tap = oracle.pack_bitplanes(w.reshape(Co * k * k, Ci), 2, TWOS).reshape(Co, k * k, 2, Cw)
+    assert np.array_equal(got.reshape(Co, 2, k * k, Cw), per_tap.transpose(0, 2, 1, 3))
+
+
+# ---- epilogue and quantizer ----------------------------------------------------------------------
+def test_epilogue_special_cases_and_float64_reference(oracle):
+    r = rng(41)
+    C = 13
+    acc = r.integers(-500000, 500000, size=(17, C)).astype(np.int32)
+    scale = r.uniform(0.01, 0.1, C).astype(np.float32)
+    bias = r.uniform(-3, 3, C).astype(np.float32)
+    y, _ = oracle.epilogue_f32(np.zeros_like(acc), scale, bias)
+    assert np.array_equal(y, np.tile(bias, (17, 1)))
+    y, _ = oracle.epilogue_f32(acc, np.ones(C, np.float32), None)
+    assert np.array_equal(y, acc.astype(np.float32))
+    y, _ = oracle.epilogue_f32(acc, scale, bias)
+    ref = (acc.astype(np.float64) * scale.astype(np.float64) + bias.astype(np.float64))
+    # a single fused multiply-add is the correctly rounded value of the exact expression
+    assert np.array_equal(y, ref.astype(np.float32))
+    # scale varies along the LAST axis (channels), not along rows
+    y2, _ = oracle.epilogue_f32(np.ones((2, 3), np.int32), np.array([1, 2, 3], np.float32), None)
+    assert y2.tolist() == [[1, 2, 3], [1, 2, 3]]
+
+
+def test_epilogue_requant_ties_to_even_and_clamps(oracle):
+    acc = np.array([[1, 3, 5, 7, -3, 9, 100]], np.int32)
+    scale = np.full(7, 0.5, np.float32)
+    _, q = oracle.epilogue_f32(acc, scale, None, qbits=2)
+    #            0.5 1.5 2.5 3.5 -1.5 4.5 50
+    assert q.tolist() == [[0, 2, 2, 3, 0, 3, 3]]
+    _, q = oracle.epilogue_f32(acc, scale, None, qbits=4)
+    assert q.tolist() == [[0, 2, 2, 4, 0, 4, 15]]
+
+
+def test_quantizer_ranges_grid_points_saturation_and_error_bound(oracle):
+    r = rng(51)
+    s = np.float32(0.37)
+    for bits in (1, 2, 3, 4):
+        lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1  # Section IV: -Q_N, Q_P
+        x = r.normal(0, 2.0, size=(4, 200)).astype(np.float32)
+        q = oracle.quantize(x, s, bits, TWOS)
+        assert q.min() >= lo and q.max() <= hi
+        assert q.min() == lo and q.max() == hi  # wide input: both clip limits reached
+        grid = np.arange(lo, hi + 1)
+        assert oracle.quantize((grid * s).astype(np.float32)[None], s, bits, TWOS).ravel().tolist() == grid.tolist()
+        inside = (x / s >= lo) & (x / s <= hi)
+        err = np.abs(x.astype(np.float64) - q.astype(np.float64) * float(s))
+        assert np.all(err[inside] <= float(s) / 2 * (1 + 1e-6))
+    assert oracle.quantize(np.array([[1e9, -1e9]], np.float32), 1.0, 2, TWOS).tolist() == [[1, -2]]
+    assert oracle.quantize(np.array([[1e9, -1e9, 2.5, 0.5, 1.5]], np.float32), 1.0, 2, UNSIGNED).tolist() == [[3, 0, 2, 0, 2]]
+    # per-row scales
+    xr = np.array([[1.0, 2.0], [1.0, 2.0]], np.float32)
+    assert oracle.quantize(xr, np.array([1.0, 0.5], np.float32), 4, UNSIGNED).tolist() == [[1, 2], [2, 4]]
+
+
+# ---- workload tables (host logic) -----------------------------------------------------------------
+def test_workload_tables_match_the_stated_shapes():
+    r18 = inputs.resnet18_stack()
+    assert len(r18) == 19
+    assert sum(L.macs for L in r18) == 1695547392  # 1695.5 MMAC
+    assert [(L.M, L.Co, L.K) for L in r18[:6]] == [(3136, 64, 576)] * 4 + [(784, 128, 576), (784, 128, 64)]
+    assert (r18[-1].M, r18[-1].Co, r18[-1].K) == (49, 512, 4608)
+    assert r18[5].src == r18[4].src == 3 and r18[6].src == 4
+    yolo = inputs.yolo_style_stack()
+    assert len(yolo) == 16
+    assert (yolo[0].M, yolo[0].Co, yolo[0].K) == (25600, 64, 288)
+    assert (yolo[12].M, yolo[12].Co, yolo[12].K) == (400, 512, 2304)
+    assert abs(sum(L.macs for L in yolo) / 1e6 - 2621.4) < 0.1
