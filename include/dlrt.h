@@ -1,0 +1,128 @@
+/*
+ * dlrt.h - C ABI of the MI355X (gfx950) bit-serial low-bit GEMM / convolution library.
+ *
+ * The operations are those of DeepliteRT (arXiv 2207.08820): operands quantized to 1-4 bits
+ * (Section IV) are split into bitplanes (Section V), every dot product is
+ *      sum_i sum_j  s_w(i) s_a(j) 2^(i+j) popcount(W[i] & A[j])          (Section V, multi-bit equation)
+ * accumulated in int32, and the result is dequantized by a scale (Section IV, t_hat = t_bar * s).
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer owned by the caller, except where a parameter says "host".
+ *   - The library allocates nothing, keeps no state between calls and never synchronises:
+ *     each call validates its arguments on the host, enqueues its kernels on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and returns.
+ *   - Buffers must stay alive until the stream has passed the call.  Output buffers are fully
+ *     overwritten; inputs are never written.
+ *   - Argument errors return a specific DLRT_ERR_* code and enqueue nothing.  A failed launch
+ *     returns DLRT_ERR_LAUNCH.
+ *   - Packed operand format ("bitplane tensor"): uint32 words, [rows][bits][Kw], Kw = ceil(K/32).
+ *     Element k of a row occupies bit (k % 32) of word (k / 32) of each plane; plane p holds bit p
+ *     of the element's pattern (plane 0 = least significant).  Bits beyond K are zero.
+ *     Packed buffers must be 16-byte aligned (DLRT_ERR_ALIGN otherwise).
+ *   - Overflow is a precondition, not checked: K_total * (2^abits - 1) * 2^(wbits-1) < 2^31.
+ */
+#ifndef DLRT_H
+#define DLRT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DLRT_OK = 0,
+    DLRT_ERR_NULL = 1,     /* a required pointer is NULL                               */
+    DLRT_ERR_BITS = 2,     /* a bit width outside 1..4                                 */
+    DLRT_ERR_SHAPE = 3,    /* a non-positive or inconsistent size                      */
+    DLRT_ERR_ENCODING = 4, /* unknown encoding, or one not allowed for that operand    */
+    DLRT_ERR_ALIGN = 5,    /* a packed buffer is not 16-byte aligned                   */
+    DLRT_ERR_LAUNCH = 6    /* the HIP runtime refused the launch                       */
+} dlrt_status;
+
+/* How a b-bit pattern maps to a value.  Section V states the unipolar {0,1} planes; the signed
+ * ranges are the quantizer's of Section IV. */
+typedef enum {
+    DLRT_UNSIGNED = 0, /* value = sum_p 2^p bit_p                      in [0, 2^b - 1]            */
+    DLRT_TWOS = 1,     /* as above but plane b-1 weighs -2^(b-1)       in [-2^(b-1), 2^(b-1) - 1] */
+    DLRT_BIPOLAR = 2   /* b must be 1: bit 1 -> +1, bit 0 -> -1 (weights only)                    */
+} dlrt_encoding;
+
+typedef enum {
+    DLRT_SRC_U8 = 0, /* uint8 holding the value (unsigned) or its low bits                  */
+    DLRT_SRC_I8 = 1, /* int8 holding the value                                              */
+    DLRT_SRC_F32 = 2 /* float32, quantized on the fly: q = round(clip(x / s, lo, hi))       */
+} dlrt_src;
+
+/* Number of uint32 words of a packed [rows][bits][ceil(K/32)] tensor; 0 if an argument is invalid. */
+size_t dlrt_packed_words(int64_t rows, int64_t K, int bits);
+
+/* Static, NUL-terminated description of a status code (host memory, never freed). */
+const char *dlrt_status_string(dlrt_status status);
+
+/*
+ * Bitplane split (Section V) with the optional forward quantizer of Section IV in front.
+ *   src    rows x K elements of type `st`, element (r, k) at src[r * ld + k]; ld >= K.
+ *   scale  NULL, or for DLRT_SRC_F32 (required there): one float (scale_per_row == 0) or `rows`
+ *          floats.  q = rint(min(max(x / s, lo), hi)), ties to even, [lo, hi] the range of `enc`.
+ *          Integer sources are taken as already quantized: the low `bits` bits of the two's
+ *          complement pattern are packed (bipolar: bit = value > 0); `scale` is ignored.
+ *   dst    [rows][bits][ceil(K/32)] words, fully written.
+ * For NHWC activations call with rows = N*H*W, K = C.
+ */
+dlrt_status dlrt_pack_bitplanes(const void *src, dlrt_src st, int64_t rows, int64_t K, int64_t ld,
+                                int bits, dlrt_encoding enc, const float *scale, int scale_per_row,
+                                uint32_t *dst, void *stream);
+
+/*
+ * Convolution weights, OHWI [Co][KH][KW][Ci] -> [Co][bits][KH*KW*Cw] words, Cw = ceil(Ci/32): every
+ * (kh, kw) tap is padded to whole words on its own, so that tap t of plane p starts at word
+ * (p*KH*KW + t) * Cw of its output channel and lines up with one pixel's packed NHWC words.
+ * scale: as above but one float for the whole tensor (F32 source only).
+ */
+dlrt_status dlrt_pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci,
+                                   int bits, dlrt_encoding enc, const float *scale, uint32_t *dst,
+                                   void *stream);
+
+/*
+ * Bit-serial GEMM (Section V, multi-bit equation applied to every (m, n) pair):
+ *   C[m][n] = sum_k a[m][k] * w[n][k]      int32, row-major, leading dimension N.
+ *   A  packed [M][abits][Kw], W packed [N][wbits][Kw]; both reduce along their packed axis.
+ *   enc_a: UNSIGNED or TWOS.  enc_w: UNSIGNED, TWOS, or BIPOLAR (then wbits must be 1 and
+ *   C = sum_j s_a(j) 2^j (2 popcount(A[j] & W) - popcount(A[j]))).
+ */
+dlrt_status dlrt_bitserial_gemm(const uint32_t *A, const uint32_t *W, int32_t *C,
+                                int64_t M, int64_t N, int64_t K, int abits, int wbits,
+                                dlrt_encoding enc_a, dlrt_encoding enc_w, void *stream);
+
+/*
+ * Bit-serial convolution (Section V: the convolution's dot products computed bit-serially), as an
+ * implicit im2col over packed NHWC activations; zero padding (an out-of-image tap contributes 0,
+ * also for bipolar weights).
+ *   X   packed [N][H][W][abits][Cw]   (dlrt_pack_bitplanes with rows = N*H*W, K = Ci)
+ *   Wp  packed [Co][wbits][KH*KW*Cw]  (dlrt_pack_conv_weights)
+ *   Y   int32 NHWC [N][Ho][Wo][Co],  Ho = (H + 2*pad_h - KH) / stride_h + 1, same for Wo.
+ */
+dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t *Y,
+                                  int N, int H, int W, int Ci, int Co, int KH, int KW,
+                                  int stride_h, int stride_w, int pad_h, int pad_w,
+                                  int abits, int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w,
+                                  void *stream);
+
+/*
+ * Dequantize / requantize epilogue (Section IV: t_hat = t_bar * s, then the quantizer again for
+ * the next layer), per output channel:
+ *   y = fmaf((float)acc[r][c], scale[c], bias ? bias[c] : 0.0f)          -> out_f32 (may be NULL)
+ *   q = (uint8) min(max(rint(y), 0), 2^qbits - 1), ties to even          -> out_q   (may be NULL)
+ * acc is rows x C with the channel innermost; out_f32 and out_q must not both be NULL; qbits in
+ * 1..8 is read only when out_q is given.
+ */
+dlrt_status dlrt_epilogue_f32(const int32_t *acc, const float *scale, const float *bias,
+                              int64_t rows, int C, float *out_f32, uint8_t *out_q, int qbits,
+                              void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLRT_H */

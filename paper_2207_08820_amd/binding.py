@@ -1,0 +1,152 @@
+"""ctypes binding over the C ABI of ``include/dlrt.h``: argument marshalling only.
+
+Every function has the name of the C entry point it calls and takes ``torch`` CUDA tensors
+(used here purely as owners of device memory) plus the scalar arguments of the C call; the
+kernels are enqueued on torch's current stream.  Nothing is computed in Python, and there is
+no fallback: if the HIP library has not been built, ``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdlrt_hip.so")
+
+OK = 0
+UNSIGNED, TWOS, BIPOLAR = 0, 1, 2
+SRC_U8, SRC_I8, SRC_F32 = 0, 1, 2
+
+_lib = None
+
+
+class DlrtError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = _lib.dlrt_status_string(code).decode() if _lib is not None else "?"
+        super().__init__(f"{where}: {msg} (status {code})")
+
+
+def load():
+    """Load libdlrt_hip.so (after torch, so that both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2207_08820_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.dlrt_packed_words.restype = sz
+    lib.dlrt_packed_words.argtypes = [i64, i64, i32]
+    lib.dlrt_status_string.restype = ctypes.c_char_p
+    lib.dlrt_status_string.argtypes = [i32]
+    lib.dlrt_pack_bitplanes.restype = i32
+    lib.dlrt_pack_bitplanes.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, i32, vp, vp]
+    lib.dlrt_pack_conv_weights.restype = i32
+    lib.dlrt_pack_conv_weights.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.dlrt_bitserial_gemm.restype = i32
+    lib.dlrt_bitserial_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
+    lib.dlrt_bitserial_conv2d.restype = i32
+    lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
+    lib.dlrt_epilogue_f32.restype = i32
+    lib.dlrt_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp]
+    _lib = lib
+    return lib
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    return t.data_ptr()
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise DlrtError(code, where)
+
+
+_SRC_OF = {torch.uint8: SRC_U8, torch.int8: SRC_I8, torch.float32: SRC_F32}
+
+
+def dlrt_packed_words(rows: int, K: int, bits: int) -> int:
+    return int(load().dlrt_packed_words(rows, K, bits))
+
+
+def dlrt_pack_bitplanes(src: torch.Tensor, bits: int, enc: int, scale: torch.Tensor | None = None,
+                        out: torch.Tensor | None = None, K: int | None = None) -> torch.Tensor:
+    """src [..., ld] (uint8 / int8 / float32) -> int32 words [rows, bits, ceil(K/32)], rows = prod of the rest.
+    K defaults to the row length ld; a smaller K packs the first K elements of every row."""
+    lib = load()
+    ld = src.shape[-1]
+    K = ld if K is None else K
+    rows = src.numel() // ld
+    Kw = (K + 31) // 32
+    if out is None:
+        out = torch.empty((rows, bits, Kw), dtype=torch.int32, device=src.device)
+    per_row = int(scale is not None and scale.numel() != 1)
+    _check(lib.dlrt_pack_bitplanes(_ptr(src), _SRC_OF[src.dtype], rows, K, ld, bits, enc, _ptr(scale), per_row,
+                                   _ptr(out), _stream()), "dlrt_pack_bitplanes")
+    return out
+
+
+def dlrt_pack_conv_weights(w_ohwi: torch.Tensor, bits: int, enc: int, scale: torch.Tensor | None = None,
+                           out: torch.Tensor | None = None) -> torch.Tensor:
+    """w [Co, KH, KW, Ci] -> int32 words [Co, bits, KH*KW*ceil(Ci/32)]."""
+    lib = load()
+    Co, KH, KW, Ci = w_ohwi.shape
+    if out is None:
+        out = torch.empty((Co, bits, KH * KW * ((Ci + 31) // 32)), dtype=torch.int32, device=w_ohwi.device)
+    _check(lib.dlrt_pack_conv_weights(_ptr(w_ohwi), _SRC_OF[w_ohwi.dtype], Co, KH, KW, Ci, bits, enc, _ptr(scale),
+                                      _ptr(out), _stream()), "dlrt_pack_conv_weights")
+    return out
+
+
+def dlrt_bitserial_gemm(A: torch.Tensor, W: torch.Tensor, M: int, N: int, K: int, abits: int, wbits: int,
+                        enc_a: int, enc_w: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Packed A [M, abits, Kw] and W [N, wbits, Kw] -> int32 C [M, N]."""
+    lib = load()
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _check(lib.dlrt_bitserial_gemm(_ptr(A), _ptr(W), _ptr(out), M, N, K, abits, wbits, enc_a, enc_w, _stream()),
+           "dlrt_bitserial_gemm")
+    return out
+
+
+def dlrt_bitserial_conv2d(X: torch.Tensor, Wp: torch.Tensor, N: int, H: int, W: int, Ci: int, Co: int, KH: int,
+                          KW: int, stride, pad, abits: int, wbits: int, enc_a: int, enc_w: int,
+                          out: torch.Tensor | None = None) -> torch.Tensor:
+    """Packed X [N, H, W, abits, Cw] and Wp [Co, wbits, KH*KW*Cw] -> int32 Y [N, Ho, Wo, Co]."""
+    lib = load()
+    sh, sw = stride
+    ph, pw = pad
+    Ho = (H + 2 * ph - KH) // sh + 1
+    Wo = (W + 2 * pw - KW) // sw + 1
+    if out is None:
+        out = torch.empty((N, max(Ho, 0), max(Wo, 0), Co), dtype=torch.int32, device=X.device)
+    _check(lib.dlrt_bitserial_conv2d(_ptr(X), _ptr(Wp), _ptr(out), N, H, W, Ci, Co, KH, KW, sh, sw, ph, pw,
+                                     abits, wbits, enc_a, enc_w, _stream()), "dlrt_bitserial_conv2d")
+    return out
+
+
+def dlrt_epilogue_f32(acc: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor | None = None,
+                      want_f32: bool = True, qbits: int | None = None, out_f32: torch.Tensor | None = None,
+                      out_q: torch.Tensor | None = None):
+    """acc [..., C] int32 -> (float32 y or None, uint8 q or None)."""
+    lib = load()
+    C = acc.shape[-1]
+    rows = acc.numel() // C
+    if want_f32 and out_f32 is None:
+        out_f32 = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    if qbits is not None and out_q is None:
+        out_q = torch.empty(acc.shape, dtype=torch.uint8, device=acc.device)
+    _check(lib.dlrt_epilogue_f32(_ptr(acc), _ptr(scale), _ptr(bias), rows, C, _ptr(out_f32), _ptr(out_q),
+                                 int(qbits or 0), _stream()), "dlrt_epilogue_f32")
+    return out_f32, out_q

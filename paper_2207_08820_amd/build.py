@@ -1,0 +1,48 @@
+"""Build the HIP library in-tree: hipcc cross-compiles for gfx950, no GPU needed.
+
+    python -m paper_2207_08820_amd.build
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libdlrt_hip.so")
+# (source, object name, extra defines); contract.hip is built once per activation bit width
+UNITS = [("api.hip", "api.o", []), ("pack.hip", "pack.o", []), ("epilogue.hip", "epilogue.o", []),
+         ("contract_dispatch.hip", "contract_dispatch.o", [])] + \
+        [("contract.hip", f"contract_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+# packed-fp32 instruction selection is switched off for every device compile
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+
+def _compile(unit, extra) -> str:
+    name, objname, defines = unit
+    obj = os.path.join(OBJ, objname)
+    subprocess.run([HIPCC, *FLAGS, *defines, *extra, "-c", os.path.join(CSRC, name), "-o", obj], check=True,
+                   stderr=subprocess.PIPE if not os.environ.get("DLRT_BUILD_VERBOSE") else None)
+    return obj
+
+
+def build_library(extra_flags=()) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=min(len(UNITS), os.cpu_count() or 4, 16)) as pool:
+        objs = list(pool.map(lambda u: _compile(u, list(extra_flags)), UNITS))
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs,
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(sys.argv[1:]))

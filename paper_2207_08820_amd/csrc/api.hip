@@ -1,0 +1,128 @@
+// The C ABI of include/dlrt.h: argument validation on the host, then a launch.  Nothing here
+// allocates, synchronises or keeps state.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dlrt.h"
+#include "launch.h"
+
+namespace {
+
+bool bits_ok(int b) { return b >= 1 && b <= 4; }
+bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+dlrt_status check_encodings(int abits, int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w)
+{
+    if (!bits_ok(abits) || !bits_ok(wbits)) return DLRT_ERR_BITS;
+    if (enc_a != DLRT_UNSIGNED && enc_a != DLRT_TWOS) return DLRT_ERR_ENCODING;
+    if (enc_w != DLRT_UNSIGNED && enc_w != DLRT_TWOS && enc_w != DLRT_BIPOLAR) return DLRT_ERR_ENCODING;
+    if (enc_w == DLRT_BIPOLAR && wbits != 1) return DLRT_ERR_ENCODING;
+    return DLRT_OK;
+}
+
+dlrt_status check_pack(const void *src, dlrt_src st, int bits, dlrt_encoding enc, const float *scale, const void *dst)
+{
+    if (!src || !dst) return DLRT_ERR_NULL;
+    if (!bits_ok(bits)) return DLRT_ERR_BITS;
+    if (st != DLRT_SRC_U8 && st != DLRT_SRC_I8 && st != DLRT_SRC_F32) return DLRT_ERR_SHAPE;
+    if (enc != DLRT_UNSIGNED && enc != DLRT_TWOS && enc != DLRT_BIPOLAR) return DLRT_ERR_ENCODING;
+    if (enc == DLRT_BIPOLAR && bits != 1) return DLRT_ERR_ENCODING;
+    if (st == DLRT_SRC_F32 && !scale) return DLRT_ERR_NULL;
+    if (!aligned16(dst)) return DLRT_ERR_ALIGN;
+    return DLRT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dlrt_packed_words(int64_t rows, int64_t K, int bits)
+{
+    if (rows <= 0 || K <= 0 || !bits_ok(bits)) return 0;
+    return (size_t)rows * (size_t)bits * (size_t)((K + 31) / 32);
+}
+
+const char *dlrt_status_string(dlrt_status status)
+{
+    switch (status) {
+    case DLRT_OK: return "ok";
+    case DLRT_ERR_NULL: return "a required pointer is NULL";
+    case DLRT_ERR_BITS: return "bit width outside 1..4";
+    case DLRT_ERR_SHAPE: return "non-positive or inconsistent size";
+    case DLRT_ERR_ENCODING: return "encoding unknown or not allowed for this operand";
+    case DLRT_ERR_ALIGN: return "packed buffer is not 16-byte aligned";
+    case DLRT_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+dlrt_status dlrt_pack_bitplanes(const void *src, dlrt_src st, int64_t rows, int64_t K, int64_t ld, int bits,
+                                dlrt_encoding enc, const float *scale, int scale_per_row, uint32_t *dst, void *stream)
+{
+    if (dlrt_status s = check_pack(src, st, bits, enc, scale, dst)) return s;
+    if (rows <= 0 || K <= 0 || ld < K) return DLRT_ERR_SHAPE;
+    const int64_t Kw = (K + 31) / 32;
+    if (rows > 0x7fffffffLL * 32 / Kw) return DLRT_ERR_SHAPE;
+    dlrt::PackArgs p{};
+    p.src = src; p.src_type = st; p.rows = rows; p.K = K; p.ld = ld; p.bits = bits; p.enc = enc;
+    p.scale = scale; p.scale_per_row = scale_per_row != 0; p.dst = dst;
+    p.taps = 1; p.outer_stride = bits * Kw; p.plane_stride = Kw; p.tap_stride = 0;
+    return dlrt::launch_pack(p, as_stream(stream));
+}
+
+dlrt_status dlrt_pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci, int bits,
+                                   dlrt_encoding enc, const float *scale, uint32_t *dst, void *stream)
+{
+    if (dlrt_status s = check_pack(w_ohwi, st, bits, enc, scale, dst)) return s;
+    if (Co <= 0 || KH <= 0 || KW <= 0 || Ci <= 0) return DLRT_ERR_SHAPE;
+    const int64_t Cw = (Ci + 31) / 32, taps = (int64_t)KH * KW;
+    if ((int64_t)Co * taps > 0x7fffffffLL * 32 / Cw) return DLRT_ERR_SHAPE;
+    dlrt::PackArgs p{};
+    p.src = w_ohwi; p.src_type = st; p.rows = (int64_t)Co * taps; p.K = Ci; p.ld = Ci; p.bits = bits; p.enc = enc;
+    p.scale = scale; p.scale_per_row = 0; p.dst = dst;
+    p.taps = taps; p.outer_stride = bits * taps * Cw; p.plane_stride = taps * Cw; p.tap_stride = Cw;
+    return dlrt::launch_pack(p, as_stream(stream));
+}
+
+dlrt_status dlrt_bitserial_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int64_t M, int64_t N, int64_t K,
+                                int abits, int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w, void *stream)
+{
+    if (!A || !W || !C) return DLRT_ERR_NULL;
+    if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
+    if (M <= 0 || N <= 0 || K <= 0) return DLRT_ERR_SHAPE;
+    const int64_t Kw = (K + 31) / 32;
+    if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(A) || !aligned16(W)) return DLRT_ERR_ALIGN;
+    return dlrt::launch_gemm(A, W, C, (int)M, (int)N, (int)Kw, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS,
+                             enc_w == DLRT_BIPOLAR, as_stream(stream));
+}
+
+dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t *Y, int N, int H, int W, int Ci,
+                                  int Co, int KH, int KW, int stride_h, int stride_w, int pad_h, int pad_w, int abits,
+                                  int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w, void *stream)
+{
+    if (!X || !Wp || !Y) return DLRT_ERR_NULL;
+    if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
+    if (N <= 0 || H <= 0 || W <= 0 || Ci <= 0 || Co <= 0 || KH <= 0 || KW <= 0) return DLRT_ERR_SHAPE;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return DLRT_ERR_SHAPE;
+    if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return DLRT_ERR_SHAPE;
+    const int Ho = (H + 2 * pad_h - KH) / stride_h + 1, Wo = (W + 2 * pad_w - KW) / stride_w + 1;
+    const int64_t Cw = (Ci + 31) / 32;
+    if ((int64_t)N * Ho * Wo > 0x7fffffff || (int64_t)KH * KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if ((int64_t)H * W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Wp)) return DLRT_ERR_ALIGN;
+    return dlrt::launch_conv(X, Wp, Y, N, H, W, (int)Cw, Co, KH, KW, Ho, Wo, stride_h, stride_w, pad_h, pad_w, abits,
+                             wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, as_stream(stream));
+}
+
+dlrt_status dlrt_epilogue_f32(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
+                              float *out_f32, uint8_t *out_q, int qbits, void *stream)
+{
+    if (!acc || !scale || (!out_f32 && !out_q)) return DLRT_ERR_NULL;
+    if (rows <= 0 || C <= 0) return DLRT_ERR_SHAPE;
+    if (out_q && (qbits < 1 || qbits > 8)) return DLRT_ERR_BITS;
+    return dlrt::launch_epilogue(acc, scale, bias, rows, C, out_f32, out_q, out_q ? qbits : 1, as_stream(stream));
+}
+
+}  // extern "C"

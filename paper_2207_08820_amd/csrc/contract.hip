@@ -1,0 +1,419 @@
+// Bit-serial contraction kernels for gfx950: GEMM and implicit-im2col convolution.
+//
+// Section V of arXiv 2207.08820: with operands split into bitplanes, a dot product is
+//     sum_i sum_j popcount(W[i] & A[j]) << (i + j).
+// Here every (j, i) plane pair of every output owns an int32 accumulator that is fed by
+// v_and_b32 + v_bcnt_u32_b32 (the popcount instruction adds into its third operand, so one
+// AND and one BCNT per 32 reduction elements per plane pair is all the inner loop issues).
+// The shifts and the signs of two's-complement MSB planes are applied once per output after
+// the reduction.  Bipolar 1-bit weights use 2*popcount(A[j] & W) - popcount(A[j]).
+//
+// Tiling (wave64, 256 threads = 16 x 16 lanes): a lane owns TM x TN outputs, rows ty + 16*r and
+// columns tx + 16*s, so a block owns (16*TM) x (16*TN) outputs.  TM*abits and TN*wbits are kept
+// near 8, which keeps the accumulator count near 64 per lane and the LDS traffic per VALU
+// instruction constant over bit widths.  Packed A / W tiles are staged through LDS in chunks of
+// 16 words (512 reduction elements), double buffered, laid out [k4][plane][row] in 16-byte
+// units so that the inner loop reads whole uint4 with compile-time offsets and neighbouring
+// lanes read neighbouring 16-byte units.
+//
+// This file is compiled once per activation bit width (-DDLRT_ABITS=1..4) so that the
+// instantiations build in parallel; contract_dispatch.hip picks the translation unit.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+#include "dlrt.h"
+#include "launch.h"
+
+#ifndef DLRT_ABITS
+#error "compile with -DDLRT_ABITS=1..4"
+#endif
+
+namespace {
+
+using dlrt::ContractArgs;
+
+constexpr int kThreads = 256;
+constexpr int kK4 = 4;   // 16-byte groups per chunk
+constexpr int kKC = 16;  // words per chunk
+
+// One 16-byte staging slot of a tile: which (row, plane, k4) of the chunk a thread moves.
+template <int PLANES, int ROWS>
+struct SlotMap {
+    static constexpr int kSlots = kK4 * PLANES * ROWS;
+    static constexpr int kPerThread = (kSlots + kThreads - 1) / kThreads;
+    __device__ static void decode(int s, int &row, int &plane, int &k4)
+    {
+        // 8 consecutive lanes take 8 consecutive rows (one conflict-free 128-byte LDS write),
+        // the next lane bits walk along K (one 64-byte global segment per row and plane).
+        const int rowlo = s & 7;
+        k4 = (s >> 3) & 3;
+        const int rest = s >> 5;
+        plane = rest % PLANES;
+        row = (rest / PLANES) * 8 + rowlo;
+    }
+    __device__ static int lds_index(int row, int plane, int k4) { return (k4 * PLANES + plane) * ROWS + row; }
+};
+
+// Unguarded load of the 4 words at p with the widest access the operand's alignment allows.
+template <int VEC>
+__device__ __forceinline__ uint4 load4(const uint32_t *p)
+{
+    if (VEC == 4) return *reinterpret_cast<const uint4 *>(p);
+    if (VEC == 2) {
+        const uint2 lo = *reinterpret_cast<const uint2 *>(p), hi = *reinterpret_cast<const uint2 *>(p + 2);
+        return make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+    return make_uint4(p[0], p[1], p[2], p[3]);
+}
+
+// p points at word k0 of a plane of kend words; words at or beyond kend read as zero.  Branch-free:
+// out-of-range words are fetched from the plane's last word and then discarded.
+__device__ __forceinline__ uint4 load4_tail(const uint32_t *p, int k0, int kend)
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int k = k0 + e;
+        const uint32_t t = p[(k < kend ? k : kend - 1) - k0];
+        w[e] = k < kend ? t : 0u;
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// acc[n] += popcount(a & w[n]) for a group of N outputs that share the activation word `a`:
+// exactly one v_and_b32 and one accumulating v_bcnt_u32_b32 per output, the ANDs running two
+// instructions ahead of the BCNTs that consume them.  Written as asm because the optimiser
+// otherwise re-associates the accumulation chains into trees of partial sums (extra adds and
+// registers), and as one block per group because every separate asm statement costs a wait state.
+template <int N>
+__device__ __forceinline__ void and_popc_group(int (&acc)[N], uint32_t a, const uint32_t (&w)[N]);
+
+template <>
+__device__ __forceinline__ void and_popc_group<6>(int (&acc)[6], uint32_t a, const uint32_t (&w)[6])
+{
+    uint32_t t0, t1;
+    asm("v_and_b32 %6, %8, %9\n\t"
+        "v_and_b32 %7, %8, %10\n\t"
+        "v_bcnt_u32_b32 %0, %6, %0\n\t"
+        "v_and_b32 %6, %8, %11\n\t"
+        "v_bcnt_u32_b32 %1, %7, %1\n\t"
+        "v_and_b32 %7, %8, %12\n\t"
+        "v_bcnt_u32_b32 %2, %6, %2\n\t"
+        "v_and_b32 %6, %8, %13\n\t"
+        "v_bcnt_u32_b32 %3, %7, %3\n\t"
+        "v_and_b32 %7, %8, %14\n\t"
+        "v_bcnt_u32_b32 %4, %6, %4\n\t"
+        "v_bcnt_u32_b32 %5, %7, %5"
+        : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]), "=&v"(t0), "=&v"(t1)
+        : "v"(a), "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]));
+}
+
+template <>
+__device__ __forceinline__ void and_popc_group<8>(int (&acc)[8], uint32_t a, const uint32_t (&w)[8])
+{
+    uint32_t t0, t1;
+    asm("v_and_b32 %8, %10, %11\n\t"
+        "v_and_b32 %9, %10, %12\n\t"
+        "v_bcnt_u32_b32 %0, %8, %0\n\t"
+        "v_and_b32 %8, %10, %13\n\t"
+        "v_bcnt_u32_b32 %1, %9, %1\n\t"
+        "v_and_b32 %9, %10, %14\n\t"
+        "v_bcnt_u32_b32 %2, %8, %2\n\t"
+        "v_and_b32 %8, %10, %15\n\t"
+        "v_bcnt_u32_b32 %3, %9, %3\n\t"
+        "v_and_b32 %9, %10, %16\n\t"
+        "v_bcnt_u32_b32 %4, %8, %4\n\t"
+        "v_and_b32 %8, %10, %17\n\t"
+        "v_bcnt_u32_b32 %5, %9, %5\n\t"
+        "v_and_b32 %9, %10, %18\n\t"
+        "v_bcnt_u32_b32 %6, %8, %6\n\t"
+        "v_bcnt_u32_b32 %7, %9, %7"
+        : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]), "+v"(acc[5]), "+v"(acc[6]),
+          "+v"(acc[7]), "=&v"(t0), "=&v"(t1)
+        : "v"(a), "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]));
+}
+
+__device__ __forceinline__ void popc_acc(int &acc, uint32_t a)
+{
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(a));
+}
+
+// n / d for 0 <= n, n * d < 2^32, with magic = ceil(2^32 / d) computed on the host (0 stands for d = 1).
+__device__ __forceinline__ int fast_div(int n, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)n, magic) : n; }
+
+// VEC: widest aligned access, in words, that both operands allow (4, 2 or 1).  A template
+// parameter rather than a run-time branch: the optimiser merges run-time variants of the same
+// load into the narrowest one.
+template <int AB, int WB, int TM, int TN, int VEC, bool BIPOLAR, bool CONV>
+__global__ __launch_bounds__(kThreads, 2) void contract_kernel(const ContractArgs g)
+{
+    constexpr int BM = 16 * TM, BN = 16 * TN;
+    using MapA = SlotMap<AB, BM>;
+    using MapW = SlotMap<WB, BN>;
+    constexpr int kTileA = kK4 * AB * BM, kTileW = kK4 * WB * BN;  // uint4 units per buffer
+
+    __shared__ uint4 ldsA[2 * kTileA];
+    __shared__ uint4 ldsW[2 * kTileW];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int tilesN = (g.N + BN - 1) / BN;
+    const int tileM = blockIdx.x / tilesN, tileN = blockIdx.x - tileM * tilesN;
+    const int m0 = tileM * BM, n0 = tileN * BN;
+
+    // ---- staging slots, resolved once.  Rows beyond the matrix are clamped to its last row:
+    // they are loaded like any other and their outputs are never stored. ----
+    const uint32_t *srcA[MapA::kPerThread];
+    int dstA[MapA::kPerThread], k4A[MapA::kPerThread];
+    int ih0[MapA::kPerThread], iw0[MapA::kPerThread];
+#pragma unroll
+    for (int t = 0; t < MapA::kPerThread; ++t) {
+        const int s = tid + t * kThreads;
+        int row, plane, k4;
+        MapA::decode(s < MapA::kSlots ? s : 0, row, plane, k4);
+        dstA[t] = s < MapA::kSlots ? MapA::lds_index(row, plane, k4) : -1;
+        k4A[t] = k4;
+        const int m = min(m0 + row, g.M - 1);
+        ih0[t] = 0;
+        iw0[t] = 0;
+        if (CONV) {
+            const int hw = g.Ho * g.Wo;
+            const int n = m / hw, rem = m - n * hw;
+            const int oh = rem / g.Wo, ow = rem - oh * g.Wo;
+            ih0[t] = oh * g.sh - g.ph;
+            iw0[t] = ow * g.sw - g.pw;
+            // plane `plane` of pixel (n, 0, 0); pixel and channel-word offsets are added per load
+            srcA[t] = g.A + (size_t)n * g.H * g.Wd * AB * g.Cw + plane * g.Cw;
+        } else {
+            srcA[t] = g.A + ((size_t)m * AB + plane) * g.Kw + k4 * 4;
+        }
+    }
+    const uint32_t *srcW[MapW::kPerThread];
+    int dstW[MapW::kPerThread], k4W[MapW::kPerThread];
+#pragma unroll
+    for (int t = 0; t < MapW::kPerThread; ++t) {
+        const int s = tid + t * kThreads;
+        int row, plane, k4;
+        MapW::decode(s < MapW::kSlots ? s : 0, row, plane, k4);
+        dstW[t] = s < MapW::kSlots ? MapW::lds_index(row, plane, k4) : -1;
+        k4W[t] = k4;
+        srcW[t] = g.W + ((size_t)min(n0 + row, g.N - 1) * WB + plane) * g.Kw + k4 * 4;
+    }
+
+    uint4 stageA[MapA::kPerThread], stageW[MapW::kPerThread];
+
+    // implicit im2col: reduction word kwd = tap * Cw + c, tap = kh * KW + kw.  Loads VEC words of
+    // one tap; a tap outside the image, or a word beyond the reduction, reads as zero.  Branch-free:
+    // the address is clamped into the image and the result discarded.
+    auto tap_load = [&](int t, int kwd, uint32_t *out) {
+        bool ok = kwd < g.Kw;
+        const int kc = ok ? kwd : g.Kw - 1;
+        const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
+        const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
+        const int ih = ih0[t] + kh, iw = iw0[t] + kw;
+        ok = ok && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
+        const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
+        const uint32_t *p = srcA[t] + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
+        if (VEC == 4) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(p);
+            out[0] = ok ? q.x : 0u; out[1] = ok ? q.y : 0u; out[2] = ok ? q.z : 0u; out[3] = ok ? q.w : 0u;
+        } else if (VEC == 2) {
+            const uint2 q = *reinterpret_cast<const uint2 *>(p);
+            out[0] = ok ? q.x : 0u; out[1] = ok ? q.y : 0u;
+        } else {
+            const uint32_t q = *p;
+            out[0] = ok ? q : 0u;
+        }
+    };
+
+    const int nchunks = (g.Kw + kKC - 1) / kKC, nfull = g.Kw / kKC;
+    auto fetch = [&](int chunk) {
+        const int kbase = chunk * kKC;
+        if (CONV) {
+#pragma unroll
+            for (int t = 0; t < MapA::kPerThread; ++t) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; e += VEC) tap_load(t, kbase + k4A[t] * 4 + e, w + e);
+                stageA[t] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        if (chunk < nfull) {  // chunk wholly inside the reduction: no guards at all
+            if (!CONV) {
+#pragma unroll
+                for (int t = 0; t < MapA::kPerThread; ++t) stageA[t] = load4<VEC>(srcA[t] + kbase);
+            }
+#pragma unroll
+            for (int t = 0; t < MapW::kPerThread; ++t) stageW[t] = load4<VEC>(srcW[t] + kbase);
+        } else {
+            if (!CONV) {
+#pragma unroll
+                for (int t = 0; t < MapA::kPerThread; ++t)
+                    stageA[t] = load4_tail(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
+            }
+#pragma unroll
+            for (int t = 0; t < MapW::kPerThread; ++t)
+                stageW[t] = load4_tail(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int t = 0; t < MapA::kPerThread; ++t)
+            if (dstA[t] >= 0) ldsA[buf * kTileA + dstA[t]] = stageA[t];
+#pragma unroll
+        for (int t = 0; t < MapW::kPerThread; ++t)
+            if (dstW[t] >= 0) ldsW[buf * kTileW + dstW[t]] = stageW[t];
+    };
+
+    // acc[r][j][s * WB + i]: row r of the lane tile, activation plane j, column s, weight plane i
+    constexpr int NG = TN * WB;
+    int acc[TM][AB][NG];
+    int rowpc[TM][AB];
+#pragma unroll
+    for (int r = 0; r < TM; ++r)
+#pragma unroll
+        for (int j = 0; j < AB; ++j) {
+            rowpc[r][j] = 0;
+#pragma unroll
+            for (int n = 0; n < NG; ++n) acc[r][j][n] = 0;
+        }
+
+    fetch(0);
+    commit(0);
+    __syncthreads();
+
+    for (int chunk = 0; chunk < nchunks; ++chunk) {
+        const int buf = chunk & 1;
+        if (chunk + 1 < nchunks) fetch(chunk + 1);
+
+        const uint4 *la = ldsA + buf * kTileA + ty;
+        const uint4 *lw = ldsW + buf * kTileW + tx;
+        // Register double buffer over the four 16-byte steps of a chunk: the LDS reads of step
+        // k4 + 1 are issued before the AND/BCNT block of step k4 and consumed after it.  The
+        // scheduling barrier keeps the compiler from hoisting every read of the chunk to the
+        // top, which would need four times the operand registers.
+        uint4 av[2][TM][AB], wv[2][TN][WB];
+        auto lds_load = [&](int b, int k4) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int j = 0; j < AB; ++j) av[b][r][j] = la[(k4 * AB + j) * BM + 16 * r];
+#pragma unroll
+            for (int s = 0; s < TN; ++s)
+#pragma unroll
+                for (int i = 0; i < WB; ++i) wv[b][s][i] = lw[(k4 * WB + i) * BN + 16 * s];
+        };
+        auto mac = [&](int b) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t w[NG];
+#pragma unroll
+                for (int s = 0; s < TN; ++s)
+#pragma unroll
+                    for (int i = 0; i < WB; ++i) {
+                        const uint4 &q = wv[b][s][i];
+                        w[s * WB + i] = e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
+                    }
+#pragma unroll
+                for (int r = 0; r < TM; ++r)
+#pragma unroll
+                    for (int j = 0; j < AB; ++j) {
+                        const uint4 &q = av[b][r][j];
+                        const uint32_t a = e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
+                        if (BIPOLAR) popc_acc(rowpc[r][j], a);
+                        and_popc_group<NG>(acc[r][j], a, w);
+                    }
+            }
+        };
+        lds_load(0, 0);
+#pragma unroll
+        for (int k4 = 0; k4 < kK4; ++k4) {
+            if (k4 + 1 < kK4) lds_load((k4 + 1) & 1, k4 + 1);
+            mac(k4 & 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        if (chunk + 1 < nchunks) commit(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- combine the plane pairs: signs and shifts of Section V's double sum ----
+#pragma unroll
+    for (int r = 0; r < TM; ++r) {
+        const int m = m0 + ty + 16 * r;
+        if (m >= g.M) continue;
+#pragma unroll
+        for (int s = 0; s < TN; ++s) {
+            const int n = n0 + tx + 16 * s;
+            if (n >= g.N) continue;
+            int total = 0;
+#pragma unroll
+            for (int j = 0; j < AB; ++j) {
+                int part = 0;
+                if (BIPOLAR) {
+                    part = 2 * acc[r][j][s] - rowpc[r][j];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < WB; ++i) {
+                        const int term = acc[r][j][s * WB + i] << i;
+                        part += (g.w_msb_neg && i == WB - 1) ? -term : term;
+                    }
+                }
+                part <<= j;
+                total += (g.a_msb_neg && j == AB - 1) ? -part : part;
+            }
+            g.C[(size_t)m * g.N + n] = total;
+        }
+    }
+}
+
+template <int B> struct LaneTile { static constexpr int value = B == 1 ? 8 : B == 2 ? 4 : 2; };
+
+template <int WB, int VEC, bool BIPOLAR, bool CONV>
+dlrt_status launch(const ContractArgs &g, hipStream_t stream)
+{
+    constexpr int AB = DLRT_ABITS;
+    constexpr int TM = LaneTile<AB>::value, TN = LaneTile<WB>::value;
+    const int64_t tilesM = (g.M + 16 * TM - 1) / (16 * TM), tilesN = (g.N + 16 * TN - 1) / (16 * TN);
+    if (tilesM * tilesN > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    hipLaunchKernelGGL((contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>), dim3((unsigned)(tilesM * tilesN)),
+                       dim3(kThreads), 0, stream, g);
+    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+}
+
+template <int WB, bool BIPOLAR, bool CONV>
+dlrt_status pick_vec(const ContractArgs &g, hipStream_t stream)
+{
+    if (g.vec == 4) return launch<WB, 4, BIPOLAR, CONV>(g, stream);
+    if (g.vec == 2) return launch<WB, 2, BIPOLAR, CONV>(g, stream);
+    return launch<WB, 1, BIPOLAR, CONV>(g, stream);
+}
+
+template <bool CONV>
+dlrt_status pick_wbits(const ContractArgs &g, int wbits, bool bipolar, hipStream_t stream)
+{
+    switch (wbits) {
+    case 1: return bipolar ? pick_vec<1, true, CONV>(g, stream) : pick_vec<1, false, CONV>(g, stream);
+    case 2: return pick_vec<2, false, CONV>(g, stream);
+    case 3: return pick_vec<3, false, CONV>(g, stream);
+    case 4: return pick_vec<4, false, CONV>(g, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
+}  // namespace
+
+namespace dlrt {
+
+#define DLRT_CAT2(a, b) a##b
+#define DLRT_CAT(a, b) DLRT_CAT2(a, b)
+
+dlrt_status DLRT_CAT(launch_contract_a, DLRT_ABITS)(const ContractArgs &g, int wbits, bool bipolar, bool conv,
+                                                     hipStream_t stream)
+{
+    return conv ? pick_wbits<true>(g, wbits, bipolar, stream) : pick_wbits<false>(g, wbits, bipolar, stream);
+}
+
+}  // namespace dlrt

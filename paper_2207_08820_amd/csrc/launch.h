@@ -1,0 +1,59 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.  Arguments are
+// already validated; every function enqueues on `stream` and reports only launch failures.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dlrt.h"
+
+namespace dlrt {
+
+// Arguments of one contraction launch (GEMM, or convolution as an implicit im2col GEMM).
+struct ContractArgs {
+    const uint32_t *A;  // GEMM: [M][abits][Kw]; conv: X [N][H][W][abits][Cw]
+    const uint32_t *W;  // [N][wbits][Kw]
+    int32_t *C;         // [M][N]
+    int M, N, Kw;       // Kw: reduction words per plane (conv: KH*KW*Cw)
+    int a_msb_neg, w_msb_neg;
+    int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
+    // convolution geometry (unused by GEMM)
+    int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
+    uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
+};
+
+// One translation unit per activation bit width (contract.hip with -DDLRT_ABITS=n).
+dlrt_status launch_contract_a1(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a2(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a3(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a4(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
+
+dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int Kw, int abits,
+                        int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream);
+
+dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, int32_t *Y, int N, int H, int W, int Cw, int Co,
+                        int KH, int KW, int Ho, int Wo, int sh, int sw, int ph, int pw, int abits, int wbits,
+                        bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream);
+
+// rows x K elements (row stride ld) -> dst word (r, p, kw) at dst[r * row_stride + p * plane_stride + kw_off + kw].
+// The generic destination strides let the same kernel emit both the [rows][bits][Kw] tensor and the
+// per-tap padded layout of convolution weights.
+struct PackArgs {
+    const void *src;
+    int src_type;          // dlrt_src
+    int64_t rows, K, ld;
+    int bits, enc;         // dlrt_encoding
+    const float *scale;
+    int scale_per_row;
+    uint32_t *dst;
+    // destination addressing, in words
+    int64_t taps;          // rows are grouped as [outer][taps]; 1 for plain tensors
+    int64_t outer_stride;  // words between consecutive outer indices
+    int64_t plane_stride;  // words between planes
+    int64_t tap_stride;    // words between taps of one plane
+};
+dlrt_status launch_pack(const PackArgs &p, hipStream_t stream);
+
+dlrt_status launch_epilogue(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
+                            float *out_f32, uint8_t *out_q, int qbits, hipStream_t stream);
+
+}  // namespace dlrt

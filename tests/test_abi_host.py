@@ -1,0 +1,109 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header declares, and
+rejects bad arguments before any launch (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2207_08820_amd", "libdlrt_hip.so")
+HEADER = os.path.join(ROOT, "include", "dlrt.h")
+
+OK, ERR_NULL, ERR_BITS, ERR_SHAPE, ERR_ENCODING, ERR_ALIGN = 0, 1, 2, 3, 4, 5
+UNSIGNED, TWOS, BIPOLAR = 0, 1, 2
+FAKE = 0x10000  # 16-byte aligned, never dereferenced: every call below fails validation first
+NULL = None
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2207_08820_amd.build import build_library
+        build_library()
+    lib = ctypes.CDLL(LIB)
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    lib.dlrt_packed_words.restype = ctypes.c_size_t
+    lib.dlrt_packed_words.argtypes = [i64, i64, i32]
+    lib.dlrt_status_string.restype = ctypes.c_char_p
+    lib.dlrt_pack_bitplanes.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, i32, vp, vp]
+    lib.dlrt_pack_conv_weights.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.dlrt_bitserial_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
+    lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
+    lib.dlrt_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp]
+    return lib
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dlrt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_gemm", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
+                     "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_status_string"]
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_packed_words_and_status_strings(lib):
+    assert lib.dlrt_packed_words(64, 576, 2) == 64 * 2 * 18
+    assert lib.dlrt_packed_words(1, 33, 4) == 8
+    assert lib.dlrt_packed_words(4096, 4096, 2) * 4 * 16 == 4096 * 4096 * 4  # 2 bits instead of 32
+    assert lib.dlrt_packed_words(0, 5, 2) == 0 and lib.dlrt_packed_words(5, 5, 5) == 0
+    seen = {lib.dlrt_status_string(c) for c in range(7)}
+    assert len(seen) == 7 and lib.dlrt_status_string(0) == b"ok"
+
+
+def test_gemm_rejects_bad_arguments_before_launch(lib):
+    g = lib.dlrt_bitserial_gemm
+    assert g(NULL, FAKE, FAKE, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL) == ERR_NULL
+    assert g(FAKE, FAKE, NULL, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL) == ERR_NULL
+    assert g(FAKE, FAKE, FAKE, 4, 4, 32, 0, 2, UNSIGNED, TWOS, NULL) == ERR_BITS
+    assert g(FAKE, FAKE, FAKE, 4, 4, 32, 2, 5, UNSIGNED, TWOS, NULL) == ERR_BITS
+    assert g(FAKE, FAKE, FAKE, 0, 4, 32, 2, 2, UNSIGNED, TWOS, NULL) == ERR_SHAPE
+    assert g(FAKE, FAKE, FAKE, 4, 4, -1, 2, 2, UNSIGNED, TWOS, NULL) == ERR_SHAPE
+    assert g(FAKE, FAKE, FAKE, 4, 4, 32, 2, 2, BIPOLAR, TWOS, NULL) == ERR_ENCODING  # activations
+    assert g(FAKE, FAKE, FAKE, 4, 4, 32, 2, 2, UNSIGNED, BIPOLAR, NULL) == ERR_ENCODING  # wbits != 1
+    assert g(FAKE, FAKE, FAKE, 4, 4, 32, 2, 2, UNSIGNED, 7, NULL) == ERR_ENCODING
+    assert g(FAKE + 4, FAKE, FAKE, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL) == ERR_ALIGN
+
+
+def test_conv_rejects_bad_arguments_before_launch(lib):
+    c = lib.dlrt_bitserial_conv2d
+    ok_shape = [1, 8, 8, 32, 16, 3, 3, 1, 1, 1, 1]
+    assert c(NULL, FAKE, FAKE, *ok_shape, 2, 2, UNSIGNED, TWOS, NULL) == ERR_NULL
+    assert c(FAKE, FAKE, FAKE, *ok_shape, 2, 9, UNSIGNED, TWOS, NULL) == ERR_BITS
+    assert c(FAKE, FAKE, FAKE, 1, 8, 8, 32, 16, 3, 3, 0, 1, 1, 1, 2, 2, UNSIGNED, TWOS, NULL) == ERR_SHAPE  # stride 0
+    assert c(FAKE, FAKE, FAKE, 1, 2, 2, 32, 16, 5, 5, 1, 1, 0, 0, 2, 2, UNSIGNED, TWOS, NULL) == ERR_SHAPE  # kernel > image
+    assert c(FAKE, FAKE, FAKE, *ok_shape, 2, 2, UNSIGNED, BIPOLAR, NULL) == ERR_ENCODING
+    assert c(FAKE, FAKE + 8, FAKE, *ok_shape, 2, 2, UNSIGNED, TWOS, NULL) == ERR_ALIGN
+
+
+def test_pack_and_epilogue_reject_bad_arguments_before_launch(lib):
+    p = lib.dlrt_pack_bitplanes
+    assert p(NULL, 0, 4, 32, 32, 2, UNSIGNED, NULL, 0, FAKE, NULL) == ERR_NULL
+    assert p(FAKE, 0, 4, 32, 32, 6, UNSIGNED, NULL, 0, FAKE, NULL) == ERR_BITS
+    assert p(FAKE, 0, 4, 32, 16, 2, UNSIGNED, NULL, 0, FAKE, NULL) == ERR_SHAPE  # ld < K
+    assert p(FAKE, 0, 4, 32, 32, 2, BIPOLAR, NULL, 0, FAKE, NULL) == ERR_ENCODING  # bipolar needs 1 bit
+    assert p(FAKE, 2, 4, 32, 32, 2, TWOS, NULL, 0, FAKE, NULL) == ERR_NULL  # float source without scale
+    assert p(FAKE, 9, 4, 32, 32, 2, TWOS, NULL, 0, FAKE, NULL) == ERR_SHAPE  # unknown source type
+    assert p(FAKE, 0, 4, 32, 32, 2, UNSIGNED, NULL, 0, FAKE + 4, NULL) == ERR_ALIGN
+    w = lib.dlrt_pack_conv_weights
+    assert w(FAKE, 1, 0, 3, 3, 8, 2, TWOS, NULL, FAKE, NULL) == ERR_SHAPE
+    assert w(FAKE, 1, 4, 3, 3, 8, 1, 5, NULL, FAKE, NULL) == ERR_ENCODING
+    e = lib.dlrt_epilogue_f32
+    assert e(FAKE, FAKE, NULL, 4, 4, NULL, NULL, 2, NULL) == ERR_NULL  # no output at all
+    assert e(FAKE, NULL, NULL, 4, 4, FAKE, NULL, 2, NULL) == ERR_NULL
+    assert e(FAKE, FAKE, NULL, 0, 4, FAKE, NULL, 2, NULL) == ERR_SHAPE
+    assert e(FAKE, FAKE, NULL, 4, 4, NULL, FAKE, 0, NULL) == ERR_BITS
+    assert e(FAKE, FAKE, NULL, 4, 4, NULL, FAKE, 9, NULL) == ERR_BITS
+
+
+def test_binding_exposes_the_same_names():
+    from paper_2207_08820_amd import binding
+    for n in declared_functions():
+        if n != "dlrt_status_string":
+            assert callable(getattr(binding, n))
