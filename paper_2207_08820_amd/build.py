@@ -30,8 +30,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 def _compile(unit, extra) -> str:
     name, objname, defines = unit
     obj = os.path.join(OBJ, objname)
-    subprocess.run([HIPCC, *FLAGS, *defines, *extra, "-c", os.path.join(CSRC, name), "-o", obj], check=True,
-                   stderr=subprocess.PIPE if not os.environ.get("DLRT_BUILD_VERBOSE") else None)
+    proc = subprocess.run([HIPCC, *FLAGS, *defines, *extra, "-c", os.path.join(CSRC, name), "-o", obj],
+                          stderr=subprocess.PIPE, text=True)
+    # the host pass warns that it does not know the device-only target feature: harmless, dropped
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(line for line in proc.stderr.splitlines() if noise not in line)
+    if proc.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {name} {defines}:\n{err}")
+    if err.strip() and os.environ.get("DLRT_BUILD_VERBOSE"):
+        print(err, file=sys.stderr)
     return obj
 
 

@@ -111,6 +111,8 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
     const int64_t Cw = (Ci + 31) / 32;
     if ((int64_t)N * Ho * Wo > 0x7fffffff || (int64_t)KH * KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
     if ((int64_t)H * W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
+    // the kernels divide reduction-word indices by Cw and KW with a 32-bit multiply-high
+    if ((int64_t)KH * KW * Cw * (Cw > KW ? Cw : KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(Wp)) return DLRT_ERR_ALIGN;
     return dlrt::launch_conv(X, Wp, Y, N, H, W, (int)Cw, Co, KH, KW, Ho, Wo, stride_h, stride_w, pad_h, pad_w, abits,
                              wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, as_stream(stream));

@@ -209,7 +209,7 @@ __global__ __launch_bounds__(kThreads, 2) void contract_kernel(const ContractArg
     // the address is clamped into the image and the result discarded.
     auto tap_load = [&](int t, int kwd, uint32_t *out) {
         bool ok = kwd < g.Kw;
-        const int kc = ok ? kwd : g.Kw - 1;
+        const int kc = ok ? kwd : 0;  // word 0 is always a valid, VEC-aligned stand-in
         const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
         const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
         const int ih = ih0[t] + kh, iw = iw0[t] + kw;

@@ -35,11 +35,19 @@ struct Quant {
     int bipolar;  // bit = value > 0
 };
 
-// Put the wave-uniform value v into lane LANE of `old`, leaving the other lanes (one VALU op).
+// Put the two halves of a wave-uniform 64-bit ballot into lanes LANE and LANE + 1 of `old`, leaving
+// the other lanes (two VALU ops).  On gfx950 a VALU instruction that reads an SGPR as data needs two
+// wait states after the VALU instruction that wrote it (here the v_cmp of the ballot); the compiler
+// inserts them for its own code but cannot see into asm, so the block carries its own s_nop.
 template <int LANE>
-__device__ __forceinline__ uint32_t put_lane(uint32_t v, uint32_t old)
+__device__ __forceinline__ uint32_t put_lane_pair(unsigned long long m, uint32_t old)
 {
-    asm("v_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(v), "n"(LANE));
+    const uint32_t lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
+    asm("s_nop 1\n\t"
+        "v_writelane_b32 %0, %1, %3\n\t"
+        "v_writelane_b32 %0, %2, %4"
+        : "+v"(old)
+        : "s"(lo), "s"(hi), "n"(LANE), "n"(LANE + 1));
     return old;
 }
 
@@ -126,8 +134,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const dlrt::PackArgs p, 
                 for (int b = 0; b < BITS; ++b) {
                     const unsigned long long m = __ballot((v >> b) & 1u);
                     // words sub*8 + 2t and sub*8 + 2t + 1 of this step belong to those lanes
-                    outw[b] = put_lane<sub * 8 + 2 * t>((uint32_t)m, outw[b]);
-                    outw[b] = put_lane<sub * 8 + 2 * t + 1>((uint32_t)(m >> 32), outw[b]);
+                    outw[b] = put_lane_pair<sub * 8 + 2 * t>(m, outw[b]);
                 }
             });
         });
