@@ -1,0 +1,244 @@
+"""Benchmark of the bit-serial hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--sweep]
+
+A step is one pass of the whole path over one batch of synthetic input that is already resident
+in HBM: bitplane-pack the uint8 activations and the int8 weights, bit-serial GEMM into int32, and
+the per-channel fp32 scale epilogue.  The workload is the 4096^3 A2W2 GEMM the headline metric is
+quoted on (activations unsigned 2-bit, weights two's-complement 2-bit).  The ResNet-18 A2W2 conv
+stack latency, the second half of the metric, is reported in the same JSON line under "extra".
+Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+# plain 32-bit VALU rate of the chip: 256 compute units x 64 lanes per clock x 2.4 GHz
+VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_events(fn, iters):
+    """Average milliseconds of fn() over `iters` back-to-back enqueues, by events on the current stream."""
+    import torch
+
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def gemm_workload(abits, wbits, size, dev):
+    import torch
+
+    from paper_2207_08820_amd import inputs
+
+    c, a, w = inputs.config5(abits, wbits, size=size)
+    scale = inputs.uniform_scale(c.N, inputs.seed_for(5, 2))
+    t = dict(c=c, a_np=a, w_np=w, scale_np=scale,
+             a=torch.as_tensor(a.astype(np.uint8), device=dev), w=torch.as_tensor(w, device=dev),
+             scale=torch.as_tensor(scale, device=dev))
+    Kw = (c.K + 31) // 32
+    t["A"] = torch.empty((c.M, abits, Kw), dtype=torch.int32, device=dev)
+    t["W"] = torch.empty((c.N, wbits, Kw), dtype=torch.int32, device=dev)
+    t["C"] = torch.empty((c.M, c.N), dtype=torch.int32, device=dev)
+    t["Y"] = torch.empty((c.M, c.N), dtype=torch.float32, device=dev)
+    return t
+
+
+def make_step(dlrt, t, gemm_events=None):
+    c = t["c"]
+
+    def step():
+        dlrt.dlrt_pack_bitplanes(t["a"], c.abits, c.enc_a, out=t["A"])
+        dlrt.dlrt_pack_bitplanes(t["w"], c.wbits, c.enc_w, out=t["W"])
+        if gemm_events is not None:
+            import torch
+
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        dlrt.dlrt_bitserial_gemm(t["A"], t["W"], c.M, c.N, c.K, c.abits, c.wbits, c.enc_a, c.enc_w, out=t["C"])
+        if gemm_events is not None:
+            e1.record()
+            gemm_events.append((e0, e1))
+        dlrt.dlrt_epilogue_f32(t["C"], t["scale"], out_f32=t["Y"])
+
+    return step
+
+
+def resnet18_stack_ms(dlrt, dev, iters=30):
+    """Whole ResNet-18 A2W2 conv chain (19 convs: pack + conv + requant epilogue each), enqueued back
+    to back.  Scale and bias come from the closed-form mean / deviation of a uniform-input layer
+    (mean -0.75 K, sigma 2.165 sqrt(K)); timing does not depend on the values."""
+    import torch
+
+    from paper_2207_08820_amd import inputs
+    from paper_2207_08820_amd.stack import ConvStack
+
+    layers = inputs.resnet18_stack()
+    weights = inputs.stack_weights(3, layers, 2, inputs.TWOS)
+    scales = [np.full(L.Co, 1.0 / (2.165 * np.sqrt(L.K)), np.float32) for L in layers]
+    biases = [np.full(L.Co, 1.5 + 0.75 * L.K / (2.165 * np.sqrt(L.K)), np.float32) for L in layers]
+    stack = ConvStack(layers, weights, scales, biases, 2, 2, inputs.TWOS, device=dev)
+    x0 = torch.as_tensor(inputs.stack_input(3, layers).astype(np.uint8), device=dev)
+    for _ in range(5):
+        stack.run(x0)
+    torch.cuda.synchronize()
+    total = time_events(lambda: stack.run(x0), iters)
+    per_layer = []
+    for i, pl in enumerate(stack.layers):
+        src = pl.spec.src
+        xin = x0 if src < 0 else stack.layers[src].q
+        per_layer.append({"layer": pl.spec.name, "M": pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K,
+                          "ms": round(time_events(lambda: stack.run_layer(i, xin), iters), 5)})
+    return total, per_layer
+
+
+def cpu_baseline(t, budget_s=12.0):
+    """The oracle as it stands, timed on the host cores on a bounded row sample of the same GEMM:
+    pack the sample's activations, integer GEMM against all of W, scale epilogue."""
+    import oracle
+
+    c = t["c"]
+    a, w, scale = t["a_np"], t["w_np"], t["scale_np"]
+    probe = min(256, c.M)
+    t0 = time.perf_counter()
+    oracle.gemm_i32(a[:probe], w)
+    rate = 2.0 * probe * c.N * c.K / (time.perf_counter() - t0)
+    rows = int(min(c.M, max(probe, rate * budget_s / (2.0 * c.N * c.K))))
+    reps = max(1, int(rate * budget_s / (2.0 * rows * c.N * c.K)))  # whole problem fits: repeat it
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.pack_bitplanes(a[:rows], c.abits, c.enc_a)
+        acc = oracle.gemm_i32(a[:rows], w)
+        oracle.epilogue_f32(acc, scale)
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": round(2.0 * rows * c.N * c.K / dt / 1e12, 6), "unit": "effective TOPS",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {rows} of {c.M} activation rows against all {c.N} weight rows, K={c.K} "
+                      f"(pack + int32 GEMM + scale epilogue), {reps} run(s) of {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--size", type=int, default=4096, help="M = N = K of the GEMM (default: the headline 4096)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also time the other bit-width pairs of the 4096^3 sweep")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (a kernel of known HBM traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+
+    from paper_2207_08820_amd import binding as dlrt
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dlrt.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    abits = wbits = 2
+    t = gemm_workload(abits, wbits, args.size, dev)
+    c = t["c"]
+    step = make_step(dlrt, t)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = []
+    timed = make_step(dlrt, t, gemm_events=events)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        timed()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    gemm_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+
+    macs = c.M * c.N * c.K
+    value = 2.0 * macs / (ms_per_step * 1e-3) / 1e12
+    lane_ops = abits * wbits * macs / 16.0  # one AND + one BCNT per plane pair per 32 elements
+    achieved = lane_ops / (gemm_ms * 1e-3)
+    roofline = {"bound": "alu", "kernel": "contract_kernel (dlrt_bitserial_gemm)",
+                "achieved": round(achieved / 1e12, 4), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 4),
+                "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_LANE_OPS, 4), "traffic": None,
+                "kernel_ms": round(gemm_ms, 5),
+                "kernel_effective_tops": round(2.0 * macs / (gemm_ms * 1e-3) / 1e12, 3)}
+    log(f"step {ms_per_step:.4f} ms, gemm kernel {gemm_ms:.4f} ms, {value:.2f} effective TOPS, "
+        f"VALU roofline {roofline['frac']:.3f}")
+
+    extra = {}
+    stack_ms, per_layer = resnet18_stack_ms(dlrt, dev)
+    extra["resnet18_a2w2_conv_stack_ms"] = round(stack_ms, 5)
+    extra["resnet18_per_layer"] = per_layer
+    log(f"ResNet-18 A2W2 conv stack: {stack_ms:.4f} ms for 19 convs")
+
+    if args.sweep:
+        from paper_2207_08820_amd import inputs
+
+        sweep = []
+        for ab, wb in inputs.CONFIG5_PAIRS:
+            ts = gemm_workload(ab, wb, args.size, dev)
+            cs = ts["c"]
+
+            def only_gemm(ts=ts, cs=cs):
+                dlrt.dlrt_bitserial_gemm(ts["A"], ts["W"], cs.M, cs.N, cs.K, cs.abits, cs.wbits, cs.enc_a, cs.enc_w,
+                                         out=ts["C"])
+
+            make_step(dlrt, ts)()
+            for _ in range(3):
+                only_gemm()
+            torch.cuda.synchronize()
+            ms = time_events(only_gemm, 20)
+            ops = ab * wb * macs / 16.0
+            sweep.append({"abits": ab, "wbits": wb, "gemm_ms": round(ms, 5),
+                          "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
+                          "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
+            log(sweep[-1])
+            del ts
+        extra["sweep_4096"] = sweep
+
+    out = {"metric": "bit-serial GEMM effective TOPS (A2W2 4096^3) + ResNet-18 A2W2 conv-stack ms, 1 GPU",
+           "value": round(value, 3), "unit": "effective TOPS (2*M*N*K / step time)", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+           "data": "synthetic",
+           "config": {"workload": f"gemm_{c.M}x{c.N}x{c.K}_A{abits}W{wbits} (bit-width sweep config, pair (2,2)): "
+                                  "pack A + pack W + bit-serial GEMM + fp32 scale epilogue",
+                      "abits": abits, "wbits": wbits, "enc_a": "unsigned", "enc_w": "twos_complement"},
+           "roofline": roofline, "extra": extra}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(t)
+        log("cpu baseline:", out["cpu_baseline"])
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
