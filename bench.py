@@ -77,10 +77,12 @@ def make_step(dlrt, t, gemm_events=None):
     return step
 
 
-def resnet18_stack_ms(dlrt, dev, iters=30):
-    """Whole ResNet-18 A2W2 conv chain (19 convs: pack + conv + requant epilogue each), enqueued back
-    to back.  Scale and bias come from the closed-form mean / deviation of a uniform-input layer
-    (mean -0.75 K, sigma 2.165 sqrt(K)); timing does not depend on the values."""
+def resnet18_stack_ms(dlrt, dev, iters=50):
+    """Whole ResNet-18 A2W2 conv chain (19 convs).  Scale and bias come from the closed-form mean /
+    deviation of a uniform-input layer (mean -0.75 K, sigma 2.165 sqrt(K)); timing does not depend on
+    the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
+    conv launch per layer), the same chain enqueued eagerly from Python, and the unfused chain
+    (pack + conv + epilogue per layer); per-layer times are of the fused kernel alone."""
     import torch
 
     from paper_2207_08820_amd import inputs
@@ -90,19 +92,28 @@ def resnet18_stack_ms(dlrt, dev, iters=30):
     weights = inputs.stack_weights(3, layers, 2, inputs.TWOS)
     scales = [np.full(L.Co, 1.0 / (2.165 * np.sqrt(L.K)), np.float32) for L in layers]
     biases = [np.full(L.Co, 1.5 + 0.75 * L.K / (2.165 * np.sqrt(L.K)), np.float32) for L in layers]
-    stack = ConvStack(layers, weights, scales, biases, 2, 2, inputs.TWOS, device=dev)
     x0 = torch.as_tensor(inputs.stack_input(3, layers).astype(np.uint8), device=dev)
+    out = {}
+
+    stack = ConvStack(layers, weights, scales, biases, 2, 2, inputs.TWOS, device=dev, fused=True, keep_outputs=False)
+    stack.capture(x0)
     for _ in range(5):
-        stack.run(x0)
+        stack.replay()
     torch.cuda.synchronize()
-    total = time_events(lambda: stack.run(x0), iters)
+    out["graph_fused_ms"] = time_events(stack.replay, iters)
+    out["eager_fused_ms"] = time_events(lambda: stack.run(x0), iters)
     per_layer = []
     for i, pl in enumerate(stack.layers):
-        src = pl.spec.src
-        xin = x0 if src < 0 else stack.layers[src].q
-        per_layer.append({"layer": pl.spec.name, "M": pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K,
-                          "ms": round(time_events(lambda: stack.run_layer(i, xin), iters), 5)})
-    return total, per_layer
+        xin = stack.layer_input(i)
+        ms = time_events(lambda: stack.run_layer_fused(i, xin), iters)
+        per_layer.append({"layer": pl.spec.name, "M": pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K, "ms": round(ms, 5)})
+
+    unfused = ConvStack(layers, weights, scales, biases, 2, 2, inputs.TWOS, device=dev, fused=False)
+    for _ in range(3):
+        unfused.run(x0)
+    torch.cuda.synchronize()
+    out["eager_unfused_ms"] = time_events(lambda: unfused.run(x0), iters)
+    return out, per_layer
 
 
 def cpu_baseline(t, budget_s=12.0):
@@ -196,9 +207,10 @@ def main():
 
     extra = {}
     stack_ms, per_layer = resnet18_stack_ms(dlrt, dev)
-    extra["resnet18_a2w2_conv_stack_ms"] = round(stack_ms, 5)
+    extra["resnet18_a2w2_conv_stack_ms"] = round(stack_ms["graph_fused_ms"], 5)
+    extra["resnet18_a2w2_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in stack_ms.items()}
     extra["resnet18_per_layer"] = per_layer
-    log(f"ResNet-18 A2W2 conv stack: {stack_ms:.4f} ms for 19 convs")
+    log(f"ResNet-18 A2W2 conv stack (19 convs): {stack_ms}")
 
     if args.sweep:
         from paper_2207_08820_amd import inputs

@@ -111,6 +111,31 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
                                   void *stream);
 
 /*
+ * Convolution with the epilogue fused in, for chained layers (Section V's convolution followed by
+ * Section IV's t_hat = t_bar * s and the quantizer for the next layer), as ONE launch:
+ *   acc = the int32 result of dlrt_bitserial_conv2d on the same X, Wp and geometry
+ *   y   = fmaf((float)acc, scale[co], bias ? bias[co] : 0.0f)
+ *   q   = (uint8) min(max(rint(y), 0), 2^qbits - 1)
+ *   out_packed = bitplanes of q, [N*Ho*Wo][qbits][ceil(Co/32)] words: exactly what
+ *                dlrt_pack_bitplanes(q, DLRT_SRC_U8, rows = N*Ho*Wo, K = Co, qbits, DLRT_UNSIGNED)
+ *                would write, i.e. the next layer's X.
+ * Any of out_acc, out_f32, out_q, out_packed may be NULL, not all of them; scale is required unless
+ * only out_acc is given; bias may be NULL; qbits in 1..4 (read when out_q or out_packed is given).
+ * out_packed must be 16-byte aligned.  tile_rows and ksplit are tuning hints: 0 lets the library
+ * plan; otherwise tile_rows is the number of output pixels per wave tile (8, 16 or 32 for
+ * wbits <= 2; 4, 8 or 16 for wbits >= 3) and ksplit (1, 2, 4, 8) the number of waves that split the
+ * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
+ * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  The result does not depend on the hints.
+ */
+dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, const float *scale,
+                                        const float *bias, int N, int H, int W, int Ci, int Co, int KH,
+                                        int KW, int stride_h, int stride_w, int pad_h, int pad_w,
+                                        int abits, int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w,
+                                        int32_t *out_acc, float *out_f32, uint8_t *out_q,
+                                        uint32_t *out_packed, int qbits, int tile_rows, int ksplit,
+                                        void *stream);
+
+/*
  * Dequantize / requantize epilogue (Section IV: t_hat = t_bar * s, then the quantizer again for
  * the next layer), per output channel:
  *   y = fmaf((float)acc[r][c], scale[c], bias ? bias[c] : 0.0f)          -> out_f32 (may be NULL)

@@ -50,6 +50,8 @@ def load():
     lib.dlrt_bitserial_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
     lib.dlrt_bitserial_conv2d.restype = i32
     lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
+    lib.dlrt_bitserial_conv2d_fused.restype = i32
+    lib.dlrt_bitserial_conv2d_fused.argtypes = [vp, vp, vp, vp] + [i32] * 15 + [vp, vp, vp, vp, i32, i32, i32, vp]
     lib.dlrt_epilogue_f32.restype = i32
     lib.dlrt_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp]
     _lib = lib
@@ -134,6 +136,23 @@ def dlrt_bitserial_conv2d(X: torch.Tensor, Wp: torch.Tensor, N: int, H: int, W: 
     _check(lib.dlrt_bitserial_conv2d(_ptr(X), _ptr(Wp), _ptr(out), N, H, W, Ci, Co, KH, KW, sh, sw, ph, pw,
                                      abits, wbits, enc_a, enc_w, _stream()), "dlrt_bitserial_conv2d")
     return out
+
+
+def dlrt_bitserial_conv2d_fused(X: torch.Tensor, Wp: torch.Tensor, scale: torch.Tensor | None,
+                                bias: torch.Tensor | None, N: int, H: int, W: int, Ci: int, Co: int, KH: int, KW: int,
+                                stride, pad, abits: int, wbits: int, enc_a: int, enc_w: int, qbits: int = 2,
+                                out_acc: torch.Tensor | None = None, out_f32: torch.Tensor | None = None,
+                                out_q: torch.Tensor | None = None, out_packed: torch.Tensor | None = None,
+                                tile_rows: int = 0, ksplit: int = 0):
+    """One launch: conv -> scale/bias -> requant -> bitplanes of the result.  Only the outputs whose
+    buffers are passed are written; returns nothing."""
+    lib = load()
+    sh, sw = stride
+    ph, pw = pad
+    _check(lib.dlrt_bitserial_conv2d_fused(_ptr(X), _ptr(Wp), _ptr(scale), _ptr(bias), N, H, W, Ci, Co, KH, KW,
+                                           sh, sw, ph, pw, abits, wbits, enc_a, enc_w, _ptr(out_acc), _ptr(out_f32),
+                                           _ptr(out_q), _ptr(out_packed), qbits, tile_rows, ksplit, _stream()),
+           "dlrt_bitserial_conv2d_fused")
 
 
 def dlrt_epilogue_f32(acc: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor | None = None,

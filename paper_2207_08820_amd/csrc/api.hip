@@ -118,6 +118,36 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
                              wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, as_stream(stream));
 }
 
+dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, const float *scale, const float *bias,
+                                        int N, int H, int W, int Ci, int Co, int KH, int KW, int stride_h,
+                                        int stride_w, int pad_h, int pad_w, int abits, int wbits, dlrt_encoding enc_a,
+                                        dlrt_encoding enc_w, int32_t *out_acc, float *out_f32, uint8_t *out_q,
+                                        uint32_t *out_packed, int qbits, int tile_rows, int ksplit, void *stream)
+{
+    if (!X || !Wp) return DLRT_ERR_NULL;
+    if (!out_acc && !out_f32 && !out_q && !out_packed) return DLRT_ERR_NULL;
+    if ((out_f32 || out_q || out_packed) && !scale) return DLRT_ERR_NULL;
+    if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
+    if ((out_q || out_packed) && !bits_ok(qbits)) return DLRT_ERR_BITS;
+    if (N <= 0 || H <= 0 || W <= 0 || Ci <= 0 || Co <= 0 || KH <= 0 || KW <= 0) return DLRT_ERR_SHAPE;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return DLRT_ERR_SHAPE;
+    if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return DLRT_ERR_SHAPE;
+    if (tile_rows < 0 || ksplit < 0) return DLRT_ERR_SHAPE;
+    const int Ho = (H + 2 * pad_h - KH) / stride_h + 1, Wo = (W + 2 * pad_w - KW) / stride_w + 1;
+    const int64_t Cw = (Ci + 31) / 32;
+    if ((int64_t)N * Ho * Wo > 0x7fffffff || (int64_t)KH * KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if ((int64_t)H * W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if ((int64_t)KH * KW * Cw * (Cw > KW ? Cw : KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Wp) || (out_packed && !aligned16(out_packed))) return DLRT_ERR_ALIGN;
+    dlrt::ConvShape c{N, H, W, (int)Cw, Co, KH, KW, Ho, Wo, stride_h, stride_w, pad_h, pad_w};
+    dlrt::FusedOut o{};
+    o.acc = out_acc; o.y = out_f32; o.q = out_q; o.packed = out_packed;
+    o.scale = scale; o.bias = bias;
+    o.qbits = (out_q || out_packed) ? qbits : 1;
+    return dlrt::launch_conv_fused(X, Wp, c, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS,
+                                   enc_w == DLRT_BIPOLAR, o, tile_rows, ksplit, as_stream(stream));
+}
+
 dlrt_status dlrt_epilogue_f32(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
                               float *out_f32, uint8_t *out_q, int qbits, void *stream)
 {

@@ -30,6 +30,67 @@ dlrt_status by_abits(const dlrt::ContractArgs &g, int abits, int wbits, bool bip
     return DLRT_ERR_BITS;
 }
 
+dlrt_status wave_by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
+                          bool conv, int tm, int ksplit, hipStream_t stream)
+{
+    switch (abits) {
+    case 1: return dlrt::launch_wave_a1(g, o, wbits, bipolar, conv, tm, ksplit, stream);
+    case 2: return dlrt::launch_wave_a2(g, o, wbits, bipolar, conv, tm, ksplit, stream);
+    case 3: return dlrt::launch_wave_a3(g, o, wbits, bipolar, conv, tm, ksplit, stream);
+    case 4: return dlrt::launch_wave_a4(g, o, wbits, bipolar, conv, tm, ksplit, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
+// ---- tile planning -----------------------------------------------------------------------------
+// Block kernel (contract.hip): lane tile {8,4,2,2}[bits] on 16 x 16 lanes.
+int block_tile(int bits) { return 16 * (bits == 1 ? 8 : bits == 2 ? 4 : 2); }
+
+// The block kernel needs enough 256-thread blocks to occupy 256 compute units twice over; below
+// that the per-wave kernel spreads the same work over more, smaller waves.
+bool prefer_wave_kernel(int M, int N, int abits, int wbits)
+{
+    const int64_t blocks = (int64_t)((M + block_tile(abits) - 1) / block_tile(abits)) *
+                           ((N + block_tile(wbits) - 1) / block_tile(wbits));
+    return blocks < 512;
+}
+
+struct WavePlan {
+    int tm, ksplit;
+    bool found;  // false: no feasible candidate matched the hints
+};
+
+// Per-wave kernel: wave tile (LY * tm) rows x 32 columns, LY = 8 for wbits <= 2 else 4.  Picks the
+// (tm, ksplit) with the smallest modelled time: VALU and load cycles of one wave, stretched when
+// there are more waves than the chip's 1024 SIMDs, plus the cost of the cross-wave reduction.
+WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hint, int ksplit_hint)
+{
+    const int tn = wbits <= 2 ? 4 : 2, ly = 2 * tn;
+    const int steps = (Kw + 3) / 4;
+    WavePlan best{1, 1, false};
+    double best_cost = 1e300;
+    for (int tm = 1; tm <= 4; tm *= 2) {
+        if (tm * tn * abits * wbits > 72) break;
+        if (tile_rows_hint > 0 && ly * tm != tile_rows_hint) continue;
+        const int rows = ly * tm;
+        const int64_t tiles = (int64_t)((M + rows - 1) / rows) * ((N + 31) / 32);
+        for (int ks = 1; ks <= 8; ks *= 2) {
+            if (ksplit_hint > 0 && ks != ksplit_hint) continue;
+            if (ks > 1 && ks > steps) break;
+            const int units = 4 * abits * rows + 4 * wbits * 32;
+            if ((int64_t)ks * units * 16 > 65536) break;
+            const int spw = (steps + ks - 1) / ks;
+            const double valu = (double)spw * 4 * tm * tn * abits * wbits * 2 * 4 / 0.7;
+            const double load = (double)spw * (abits * rows + wbits * 32) * 16 / 32;
+            const double waves = (double)tiles * ks;
+            const double stretch = waves > 1024 ? waves / 1024 : 1.0;
+            const double cost = (valu + load) * stretch + (ks > 1 ? 500 + 120 * ks : 0);
+            if (cost < best_cost) { best_cost = cost; best = WavePlan{tm, ks, true}; }
+        }
+    }
+    return best;
+}
+
 }  // namespace
 
 namespace dlrt {
@@ -42,6 +103,13 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int M,
     g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
+    if (prefer_wave_kernel(M, N, abits, wbits)) {
+        FusedOut o{};
+        o.acc = C;
+        o.qbits = 1;
+        const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
+        return wave_by_abits(g, o, abits, wbits, bipolar, false, p.tm, p.ksplit, stream);
+    }
     return by_abits(g, abits, wbits, bipolar, false, stream);
 }
 
@@ -61,7 +129,33 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, int32_t *Y, int N
     g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
     g.magicCw = magic_for(Cw);
     g.magicKW = magic_for(KW);
+    if (prefer_wave_kernel(g.M, g.N, abits, wbits)) {
+        FusedOut o{};
+        o.acc = Y;
+        o.qbits = 1;
+        const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, 0, 0);
+        return wave_by_abits(g, o, abits, wbits, bipolar, true, p.tm, p.ksplit, stream);
+    }
     return by_abits(g, abits, wbits, bipolar, true, stream);
+}
+
+dlrt_status launch_conv_fused(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
+                              bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows,
+                              int ksplit, hipStream_t stream)
+{
+    ContractArgs g{};
+    g.A = X; g.W = Wp; g.C = nullptr;
+    g.M = c.N * c.Ho * c.Wo; g.N = c.Co; g.Kw = c.KH * c.KW * c.Cw;
+    g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
+    const int va = widest_vec(X, c.Cw), vw = widest_vec(Wp, g.Kw);
+    g.vec = va < vw ? va : vw;
+    g.H = c.H; g.Wd = c.W; g.Cw = c.Cw; g.KH = c.KH; g.KW = c.KW; g.Ho = c.Ho; g.Wo = c.Wo;
+    g.sh = c.sh; g.sw = c.sw; g.ph = c.ph; g.pw = c.pw;
+    g.magicCw = magic_for(c.Cw);
+    g.magicKW = magic_for(c.KW);
+    const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
+    if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have
+    return wave_by_abits(g, o, abits, wbits, bipolar, true, p.tm, p.ksplit, stream);
 }
 
 }  // namespace dlrt

@@ -1,0 +1,375 @@
+// Latency-oriented bit-serial contraction for small problems (single conv layers at batch 1):
+// one WAVE owns an output tile of (LY*TM) rows x 32 columns over a slice of the reduction, so a
+// layer with a few thousand outputs still spreads over hundreds of waves.
+//
+// Same arithmetic as contract.hip (Section V of arXiv 2207.08820: accumulate popcount(W[i] & A[j])
+// per plane pair, apply shifts and signs once at the end); what differs is the decomposition:
+//   * no block-wide barrier in the reduction loop: every wave stages its own A / W chunk in its own
+//     LDS region and only has to order its own LDS traffic;
+//   * the waves of a block split the reduction (ksplit = 1..8 slices of whole 4-word steps) and add
+//     their partial sums through LDS at the end;
+//   * the epilogue is fused: scale / bias (Section IV, t_hat = t_bar * s), requantization and the
+//     bitplane packing of the NEXT layer's activations happen on the accumulators in registers,
+//     so a chained layer is one launch and the int32 tensor never has to touch HBM.
+// A wave tile is always 32 columns wide (lane grid LX x LY = (32/TN) x (2*TN), lane (lx, ly) owns
+// columns lx*TN + s and rows ly + LY*r): the TN result bits of a lane are adjacent bits of one
+// packed output word, which an OR-reduction over the LX lanes of a row completes.
+//
+// Compiled once per activation bit width (-DDLRT_ABITS=1..4), like contract.hip.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "contract_common.h"
+#include "dlrt.h"
+#include "launch.h"
+
+#ifndef DLRT_ABITS
+#error "compile with -DDLRT_ABITS=1..4"
+#endif
+
+namespace {
+
+using dlrt::ContractArgs;
+using dlrt::FusedOut;
+
+template <int WB> struct WaveTN { static constexpr int value = WB <= 2 ? 4 : 2; };
+
+template <int AB, int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
+__global__ __launch_bounds__(512) void contract_wave_kernel(const ContractArgs g, const FusedOut o, const int ksplit,
+                                                            const int steps_per_wave)
+{
+    constexpr int TN = WaveTN<WB>::value;
+    constexpr int LX = 32 / TN, LY = 64 / LX;
+    constexpr int ROWS = LY * TM;     // rows of the wave tile; it is 32 columns wide
+    constexpr int UA = 4 * AB * ROWS; // 16-byte units of one staged A chunk (4 steps x planes x rows)
+    constexpr int UW = 4 * WB * 32;
+    constexpr int NA = (UA + 63) / 64, NW = UW / 64;  // staging slots per lane
+    constexpr int NG = TN * WB;
+
+    extern __shared__ uint4 lds[];  // ksplit regions of UA + UW units; reused for the final reduction
+
+    const int lane = threadIdx.x & 63;
+    const int ks = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave index = reduction slice
+    uint4 *const la = lds + ks * (UA + UW);
+    uint4 *const lw = la + UA;
+    const int lx = lane % LX, ly = lane / LX;
+    const int tilesN = (g.N + 31) / 32;
+    const int tileM = blockIdx.x / tilesN, tileN = blockIdx.x - tileM * tilesN;
+    const int m0 = tileM * ROWS, n0 = tileN * 32;
+
+    // ---- staging slots: lane + 64 t; four consecutive lanes fetch the 64 contiguous bytes of one
+    // (row, plane).  Rows / columns beyond the matrix are clamped (loaded, never stored). ----
+    const uint32_t *srcA[NA];
+    int dstA[NA], k4A[NA], ih0[NA], iw0[NA];
+#pragma unroll
+    for (int t = 0; t < NA; ++t) {
+        const int s = lane + 64 * t;
+        const int sc = s < UA ? s : 0;
+        const int k4 = sc & 3, rp = sc >> 2, plane = rp % AB, row = rp / AB;
+        dstA[t] = s < UA ? (k4 * AB + plane) * ROWS + row : -1;
+        k4A[t] = k4;
+        const int m = min(m0 + row, g.M - 1);
+        ih0[t] = 0;
+        iw0[t] = 0;
+        if (CONV) {
+            const int hw = g.Ho * g.Wo;
+            const int n = m / hw, rem = m - n * hw;
+            const int oh = rem / g.Wo, ow = rem - oh * g.Wo;
+            ih0[t] = oh * g.sh - g.ph;
+            iw0[t] = ow * g.sw - g.pw;
+            srcA[t] = g.A + (size_t)n * g.H * g.Wd * AB * g.Cw + plane * g.Cw;
+        } else {
+            srcA[t] = g.A + ((size_t)m * AB + plane) * g.Kw + k4 * 4;
+        }
+    }
+    const uint32_t *srcW[NW];
+    int dstW[NW], k4W[NW];
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        const int s = lane + 64 * t;
+        const int k4 = s & 3, rp = s >> 2, plane = rp % WB, col = rp / WB;
+        // column c is read by lane lx = c / TN as its s = c % TN: place it so that lanes of
+        // consecutive lx read consecutive 16-byte units
+        dstW[t] = (k4 * WB + plane) * 32 + (col % TN) * LX + col / TN;
+        k4W[t] = k4;
+        srcW[t] = g.W + ((size_t)min(n0 + col, g.N - 1) * WB + plane) * g.Kw + k4 * 4;
+    }
+
+    uint4 stageA[NA], stageW[NW];
+
+    // implicit im2col (see contract.hip): VEC words of one tap, zero outside the image / reduction
+    auto tap_load = [&](int t, int kwd, uint32_t *out) {
+        bool ok = kwd < g.Kw;
+        const int kc = ok ? kwd : 0;
+        const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
+        const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
+        const int ih = ih0[t] + kh, iw = iw0[t] + kw;
+        ok = ok && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
+        const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
+        const uint32_t *p = srcA[t] + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
+        if (VEC == 4) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(p);
+            out[0] = ok ? q.x : 0u; out[1] = ok ? q.y : 0u; out[2] = ok ? q.z : 0u; out[3] = ok ? q.w : 0u;
+        } else if (VEC == 2) {
+            const uint2 q = *reinterpret_cast<const uint2 *>(p);
+            out[0] = ok ? q.x : 0u; out[1] = ok ? q.y : 0u;
+        } else {
+            const uint32_t q = *p;
+            out[0] = ok ? q : 0u;
+        }
+    };
+    auto fetch = [&](int kbase) {
+        if (CONV) {
+#pragma unroll
+            for (int t = 0; t < NA; ++t) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; e += VEC) tap_load(t, kbase + k4A[t] * 4 + e, w + e);
+                stageA[t] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        if (kbase + 16 <= g.Kw) {  // all four steps inside the reduction: no guards
+            if (!CONV) {
+#pragma unroll
+                for (int t = 0; t < NA; ++t) stageA[t] = load4<VEC>(srcA[t] + kbase);
+            }
+#pragma unroll
+            for (int t = 0; t < NW; ++t) stageW[t] = load4<VEC>(srcW[t] + kbase);
+        } else {
+            if (!CONV) {
+#pragma unroll
+                for (int t = 0; t < NA; ++t) stageA[t] = load4_tail(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
+            }
+#pragma unroll
+            for (int t = 0; t < NW; ++t) stageW[t] = load4_tail(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int t = 0; t < NA; ++t)
+            if (dstA[t] >= 0) la[dstA[t]] = stageA[t];
+#pragma unroll
+        for (int t = 0; t < NW; ++t) lw[dstW[t]] = stageW[t];
+        // the chunk is read back by other lanes of this wave only: order the wave's LDS traffic
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    int acc[TM][AB][NG];
+    int rowpc[TM][AB];
+#pragma unroll
+    for (int r = 0; r < TM; ++r)
+#pragma unroll
+        for (int j = 0; j < AB; ++j) {
+            rowpc[r][j] = 0;
+#pragma unroll
+            for (int n = 0; n < NG; ++n) acc[r][j][n] = 0;
+        }
+
+    // this wave's slice of the reduction, in steps of 4 words
+    const int steps = (g.Kw + 3) / 4;
+    const int s_begin = min(ks * steps_per_wave, steps), s_end = min(s_begin + steps_per_wave, steps);
+
+    if (s_begin < s_end) {
+        fetch(s_begin * 4);
+        commit();
+    }
+    for (int c0 = s_begin; c0 < s_end; c0 += 4) {
+        const int nst = min(4, s_end - c0);
+        const bool more = c0 + 4 < s_end;
+        if (more) fetch((c0 + 4) * 4);
+
+        uint4 av[2][TM][AB], wv[2][TN][WB];
+        auto lds_load = [&](int b, int k4) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int j = 0; j < AB; ++j) av[b][r][j] = la[(k4 * AB + j) * ROWS + ly + LY * r];
+#pragma unroll
+            for (int s = 0; s < TN; ++s)
+#pragma unroll
+                for (int i = 0; i < WB; ++i) wv[b][s][i] = lw[(k4 * WB + i) * 32 + s * LX + lx];
+        };
+        auto mac = [&](int b) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t w[NG];
+#pragma unroll
+                for (int s = 0; s < TN; ++s)
+#pragma unroll
+                    for (int i = 0; i < WB; ++i) {
+                        const uint4 &q = wv[b][s][i];
+                        w[s * WB + i] = e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
+                    }
+#pragma unroll
+                for (int r = 0; r < TM; ++r)
+#pragma unroll
+                    for (int j = 0; j < AB; ++j) {
+                        const uint4 &q = av[b][r][j];
+                        const uint32_t a = e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
+                        if (BIPOLAR) popc_acc(rowpc[r][j], a);
+                        and_popc_group<NG>(acc[r][j], a, w);
+                    }
+            }
+        };
+        lds_load(0, 0);
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+            if (k4 < nst) {
+                if (k4 + 1 < 4) lds_load((k4 + 1) & 1, k4 + 1);  // step k4+1 may lie beyond nst: read, not used
+                mac(k4 & 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) commit();
+    }
+
+    // ---- plane pairs -> one integer per output (signs and shifts of Section V's double sum) ----
+    int total[TM][TN];
+#pragma unroll
+    for (int r = 0; r < TM; ++r)
+#pragma unroll
+        for (int s = 0; s < TN; ++s) {
+            int sum = 0;
+#pragma unroll
+            for (int j = 0; j < AB; ++j) {
+                int part = 0;
+                if (BIPOLAR) {
+                    part = 2 * acc[r][j][s] - rowpc[r][j];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < WB; ++i) {
+                        const int term = acc[r][j][s * WB + i] << i;
+                        part += (g.w_msb_neg && i == WB - 1) ? -term : term;
+                    }
+                }
+                part <<= j;
+                sum += (g.a_msb_neg && j == AB - 1) ? -part : part;
+            }
+            total[r][s] = sum;
+        }
+
+    // ---- add the slices of the other waves (the sum is linear in the slices) ----
+    if (ksplit > 1) {
+        int *red = reinterpret_cast<int *>(lds);
+        __syncthreads();  // every wave is done with its staging region
+        if (ks > 0) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int s = 0; s < TN; ++s) red[((ks - 1) * TM * TN + r * TN + s) * 64 + lane] = total[r][s];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+        for (int k = 1; k < ksplit; ++k) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int s = 0; s < TN; ++s) total[r][s] += red[((k - 1) * TM * TN + r * TN + s) * 64 + lane];
+        }
+    }
+
+    // ---- fused epilogue on the registers of wave 0 ----
+    const float qmax = (float)((1 << o.qbits) - 1);
+    const int Cwo = (g.N + 31) / 32;
+#pragma unroll
+    for (int r = 0; r < TM; ++r) {
+        const int m = m0 + ly + LY * r;
+        uint32_t q[TN];
+#pragma unroll
+        for (int s = 0; s < TN; ++s) {
+            const int n = n0 + lx * TN + s;
+            const bool live = m < g.M && n < g.N;
+            q[s] = 0;
+            if (live) {
+                const size_t idx = (size_t)m * g.N + n;
+                if (o.acc) o.acc[idx] = total[r][s];
+                if (o.scale) {
+                    const float y = __fmaf_rn((float)total[r][s], o.scale[n], o.bias ? o.bias[n] : 0.0f);
+                    if (o.y) o.y[idx] = y;
+                    q[s] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
+                    if (o.q) o.q[idx] = (uint8_t)q[s];
+                }
+            }
+        }
+        if (o.packed) {  // uniform: every lane takes part in the shuffles
+            for (int p = 0; p < o.qbits; ++p) {
+                uint32_t word = 0;
+#pragma unroll
+                for (int s = 0; s < TN; ++s) word |= ((q[s] >> p) & 1u) << (lx * TN + s);
+#pragma unroll
+                for (int off = 1; off < LX; off <<= 1) word |= (uint32_t)__shfl_xor((int)word, off);
+                if (lx == 0 && m < g.M) o.packed[((size_t)m * o.qbits + p) * Cwo + tileN] = word;
+            }
+        }
+    }
+}
+
+template <int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
+dlrt_status launch(const ContractArgs &g, const FusedOut &o, int ksplit, hipStream_t stream)
+{
+    constexpr int AB = DLRT_ABITS;
+    constexpr int TN = WaveTN<WB>::value;
+    if constexpr (TM * TN * AB * WB > 72) {
+        return DLRT_ERR_SHAPE;  // never planned: too many accumulators per lane
+    } else {
+        constexpr int ROWS = (64 / (32 / TN)) * TM;
+        constexpr int units = 4 * AB * ROWS + 4 * WB * 32;
+        const int64_t tiles = (int64_t)((g.M + ROWS - 1) / ROWS) * ((g.N + 31) / 32);
+        if (tiles > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+        const int steps = (g.Kw + 3) / 4;
+        const int steps_per_wave = (steps + ksplit - 1) / ksplit;
+        const size_t lds_bytes = (size_t)ksplit * units * 16;
+        hipLaunchKernelGGL((contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>), dim3((unsigned)tiles),
+                           dim3(64 * ksplit), lds_bytes, stream, g, o, ksplit, steps_per_wave);
+        return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+    }
+}
+
+template <int WB, int TM, bool BIPOLAR, bool CONV>
+dlrt_status pick_vec(const ContractArgs &g, const FusedOut &o, int ksplit, hipStream_t stream)
+{
+    if (g.vec == 4) return launch<WB, TM, 4, BIPOLAR, CONV>(g, o, ksplit, stream);
+    if (g.vec == 2) return launch<WB, TM, 2, BIPOLAR, CONV>(g, o, ksplit, stream);
+    return launch<WB, TM, 1, BIPOLAR, CONV>(g, o, ksplit, stream);
+}
+
+template <int WB, bool BIPOLAR, bool CONV>
+dlrt_status pick_tm(const ContractArgs &g, const FusedOut &o, int tm, int ksplit, hipStream_t stream)
+{
+    if (tm == 4) return pick_vec<WB, 4, BIPOLAR, CONV>(g, o, ksplit, stream);
+    if (tm == 2) return pick_vec<WB, 2, BIPOLAR, CONV>(g, o, ksplit, stream);
+    return pick_vec<WB, 1, BIPOLAR, CONV>(g, o, ksplit, stream);
+}
+
+template <bool CONV>
+dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, int tm, int ksplit,
+                       hipStream_t stream)
+{
+    switch (wbits) {
+    case 1:
+        return bipolar ? pick_tm<1, true, CONV>(g, o, tm, ksplit, stream)
+                       : pick_tm<1, false, CONV>(g, o, tm, ksplit, stream);
+    case 2: return pick_tm<2, false, CONV>(g, o, tm, ksplit, stream);
+    case 3: return pick_tm<3, false, CONV>(g, o, tm, ksplit, stream);
+    case 4: return pick_tm<4, false, CONV>(g, o, tm, ksplit, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
+}  // namespace
+
+namespace dlrt {
+
+#define DLRT_CAT2(a, b) a##b
+#define DLRT_CAT(a, b) DLRT_CAT2(a, b)
+
+dlrt_status DLRT_CAT(launch_wave_a, DLRT_ABITS)(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar,
+                                                 bool conv, int tm, int ksplit, hipStream_t stream)
+{
+    return conv ? pick_wbits<true>(g, o, wbits, bipolar, tm, ksplit, stream)
+                : pick_wbits<false>(g, o, wbits, bipolar, tm, ksplit, stream);
+}
+
+}  // namespace dlrt

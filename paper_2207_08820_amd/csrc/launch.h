@@ -21,11 +21,38 @@ struct ContractArgs {
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
 };
 
+// Optional outputs of the fused epilogue of the per-wave kernel; any pointer may be null.
+struct FusedOut {
+    int32_t *acc;      // [M][N] accumulators
+    float *y;          // [M][N] fma(float(acc), scale[n], bias[n])
+    uint8_t *q;        // [M][N] clamp(rint(y), 0, 2^qbits - 1)
+    uint32_t *packed;  // [M][qbits][ceil(N/32)] bitplanes of q (the next layer's packed activations)
+    const float *scale, *bias;  // scale is required for y / q / packed
+    int qbits;
+};
+
 // One translation unit per activation bit width (contract.hip with -DDLRT_ABITS=n).
 dlrt_status launch_contract_a1(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
 dlrt_status launch_contract_a2(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
 dlrt_status launch_contract_a3(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
 dlrt_status launch_contract_a4(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
+
+// Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n): tm = rows per lane (1, 2, 4), ksplit = waves
+// per block that split the reduction (1, 2, 4, 8); both as planned by plan_wave().
+dlrt_status launch_wave_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+
+// Conv geometry handed from the C ABI to the launcher.
+struct ConvShape {
+    int N, H, W, Cw, Co, KH, KW, Ho, Wo, sh, sw, ph, pw;
+};
+
+// Fused convolution on the per-wave kernel; tile_rows / ksplit are hints (0 = planned by the library).
+dlrt_status launch_conv_fused(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
+                              bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows,
+                              int ksplit, hipStream_t stream);
 
 dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int Kw, int abits,
                         int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream);

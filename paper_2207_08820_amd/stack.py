@@ -1,14 +1,19 @@
 """Layer-list harness: chains packed convolutions on the GPU through the C ABI.
 
 A stand-in for the graph runtime that the paper's product has around its kernels (Section VI):
-just enough to run a list of quantized conv layers back to back.  Each layer is
-pack (activations) -> dlrt_bitserial_conv2d -> dlrt_epilogue_f32 with requantization, and the
-uint8 result feeds the layers that name it as their source.  All arithmetic happens in the
-library's kernels; this module only owns the buffers and the call order.
+just enough to run a list of quantized conv layers back to back.  Two ways to run a layer:
+
+* ``fused=True`` (default): one ``dlrt_bitserial_conv2d_fused`` launch per layer, which writes the
+  NEXT layer's packed activations directly (conv -> scale/bias -> requant -> bitplanes); only the
+  stack input goes through ``dlrt_pack_bitplanes``.
+* ``fused=False``: ``dlrt_pack_bitplanes`` -> ``dlrt_bitserial_conv2d`` -> ``dlrt_epilogue_f32`` per layer.
+
+``capture()`` records the chain once into a HIP graph so that replays cost one launch from the host.
+All arithmetic happens in the library's kernels; this module only owns the buffers and the call order.
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 
 import torch
 
@@ -22,29 +27,39 @@ class PackedLayer:
     scale: torch.Tensor          # fp32 [Co]
     bias: torch.Tensor | None    # fp32 [Co]
     # buffers, allocated once so that the timed chain allocates nothing
-    xp: torch.Tensor = field(default=None)
-    acc: torch.Tensor = field(default=None)
-    q: torch.Tensor = field(default=None)
+    xp: torch.Tensor = None      # unfused: this layer's packed input
+    acc: torch.Tensor = None     # int32 accumulators (unfused, or fused with keep_outputs)
+    q: torch.Tensor = None       # uint8 requantized output (unfused, or fused with keep_outputs)
+    out_packed: torch.Tensor = None  # fused: packed requantized output = input of the consumers
 
 
 class ConvStack:
-    def __init__(self, layers, weights_i8, scales, biases, abits: int, wbits: int, enc_w: int, device="cuda:0"):
+    def __init__(self, layers, weights_i8, scales, biases, abits: int, wbits: int, enc_w: int, device="cuda:0",
+                 fused: bool = True, keep_outputs: bool = True):
         self.abits, self.wbits, self.enc_w = abits, wbits, enc_w
+        self.fused, self.keep = fused, keep_outputs
         self.device = torch.device(device)
         self.layers = []
+        self.graph = None
         for L, w, s, b in zip(layers, weights_i8, scales, biases):
             wt = torch.as_tensor(w, device=self.device)
             wp = binding.dlrt_pack_conv_weights(wt, wbits, enc_w)
             pl = PackedLayer(L, wp, torch.as_tensor(s, device=self.device),
                              None if b is None else torch.as_tensor(b, device=self.device))
-            Cw = (L.Ci + 31) // 32
-            pl.xp = torch.empty((L.H * L.W, abits, Cw), dtype=torch.int32, device=self.device)
-            pl.acc = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.int32, device=self.device)
-            pl.q = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.uint8, device=self.device)
+            if fused:
+                pl.out_packed = torch.empty((L.Ho * L.Wo, abits, (L.Co + 31) // 32), dtype=torch.int32,
+                                            device=self.device)
+            else:
+                pl.xp = torch.empty((L.H * L.W, abits, (L.Ci + 31) // 32), dtype=torch.int32, device=self.device)
+            if keep_outputs or not fused:
+                pl.acc = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.int32, device=self.device)
+                pl.q = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.uint8, device=self.device)
             self.layers.append(pl)
+        L0 = layers[0]
+        self.x0_packed = torch.empty((L0.H * L0.W, abits, (L0.Ci + 31) // 32), dtype=torch.int32, device=self.device)
 
+    # ---- unfused: three launches per layer ----
     def run_layer(self, i: int, x_u8: torch.Tensor):
-        """x_u8: NHWC uint8 activations of layer i.  Fills the layer's acc and q buffers."""
         pl = self.layers[i]
         L = pl.spec
         binding.dlrt_pack_bitplanes(x_u8, self.abits, binding.UNSIGNED, out=pl.xp)
@@ -52,10 +67,45 @@ class ConvStack:
                                       (L.pad, L.pad), self.abits, self.wbits, binding.UNSIGNED, self.enc_w,
                                       out=pl.acc)
         binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=False, qbits=self.abits, out_q=pl.q)
-        return pl.acc, pl.q
+
+    # ---- fused: one launch per layer ----
+    def run_layer_fused(self, i: int, x_packed: torch.Tensor, tile_rows: int = 0, ksplit: int = 0):
+        pl = self.layers[i]
+        L = pl.spec
+        binding.dlrt_bitserial_conv2d_fused(pl.xp if x_packed is None else x_packed, pl.wp, pl.scale, pl.bias,
+                                            1, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride), (L.pad, L.pad),
+                                            self.abits, self.wbits, binding.UNSIGNED, self.enc_w, qbits=self.abits,
+                                            out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
+                                            out_packed=pl.out_packed, tile_rows=tile_rows, ksplit=ksplit)
+
+    def layer_input(self, i: int):
+        src = self.layers[i].spec.src
+        return self.x0_packed if src < 0 else self.layers[src].out_packed
 
     def run(self, x0_u8: torch.Tensor):
-        """Enqueue the whole chain; returns nothing (results stay in the per-layer buffers)."""
-        for i, pl in enumerate(self.layers):
-            src = pl.spec.src
-            self.run_layer(i, x0_u8 if src < 0 else self.layers[src].q)
+        """Enqueue the whole chain; results stay in the per-layer buffers."""
+        if self.fused:
+            binding.dlrt_pack_bitplanes(x0_u8, self.abits, binding.UNSIGNED, out=self.x0_packed)
+            for i in range(len(self.layers)):
+                self.run_layer_fused(i, self.layer_input(i))
+        else:
+            for i, pl in enumerate(self.layers):
+                src = pl.spec.src
+                self.run_layer(i, x0_u8 if src < 0 else self.layers[src].q)
+
+    # ---- HIP graph ----
+    def capture(self, x0_u8: torch.Tensor):
+        """Record run(x0_u8) into a HIP graph (x0_u8 is read in place on every replay)."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.run(x0_u8)  # warm-up outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.run(x0_u8)
+        return self.graph
+
+    def replay(self):
+        self.graph.replay()

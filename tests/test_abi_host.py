@@ -31,6 +31,7 @@ def lib():
     lib.dlrt_bitserial_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
     lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
     lib.dlrt_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp]
+    lib.dlrt_bitserial_conv2d_fused.argtypes = [vp, vp, vp, vp] + [i32] * 15 + [vp, vp, vp, vp, i32, i32, i32, vp]
     return lib
 
 
@@ -42,7 +43,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_gemm", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
+    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_gemm", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
                      "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_status_string"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -80,6 +81,20 @@ def test_conv_rejects_bad_arguments_before_launch(lib):
     assert c(FAKE, FAKE, FAKE, 1, 2, 2, 32, 16, 5, 5, 1, 1, 0, 0, 2, 2, UNSIGNED, TWOS, NULL) == ERR_SHAPE  # kernel > image
     assert c(FAKE, FAKE, FAKE, *ok_shape, 2, 2, UNSIGNED, BIPOLAR, NULL) == ERR_ENCODING
     assert c(FAKE, FAKE + 8, FAKE, *ok_shape, 2, 2, UNSIGNED, TWOS, NULL) == ERR_ALIGN
+
+
+def test_fused_conv_rejects_bad_arguments_before_launch(lib):
+    f = lib.dlrt_bitserial_conv2d_fused
+    shape = [1, 8, 8, 32, 16, 3, 3, 1, 1, 1, 1]
+    enc = [2, 2, UNSIGNED, TWOS]
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, NULL, NULL, NULL, NULL, 2, 0, 0, NULL) == ERR_NULL  # no output
+    assert f(FAKE, FAKE, NULL, NULL, *shape, *enc, NULL, NULL, FAKE, NULL, 2, 0, 0, NULL) == ERR_NULL  # q without scale
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, NULL, NULL, NULL, FAKE, 5, 0, 0, NULL) == ERR_BITS
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, NULL, NULL, NULL, FAKE + 4, 2, 0, 0, NULL) == ERR_ALIGN
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, 24, 0, NULL) == ERR_SHAPE  # no such tile
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, 0, 3, NULL) == ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, -1, 0, NULL) == ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, NULL, *shape, 2, 2, UNSIGNED, BIPOLAR, FAKE, NULL, NULL, NULL, 2, 0, 0, NULL) == ERR_ENCODING
 
 
 def test_pack_and_epilogue_reject_bad_arguments_before_launch(lib):

@@ -246,12 +246,10 @@ def calibrate(acc):
     return scale, bias
 
 
-def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w):
-    from paper_2207_08820_amd.stack import ConvStack
-
+def oracle_stack(oracle, config, layers, wbits, enc_w):
+    """Oracle pass, layer by layer, producing the frozen scale / bias arrays both sides use."""
     x0 = inputs.stack_input(config, layers)
     weights = inputs.stack_weights(config, layers, wbits, enc_w)
-    # oracle pass, layer by layer, producing the frozen scale / bias arrays both sides use
     ref_acc, ref_q, scales, biases = [], [], [], []
     for i, L in enumerate(layers):
         xin = x0 if L.src < 0 else ref_q[L.src]
@@ -261,20 +259,127 @@ def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w):
         hist = np.bincount(q.ravel(), minlength=4) / q.size
         assert hist.min() >= 0.05, (L.name, hist)  # the chain must not degenerate to a constant
         ref_acc.append(acc), ref_q.append(q), scales.append(s), biases.append(b)
-    stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=DEV)
-    stack.run(dev(x0.astype(np.uint8)))
+    return x0, weights, ref_acc, ref_q, scales, biases
+
+
+def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, graph=False):
+    from paper_2207_08820_amd.stack import ConvStack
+
+    x0, weights, ref_acc, ref_q, scales, biases = oracle_stack(oracle, config, layers, wbits, enc_w)
+    stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=DEV, fused=fused)
+    x0_dev = dev(x0.astype(np.uint8))
+    if graph:
+        stack.capture(x0_dev)
+    replays = 3 if graph else 1
+    for rep in range(replays):
+        if graph:
+            for pl in stack.layers:  # eager work between replays: wipe what the graph must rewrite
+                pl.acc.zero_(), pl.q.zero_(), pl.out_packed.zero_()
+            torch.cuda.synchronize()
+            stack.replay()
+        else:
+            stack.run(x0_dev)
+        torch.cuda.synchronize()
+        for i, L in enumerate(layers):
+            assert np.array_equal(stack.layers[i].acc.cpu().numpy(), ref_acc[i]), (L.name, rep)
+            assert np.array_equal(stack.layers[i].q.cpu().numpy(), ref_q[i]), (L.name, rep)
+            if fused:
+                want = oracle.pack_bitplanes(ref_q[i].reshape(-1, L.Co).astype(np.int8), 2, UNSIGNED)
+                assert np.array_equal(words(stack.layers[i].out_packed), want), (L.name, rep)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_config3_resnet18_stack_every_layer_bit_exact(dlrt, oracle, fused):
+    run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS, fused)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_config4_yolo_style_stack_bipolar_weights_every_layer_bit_exact(dlrt, oracle, fused):
+    run_stack_against_oracle(dlrt, oracle, 4, inputs.yolo_style_stack(), 1, BIPOLAR, fused)
+
+
+def test_config3_stack_as_hip_graph_every_replay_bit_exact(dlrt, oracle):
+    run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS, fused=True, graph=True)
+
+
+# ---- fused convolution: conv + scale/bias + requant + bitplanes of the result in one launch -------------
+def fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=0, ksplit=0, seed=0):
+    N, H, W_, Ci = x.shape
+    Co, KH, KW, _ = w.shape
+    ref = oracle.conv2d_i32(x, w, (stride, stride), (pad, pad))
+    scale, bias = calibrate(ref)
+    scale = (scale * (1 << qbits) / 4).astype(np.float32)  # spread over the 2^qbits levels
+    bias = (bias * (1 << qbits) / 4).astype(np.float32)
+    y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=qbits)
+    X = dlrt.dlrt_pack_bitplanes(src_tensor(x, ea), abits, ea)
+    Wp = dlrt.dlrt_pack_conv_weights(src_tensor(w, ew), wbits, ew)
+    Mo = ref.shape[0] * ref.shape[1] * ref.shape[2]
+    acc = torch.full(ref.shape, -7, dtype=torch.int32, device=DEV)
+    y = torch.full(ref.shape, -7.0, dtype=torch.float32, device=DEV)
+    q = torch.full(ref.shape, 99, dtype=torch.uint8, device=DEV)
+    packed = torch.full((Mo, qbits, (Co + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_conv2d_fused(X, Wp, dev(scale), dev(bias), N, H, W_, Ci, Co, KH, KW, (stride, stride),
+                                     (pad, pad), abits, wbits, ea, ew, qbits=qbits, out_acc=acc, out_f32=y, out_q=q,
+                                     out_packed=packed, tile_rows=tile_rows, ksplit=ksplit)
     torch.cuda.synchronize()
-    for i, L in enumerate(layers):
-        assert np.array_equal(stack.layers[i].acc.cpu().numpy(), ref_acc[i]), L.name
-        assert np.array_equal(stack.layers[i].q.cpu().numpy(), ref_q[i]), L.name
+    tag = (abits, wbits, ea, ew, qbits, tile_rows, ksplit)
+    assert np.array_equal(acc.cpu().numpy(), ref), tag
+    assert np.array_equal(y.cpu().numpy(), y_ref), tag
+    assert np.array_equal(q.cpu().numpy(), q_ref), tag
+    assert np.array_equal(words(packed), oracle.pack_bitplanes(q_ref.reshape(Mo, Co).astype(np.int8), qbits, UNSIGNED)), tag
 
 
-def test_config3_resnet18_stack_every_layer_bit_exact(dlrt, oracle):
-    run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS)
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_fused_edge_shapes_all_encodings(dlrt, oracle, shape):
+    N, H, W, Ci, Co, k, stride, pad = shape
+    cases = [(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2), (1, 1, UNSIGNED, TWOS, 1),
+             (4, 4, UNSIGNED, TWOS, 4), (3, 2, TWOS, UNSIGNED, 3), (2, 4, UNSIGNED, TWOS, 2), (3, 3, TWOS, TWOS, 2)]
+    for idx, (abits, wbits, ea, ew, qbits) in enumerate(cases):
+        x = inputs.uniform_values((N, H, W, Ci), abits, ea, 18000 + idx + H)
+        w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 19000 + idx + Ci)
+        fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits)
 
 
-def test_config4_yolo_style_stack_bipolar_weights_every_layer_bit_exact(dlrt, oracle):
-    run_stack_against_oracle(dlrt, oracle, 4, inputs.yolo_style_stack(), 1, BIPOLAR)
+def test_conv_fused_every_tile_height_and_reduction_split_gives_the_same_result(dlrt, oracle):
+    """The tuning hints select the wave tile and how many waves split the reduction; all must agree."""
+    x = inputs.uniform_values((1, 13, 11, 160), 2, UNSIGNED, 777)
+    w = inputs.uniform_values((72, 3, 3, 160), 2, TWOS, 778)
+    for tile_rows in (8, 16, 32):
+        for ksplit in (1, 2, 4, 8):
+            fused_case(dlrt, oracle, x, w, 1, 1, 2, 2, UNSIGNED, TWOS, 2, tile_rows, ksplit)
+    x4 = inputs.uniform_values((1, 9, 9, 96), 4, UNSIGNED, 779)
+    w4 = inputs.uniform_values((40, 3, 3, 96), 4, TWOS, 780)
+    for tile_rows in (4, 8):
+        for ksplit in (1, 2, 4):  # 8 slices of a 4-bit x 4-bit tile would need more than 64 KB of LDS
+            fused_case(dlrt, oracle, x4, w4, 2, 1, 4, 4, UNSIGNED, TWOS, 3, tile_rows, ksplit)
+    xb = inputs.uniform_values((2, 6, 6, 64), 2, UNSIGNED, 781)
+    wb = inputs.uniform_values((33, 3, 3, 64), 1, BIPOLAR, 782)
+    for ksplit in (1, 2, 4):
+        fused_case(dlrt, oracle, xb, wb, 1, 1, 2, 1, UNSIGNED, BIPOLAR, 2, 8, ksplit)
+
+
+def test_conv_fused_rejects_hints_the_kernels_do_not_have(dlrt):
+    X = torch.zeros((64, 4, 1), dtype=torch.int32, device=DEV)
+    Wp = torch.zeros((8, 4, 9), dtype=torch.int32, device=DEV)
+    acc = torch.zeros((1, 8, 8, 8), dtype=torch.int32, device=DEV)
+    for tile_rows, ksplit in ((24, 0), (0, 3), (16, 0)):  # 16 rows needs too many accumulators at A4W4
+        with pytest.raises(dlrt.DlrtError) as e:
+            dlrt.dlrt_bitserial_conv2d_fused(X, Wp, None, None, 1, 8, 8, 32, 8, 3, 3, (1, 1), (1, 1), 4, 4, UNSIGNED,
+                                             TWOS, out_acc=acc, tile_rows=tile_rows, ksplit=ksplit)
+        assert e.value.code == 3
+
+
+# ---- GEMM through both kernels: large shapes take the block kernel, small ones the per-wave kernel ----
+def test_gemm_ragged_large_shape_block_kernel(dlrt, oracle):
+    for abits, wbits, ea, ew, M, N, K in [(2, 2, UNSIGNED, TWOS, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 2900, 2950, 96),
+                                          (4, 4, UNSIGNED, TWOS, 730, 750, 50), (3, 3, TWOS, TWOS, 760, 710, 330),
+                                          (1, 1, UNSIGNED, TWOS, 3000, 2900, 70)]:
+        a = inputs.uniform_values((M, K), abits, ea, 31000 + M)
+        w = inputs.uniform_values((N, K), wbits, ew, 32000 + N)
+        got = gpu_gemm(dlrt, a, w, abits, wbits, ea, ew)
+        assert np.array_equal(got, a.astype(np.int64) @ w.astype(np.int64).T), (abits, wbits)
+        rows = rng(M).choice(M, size=16, replace=False)
+        assert np.array_equal(got[rows], oracle.gemm_i32(a[rows], w))
 
 
 # ---- error handling with real buffers ------------------------------------------------------------------
