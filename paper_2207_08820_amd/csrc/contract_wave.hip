@@ -167,6 +167,15 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const ContractArgs g
             for (int n = 0; n < NG; ++n) acc[r][j][n] = 0;
         }
 
+    // scale / bias of this lane's columns: fetched now so that their latency hides behind the reduction
+    float sc[TN], bs[TN];
+#pragma unroll
+    for (int s = 0; s < TN; ++s) {
+        const int n = min(n0 + lx * TN + s, g.N - 1);
+        sc[s] = (o.scale && ks == 0) ? o.scale[n] : 0.0f;
+        bs[s] = (o.bias && ks == 0) ? o.bias[n] : 0.0f;
+    }
+
     // this wave's slice of the reduction, in steps of 4 words
     const int steps = (g.Kw + 3) / 4;
     const int s_begin = min(ks * steps_per_wave, steps), s_end = min(s_begin + steps_per_wave, steps);
@@ -286,7 +295,7 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const ContractArgs g
                 const size_t idx = (size_t)m * g.N + n;
                 if (o.acc) o.acc[idx] = total[r][s];
                 if (o.scale) {
-                    const float y = __fmaf_rn((float)total[r][s], o.scale[n], o.bias ? o.bias[n] : 0.0f);
+                    const float y = __fmaf_rn((float)total[r][s], sc[s], bs[s]);
                     if (o.y) o.y[idx] = y;
                     q[s] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
                     if (o.q) o.q[idx] = (uint8_t)q[s];
