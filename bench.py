@@ -20,6 +20,11 @@ import numpy as np
 
 # plain 32-bit VALU rate of the chip: 256 compute units x 64 lanes per clock x 2.4 GHz
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
+# HBM bytes per launch of the 4096^3 A2W2 GEMM kernel, from the committed rocprofv3 --pmc runs
+# (profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md): FETCH_SIZE 18929 KiB x 2.000 (calibration
+# against a plain 256 MiB copy) + WRITE_SIZE 65536 KiB.  Counters cannot be read from inside this
+# script, so the figure is only reported for the exact workload it was measured on.
+GEMM_4096_A2W2_TRAFFIC_BYTES = int((18929 * 2.0 + 65536) * 1024)
 
 
 def log(*a):
@@ -77,10 +82,10 @@ def make_step(dlrt, t, gemm_events=None):
     return step
 
 
-def resnet18_stack_ms(dlrt, dev, iters=50):
-    """Whole ResNet-18 A2W2 conv chain (19 convs).  Scale and bias come from the closed-form mean /
-    deviation of a uniform-input layer (mean -0.75 K, sigma 2.165 sqrt(K)); timing does not depend on
-    the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
+def stack_ms(dlrt, dev, which, iters=50):
+    """Whole conv chain of a model-shaped stack ("resnet18": 19 convs A2W2; "yolo": 16 convs A2 / bipolar
+    W1).  Scale and bias come from the closed-form mean / deviation of a uniform-input layer; timing
+    does not depend on the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
     conv launch per layer), the same chain enqueued eagerly from Python, and the unfused chain
     (pack + conv + epilogue per layer); per-layer times are of the fused kernel alone."""
     import torch
@@ -88,14 +93,19 @@ def resnet18_stack_ms(dlrt, dev, iters=50):
     from paper_2207_08820_amd import inputs
     from paper_2207_08820_amd.stack import ConvStack
 
-    layers = inputs.resnet18_stack()
-    weights = inputs.stack_weights(3, layers, 2, inputs.TWOS)
-    scales = [np.full(L.Co, 1.0 / (2.165 * np.sqrt(L.K)), np.float32) for L in layers]
-    biases = [np.full(L.Co, 1.5 + 0.75 * L.K / (2.165 * np.sqrt(L.K)), np.float32) for L in layers]
-    x0 = torch.as_tensor(inputs.stack_input(3, layers).astype(np.uint8), device=dev)
+    if which == "resnet18":
+        config, layers, wbits, enc_w = 3, inputs.resnet18_stack(), 2, inputs.TWOS
+        mean, sigma = -0.75, 2.165  # per sqrt(K) / per K of a uniform {0..3} x {-2..1} product
+    else:
+        config, layers, wbits, enc_w = 4, inputs.yolo_style_stack(), 1, inputs.BIPOLAR
+        mean, sigma = 0.0, 1.871    # uniform {0..3} x {-1,+1}: mean 0, E[a^2] = 3.5
+    weights = inputs.stack_weights(config, layers, wbits, enc_w)
+    scales = [np.full(L.Co, 1.0 / (sigma * np.sqrt(L.K)), np.float32) for L in layers]
+    biases = [np.full(L.Co, 1.5 - mean * L.K / (sigma * np.sqrt(L.K)), np.float32) for L in layers]
+    x0 = torch.as_tensor(inputs.stack_input(config, layers).astype(np.uint8), device=dev)
     out = {}
 
-    stack = ConvStack(layers, weights, scales, biases, 2, 2, inputs.TWOS, device=dev, fused=True, keep_outputs=False)
+    stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=True, keep_outputs=False)
     stack.capture(x0)
     for _ in range(5):
         stack.replay()
@@ -108,7 +118,7 @@ def resnet18_stack_ms(dlrt, dev, iters=50):
         ms = time_events(lambda: stack.run_layer_fused(i, xin), iters)
         per_layer.append({"layer": pl.spec.name, "M": pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K, "ms": round(ms, 5)})
 
-    unfused = ConvStack(layers, weights, scales, biases, 2, 2, inputs.TWOS, device=dev, fused=False)
+    unfused = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=False)
     for _ in range(3):
         unfused.run(x0)
     torch.cuda.synchronize()
@@ -199,18 +209,25 @@ def main():
     achieved = lane_ops / (gemm_ms * 1e-3)
     roofline = {"bound": "alu", "kernel": "contract_kernel (dlrt_bitserial_gemm)",
                 "achieved": round(achieved / 1e12, 4), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 4),
-                "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_LANE_OPS, 4), "traffic": None,
+                "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_LANE_OPS, 4),
+                "traffic": GEMM_4096_A2W2_TRAFFIC_BYTES if args.size == 4096 else None,
+                "algorithmic_bytes": 4 * c.M * c.N + (abits * c.M + wbits * c.N) * ((c.K + 31) // 32) * 4,
                 "kernel_ms": round(gemm_ms, 5),
                 "kernel_effective_tops": round(2.0 * macs / (gemm_ms * 1e-3) / 1e12, 3)}
     log(f"step {ms_per_step:.4f} ms, gemm kernel {gemm_ms:.4f} ms, {value:.2f} effective TOPS, "
         f"VALU roofline {roofline['frac']:.3f}")
 
     extra = {}
-    stack_ms, per_layer = resnet18_stack_ms(dlrt, dev)
-    extra["resnet18_a2w2_conv_stack_ms"] = round(stack_ms["graph_fused_ms"], 5)
-    extra["resnet18_a2w2_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in stack_ms.items()}
+    r18, per_layer = stack_ms(dlrt, dev, "resnet18")
+    extra["resnet18_a2w2_conv_stack_ms"] = round(r18["graph_fused_ms"], 5)
+    extra["resnet18_a2w2_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in r18.items()}
     extra["resnet18_per_layer"] = per_layer
-    log(f"ResNet-18 A2W2 conv stack (19 convs): {stack_ms}")
+    log(f"ResNet-18 A2W2 conv stack (19 convs): {r18}")
+    yolo, per_layer = stack_ms(dlrt, dev, "yolo")
+    extra["yolo_style_a2w1_conv_stack_ms"] = round(yolo["graph_fused_ms"], 5)
+    extra["yolo_style_a2w1_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in yolo.items()}
+    extra["yolo_style_per_layer"] = per_layer
+    log(f"YOLOv5s-style A2W1 conv stack (16 convs): {yolo}")
 
     if args.sweep:
         from paper_2207_08820_amd import inputs
