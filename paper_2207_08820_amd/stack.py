@@ -33,40 +33,58 @@ class PackedLayer:
     out_packed: torch.Tensor = None  # fused: packed requantized output = input of the consumers
 
 
+def _per_layer(v, n):
+    return list(v) if isinstance(v, (list, tuple)) else [v] * n
+
+
 class ConvStack:
-    def __init__(self, layers, weights_i8, scales, biases, abits: int, wbits: int, enc_w: int, device="cuda:0",
+    """abits / wbits / enc_w are one value for the whole stack or one per layer (mixed precision, as in
+    the paper's per-layer precision choice).  A layer's output is requantized to the activation width
+    of the layers that read it (they must agree); a layer nobody reads keeps its own width."""
+
+    def __init__(self, layers, weights_i8, scales, biases, abits, wbits, enc_w, device="cuda:0",
                  fused: bool = True, keep_outputs: bool = True):
-        self.abits, self.wbits, self.enc_w = abits, wbits, enc_w
+        n = len(layers)
+        self.abits, self.wbits, self.enc_w = _per_layer(abits, n), _per_layer(wbits, n), _per_layer(enc_w, n)
+        self.qbits = list(self.abits)
+        for i in range(n):
+            readers = {self.abits[j] for j in range(n) if layers[j].src == i}
+            if len(readers) > 1:
+                raise ValueError(f"layers reading layer {i} disagree on its activation width: {readers}")
+            if readers:
+                self.qbits[i] = readers.pop()
         self.fused, self.keep = fused, keep_outputs
         self.device = torch.device(device)
         self.layers = []
         self.graph = None
-        for L, w, s, b in zip(layers, weights_i8, scales, biases):
+        for i, (L, w, s, b) in enumerate(zip(layers, weights_i8, scales, biases)):
             wt = torch.as_tensor(w, device=self.device)
-            wp = binding.dlrt_pack_conv_weights(wt, wbits, enc_w)
+            wp = binding.dlrt_pack_conv_weights(wt, self.wbits[i], self.enc_w[i])
             pl = PackedLayer(L, wp, torch.as_tensor(s, device=self.device),
                              None if b is None else torch.as_tensor(b, device=self.device))
             if fused:
-                pl.out_packed = torch.empty((L.Ho * L.Wo, abits, (L.Co + 31) // 32), dtype=torch.int32,
+                pl.out_packed = torch.empty((L.Ho * L.Wo, self.qbits[i], (L.Co + 31) // 32), dtype=torch.int32,
                                             device=self.device)
             else:
-                pl.xp = torch.empty((L.H * L.W, abits, (L.Ci + 31) // 32), dtype=torch.int32, device=self.device)
+                pl.xp = torch.empty((L.H * L.W, self.abits[i], (L.Ci + 31) // 32), dtype=torch.int32,
+                                    device=self.device)
             if keep_outputs or not fused:
                 pl.acc = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.int32, device=self.device)
                 pl.q = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.uint8, device=self.device)
             self.layers.append(pl)
         L0 = layers[0]
-        self.x0_packed = torch.empty((L0.H * L0.W, abits, (L0.Ci + 31) // 32), dtype=torch.int32, device=self.device)
+        self.x0_packed = torch.empty((L0.H * L0.W, self.abits[0], (L0.Ci + 31) // 32), dtype=torch.int32,
+                                     device=self.device)
 
     # ---- unfused: three launches per layer ----
     def run_layer(self, i: int, x_u8: torch.Tensor):
         pl = self.layers[i]
         L = pl.spec
-        binding.dlrt_pack_bitplanes(x_u8, self.abits, binding.UNSIGNED, out=pl.xp)
+        binding.dlrt_pack_bitplanes(x_u8, self.abits[i], binding.UNSIGNED, out=pl.xp)
         binding.dlrt_bitserial_conv2d(pl.xp, pl.wp, 1, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
-                                      (L.pad, L.pad), self.abits, self.wbits, binding.UNSIGNED, self.enc_w,
+                                      (L.pad, L.pad), self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
                                       out=pl.acc)
-        binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=False, qbits=self.abits, out_q=pl.q)
+        binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=False, qbits=self.qbits[i], out_q=pl.q)
 
     # ---- fused: one launch per layer ----
     def run_layer_fused(self, i: int, x_packed: torch.Tensor, tile_rows: int = 0, ksplit: int = 0):
@@ -74,7 +92,8 @@ class ConvStack:
         L = pl.spec
         binding.dlrt_bitserial_conv2d_fused(pl.xp if x_packed is None else x_packed, pl.wp, pl.scale, pl.bias,
                                             1, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride), (L.pad, L.pad),
-                                            self.abits, self.wbits, binding.UNSIGNED, self.enc_w, qbits=self.abits,
+                                            self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
+                                            qbits=self.qbits[i],
                                             out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
                                             out_packed=pl.out_packed, tile_rows=tile_rows, ksplit=ksplit)
 
@@ -87,7 +106,7 @@ class ConvStack:
         if self.fused:
             # one stream on purpose: forking the side-branch 1x1 convs onto a second stream was
             # measured slower (0.170 against 0.128 ms), the cross-queue waits cost more than they hide
-            binding.dlrt_pack_bitplanes(x0_u8, self.abits, binding.UNSIGNED, out=self.x0_packed)
+            binding.dlrt_pack_bitplanes(x0_u8, self.abits[0], binding.UNSIGNED, out=self.x0_packed)
             for i in range(len(self.layers)):
                 self.run_layer_fused(i, self.layer_input(i))
         else:

@@ -246,27 +246,39 @@ def calibrate(acc):
     return scale, bias
 
 
-def oracle_stack(oracle, config, layers, wbits, enc_w):
-    """Oracle pass, layer by layer, producing the frozen scale / bias arrays both sides use."""
-    x0 = inputs.stack_input(config, layers)
-    weights = inputs.stack_weights(config, layers, wbits, enc_w)
+def oracle_stack(oracle, config, layers, wbits, enc_w, abits=2):
+    """Oracle pass, layer by layer, producing the frozen scale / bias arrays both sides use.  abits,
+    wbits and enc_w are one value or one per layer; a layer's output takes the width its readers expect."""
+    n = len(layers)
+    ab = list(abits) if isinstance(abits, (list, tuple)) else [abits] * n
+    wb = list(wbits) if isinstance(wbits, (list, tuple)) else [wbits] * n
+    ew = list(enc_w) if isinstance(enc_w, (list, tuple)) else [enc_w] * n
+    qb = [next((ab[j] for j in range(n) if layers[j].src == i), ab[i]) for i in range(n)]
+    L0 = layers[0]
+    x0 = inputs.uniform_values((1, L0.H, L0.W, L0.Ci), ab[0], UNSIGNED, inputs.seed_for(config, 0))
+    weights = [inputs.uniform_values((L.Co, L.k, L.k, L.Ci), wb[i], ew[i], inputs.seed_for(config, 1, layer=i))
+               for i, L in enumerate(layers)]
     ref_acc, ref_q, scales, biases = [], [], [], []
     for i, L in enumerate(layers):
         xin = x0 if L.src < 0 else ref_q[L.src]
         acc = oracle.conv2d_i32(xin.astype(np.int8), weights[i], (L.stride, L.stride), (L.pad, L.pad))
         s, b = calibrate(acc)
-        _, q = oracle.epilogue_f32(acc, s, b, qbits=2)
-        hist = np.bincount(q.ravel(), minlength=4) / q.size
-        assert hist.min() >= 0.05, (L.name, hist)  # the chain must not degenerate to a constant
+        levels = 1 << qb[i]
+        s, b = (s * levels / 4).astype(np.float32), (b * levels / 4).astype(np.float32)
+        _, q = oracle.epilogue_f32(acc, s, b, qbits=qb[i])
+        hist = np.bincount(q.ravel(), minlength=levels) / q.size
+        # the chain must not degenerate to a constant: the values stay spread over the levels
+        assert hist.max() < 0.75 and (hist >= 0.02).sum() >= min(levels, 4), (L.name, hist)
         ref_acc.append(acc), ref_q.append(q), scales.append(s), biases.append(b)
-    return x0, weights, ref_acc, ref_q, scales, biases
+    return x0, weights, ref_acc, ref_q, scales, biases, qb
 
 
-def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, graph=False):
+def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, graph=False, abits=2):
     from paper_2207_08820_amd.stack import ConvStack
 
-    x0, weights, ref_acc, ref_q, scales, biases = oracle_stack(oracle, config, layers, wbits, enc_w)
-    stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=DEV, fused=fused)
+    x0, weights, ref_acc, ref_q, scales, biases, qb = oracle_stack(oracle, config, layers, wbits, enc_w, abits)
+    stack = ConvStack(layers, weights, scales, biases, abits, wbits, enc_w, device=DEV, fused=fused)
+    assert stack.qbits == qb
     x0_dev = dev(x0.astype(np.uint8))
     if graph:
         stack.capture(x0_dev)
@@ -284,7 +296,7 @@ def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, 
             assert np.array_equal(stack.layers[i].acc.cpu().numpy(), ref_acc[i]), (L.name, rep)
             assert np.array_equal(stack.layers[i].q.cpu().numpy(), ref_q[i]), (L.name, rep)
             if fused:
-                want = oracle.pack_bitplanes(ref_q[i].reshape(-1, L.Co).astype(np.int8), 2, UNSIGNED)
+                want = oracle.pack_bitplanes(ref_q[i].reshape(-1, L.Co).astype(np.int8), qb[i], UNSIGNED)
                 assert np.array_equal(words(stack.layers[i].out_packed), want), (L.name, rep)
 
 
@@ -296,6 +308,28 @@ def test_config3_resnet18_stack_every_layer_bit_exact(dlrt, oracle, fused):
 @pytest.mark.parametrize("fused", [False, True])
 def test_config4_yolo_style_stack_bipolar_weights_every_layer_bit_exact(dlrt, oracle, fused):
     run_stack_against_oracle(dlrt, oracle, 4, inputs.yolo_style_stack(), 1, BIPOLAR, fused)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_resnet18_stack_1a2w_as_in_the_papers_vww_experiment(dlrt, oracle, fused):
+    """1-bit activations with 2-bit weights, the paper's second ResNet18 precision (Section VII-A)."""
+    run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS, fused, abits=1)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_resnet18_stack_mixed_precision_per_layer(dlrt, oracle, fused):
+    """Per-layer precision lists (the paper keeps sensitive layers at higher precision, Section VII-D):
+    stage 0 at A4W4, stage 1 at A3W2 unsigned weights, stage 2 at A2W2, stage 3 at A2 with bipolar W1."""
+    layers = inputs.resnet18_stack()
+    ab, wb, ew = [], [], []
+    for L in layers:
+        stage = int(L.name[1])
+        a, w, e = [(4, 4, TWOS), (3, 2, UNSIGNED), (2, 2, TWOS), (2, 1, BIPOLAR)][stage]
+        # a stage's first convs read the previous stage's output: they take that stage's activation width
+        if stage > 0 and (L.name.endswith("b0c0_3x3") or "down" in L.name):
+            a = [4, 3, 2][stage - 1]
+        ab.append(a), wb.append(w), ew.append(e)
+    run_stack_against_oracle(dlrt, oracle, 3, layers, wb, ew, fused, abits=ab)
 
 
 def test_config3_stack_as_hip_graph_every_replay_bit_exact(dlrt, oracle):
