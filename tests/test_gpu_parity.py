@@ -416,6 +416,29 @@ def test_gemm_ragged_large_shape_block_kernel(dlrt, oracle):
         assert np.array_equal(got[rows], oracle.gemm_i32(a[rows], w))
 
 
+# ---- comparison variant: int8 matrix-instruction GEMM on the unpacked values ----------------------------
+@pytest.mark.parametrize("M,N,K", [(128, 128, 128), (1, 1, 16), (200, 300, 208), (130, 70, 1040), (512, 512, 512)])
+def test_unpacked_gemm_i8_matches_oracle(dlrt, oracle, M, N, K):
+    r = rng(M * 7 + N)
+    for lo, hi in ((0, 4), (-2, 2), (-8, 16), (-128, 128)):
+        a = r.integers(lo, hi, size=(M, K)).astype(np.int8)
+        w = r.integers(lo, hi, size=(N, K)).astype(np.int8)
+        got = dlrt.dlrt_unpacked_gemm_i8(dev(a), dev(w))
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.gemm_i32(a, w)), (lo, hi)
+
+
+def test_unpacked_gemm_i8_agrees_with_the_bit_serial_gemm_at_full_size(dlrt, oracle):
+    c, a, w = inputs.config5(2, 2)
+    got = dlrt.dlrt_unpacked_gemm_i8(dev(a.astype(np.int8)), dev(w))
+    ref = gpu_gemm(dlrt, a, w, 2, 2, c.enc_a, c.enc_w)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    rows = rng(56).choice(c.M, size=32, replace=False)
+    assert np.array_equal(got[rows], oracle.gemm_i32(a[rows], w))
+    assert np.array_equal(got, ref)
+
+
 # ---- error handling with real buffers ------------------------------------------------------------------
 def test_errors_raise_and_launch_nothing(dlrt):
     a = torch.zeros((4, 2, 1), dtype=torch.int32, device=DEV)
