@@ -30,6 +30,13 @@
 #ifndef DLRT_ABITS
 #error "compile with -DDLRT_ABITS=1..4"
 #endif
+// Tuning knobs of the block kernel (the defaults are the measured best, see the GEMM profile summary).
+#ifndef DLRT_WAVES_PER_EU
+#define DLRT_WAVES_PER_EU 2
+#endif
+#ifndef DLRT_REG_DOUBLE_BUFFER
+#define DLRT_REG_DOUBLE_BUFFER 1
+#endif
 
 namespace {
 
@@ -61,7 +68,7 @@ struct SlotMap {
 // parameter rather than a run-time branch: the optimiser merges run-time variants of the same
 // load into the narrowest one.
 template <int AB, int WB, int TM, int TN, int VEC, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(kThreads, 2) void contract_kernel(const ContractArgs g)
+__global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(const ContractArgs g)
 {
     constexpr int BM = 16 * TM, BN = 16 * TN;
     using MapA = SlotMap<AB, BM>;
@@ -241,6 +248,7 @@ __global__ __launch_bounds__(kThreads, 2) void contract_kernel(const ContractArg
                     }
             }
         };
+#if DLRT_REG_DOUBLE_BUFFER
         lds_load(0, 0);
 #pragma unroll
         for (int k4 = 0; k4 < kK4; ++k4) {
@@ -248,6 +256,14 @@ __global__ __launch_bounds__(kThreads, 2) void contract_kernel(const ContractArg
             mac(k4 & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
+#else
+#pragma unroll
+        for (int k4 = 0; k4 < kK4; ++k4) {
+            lds_load(0, k4);
+            mac(0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#endif
 
         if (chunk + 1 < nchunks) commit(buf ^ 1);
         __syncthreads();
