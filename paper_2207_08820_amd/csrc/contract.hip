@@ -30,12 +30,19 @@
 #ifndef DLRT_ABITS
 #error "compile with -DDLRT_ABITS=1..4"
 #endif
-// Tuning knobs of the block kernel (the defaults are the measured best, see the GEMM profile summary).
+// Tuning knobs of the block kernel.  Measured at 4096^3, fraction of the VALU roofline for the pairs
+// (1,1) (2,2) (3,3) (4,4) (2,4), 20 back-to-back launches each:
+//   2 waves/SIMD, operands read one 16-byte step ahead (register double buffer): .78 .88 .92 .95 .93
+//   2 waves/SIMD, operands read at the top of each step (the default):           .80 .90 .96 .96 .93
+//   3 waves/SIMD (168 registers), no double buffer (spills at 2 x 2 bits):       .74 .85 .96 .94 .89
+//   3 waves/SIMD with the double buffer (spills everywhere):                     .52 .63 .85 .73 .69
+// With two waves per SIMD the other wave covers the LDS latency, and the smaller live range lets the
+// register allocator keep everything else in registers.
 #ifndef DLRT_WAVES_PER_EU
 #define DLRT_WAVES_PER_EU 2
 #endif
 #ifndef DLRT_REG_DOUBLE_BUFFER
-#define DLRT_REG_DOUBLE_BUFFER 1
+#define DLRT_REG_DOUBLE_BUFFER 0
 #endif
 
 namespace {
@@ -211,10 +218,10 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
 
         const uint4 *la = ldsA + buf * kTileA + ty;
         const uint4 *lw = ldsW + buf * kTileW + tx;
-        // Register double buffer over the four 16-byte steps of a chunk: the LDS reads of step
-        // k4 + 1 are issued before the AND/BCNT block of step k4 and consumed after it.  The
-        // scheduling barrier keeps the compiler from hoisting every read of the chunk to the
-        // top, which would need four times the operand registers.
+        // Four 16-byte steps per chunk.  The scheduling barrier after each step keeps the compiler
+        // from hoisting every LDS read of the chunk to the top, which would need four times the
+        // operand registers (and spills).  Optionally the reads of step k4 + 1 are issued before
+        // the AND/BCNT block of step k4 (register double buffer).
         uint4 av[2][TM][AB], wv[2][TN][WB];
         auto lds_load = [&](int b, int k4) {
 #pragma unroll
