@@ -38,6 +38,10 @@
 //   3 waves/SIMD with the double buffer (spills everywhere):                     .52 .63 .85 .73 .69
 // With two waves per SIMD the other wave covers the LDS latency, and the smaller live range lets the
 // register allocator keep everything else in registers.
+// Also measured and dropped: persistent blocks (512 resident blocks walking the 4096 tiles with a fixed
+// stride, with and without fetching the next tile's first chunk during the current tile's last one):
+// .74 .82 .83 .87 .85 either way.  One block per tile lets the hardware hand tiles to whichever compute
+// unit frees up first, which is worth more than the saved set-up.
 #ifndef DLRT_WAVES_PER_EU
 #define DLRT_WAVES_PER_EU 2
 #endif
