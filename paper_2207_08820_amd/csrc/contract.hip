@@ -41,7 +41,8 @@
 // Also measured and dropped: persistent blocks (512 resident blocks walking the 4096 tiles with a fixed
 // stride, with and without fetching the next tile's first chunk during the current tile's last one):
 // .74 .82 .83 .87 .85 either way.  One block per tile lets the hardware hand tiles to whichever compute
-// unit frees up first, which is worth more than the saved set-up.
+// unit frees up first, which is worth more than the saved set-up.  Half-height lane tiles (twice as many,
+// shorter blocks): .77 .86 .91 .95 .91, no better.
 #ifndef DLRT_WAVES_PER_EU
 #define DLRT_WAVES_PER_EU 2
 #endif
