@@ -3,8 +3,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--sweep]
 
 A step is one pass of the whole path over one batch of synthetic input that is already resident
-in HBM: bitplane-pack the uint8 activations and the int8 weights, bit-serial GEMM into int32, and
-the per-channel fp32 scale epilogue.  The workload is the 4096^3 A2W2 GEMM the headline metric is
+in HBM: bitplane-pack the uint8 activations and the int8 weights, bit-serial GEMM accumulating in int32, and
+the per-channel fp32 scale epilogue (fused into the GEMM kernel; the unfused step is timed as well).  The workload is the 4096^3 A2W2 GEMM the headline metric is
 quoted on (activations unsigned 2-bit, weights two's-complement 2-bit).  The ResNet-18 A2W2 conv
 stack latency, the second half of the metric, is reported in the same JSON line under "extra".
 Prints ONE JSON line on stdout; everything else goes to stderr.
@@ -21,10 +21,10 @@ import numpy as np
 # plain 32-bit VALU rate of the chip: 256 compute units x 64 lanes per clock x 2.4 GHz
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
 # HBM bytes per launch of the 4096^3 A2W2 GEMM kernel, from the committed rocprofv3 --pmc runs
-# (profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md): FETCH_SIZE 18929 KiB x 2.000 (calibration
+# (profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md): FETCH_SIZE 18700 KiB x 2.000 (calibration
 # against a plain 256 MiB copy) + WRITE_SIZE 65536 KiB.  Counters cannot be read from inside this
 # script, so the figure is only reported for the exact workload it was measured on.
-GEMM_4096_A2W2_TRAFFIC_BYTES = int((18929 * 2.0 + 65536) * 1024)
+GEMM_4096_A2W2_TRAFFIC_BYTES = int((18700 * 2.0 + 65536) * 1024)
 
 
 def log(*a):
@@ -62,7 +62,10 @@ def gemm_workload(abits, wbits, size, dev):
     return t
 
 
-def make_step(dlrt, t, gemm_events=None):
+def make_step(dlrt, t, gemm_events=None, fused=True):
+    """One pass of the path: pack A, pack W, bit-serial GEMM, fp32 scale epilogue.  fused: the epilogue
+    runs inside the GEMM kernel (dlrt_bitserial_gemm_fused writes the fp32 result directly); otherwise the
+    int32 accumulators go through HBM to dlrt_epilogue_f32."""
     c = t["c"]
 
     def step():
@@ -73,11 +76,16 @@ def make_step(dlrt, t, gemm_events=None):
 
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-        dlrt.dlrt_bitserial_gemm(t["A"], t["W"], c.M, c.N, c.K, c.abits, c.wbits, c.enc_a, c.enc_w, out=t["C"])
+        if fused:
+            dlrt.dlrt_bitserial_gemm_fused(t["A"], t["W"], t["scale"], None, c.M, c.N, c.K, c.abits, c.wbits, c.enc_a,
+                                           c.enc_w, out_f32=t["Y"])
+        else:
+            dlrt.dlrt_bitserial_gemm(t["A"], t["W"], c.M, c.N, c.K, c.abits, c.wbits, c.enc_a, c.enc_w, out=t["C"])
         if gemm_events is not None:
             e1.record()
             gemm_events.append((e0, e1))
-        dlrt.dlrt_epilogue_f32(t["C"], t["scale"], out_f32=t["Y"])
+        if not fused:
+            dlrt.dlrt_epilogue_f32(t["C"], t["scale"], out_f32=t["Y"])
 
     return step
 
@@ -207,7 +215,7 @@ def main():
     value = 2.0 * macs / (ms_per_step * 1e-3) / 1e12
     lane_ops = abits * wbits * macs / 16.0  # one AND + one BCNT per plane pair per 32 elements
     achieved = lane_ops / (gemm_ms * 1e-3)
-    roofline = {"bound": "alu", "kernel": "contract_kernel (dlrt_bitserial_gemm)",
+    roofline = {"bound": "alu", "kernel": "contract_kernel (dlrt_bitserial_gemm_fused)",
                 "achieved": round(achieved / 1e12, 4), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 4),
                 "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_LANE_OPS, 4),
                 "traffic": GEMM_4096_A2W2_TRAFFIC_BYTES if args.size == 4096 else None,
@@ -218,6 +226,11 @@ def main():
         f"VALU roofline {roofline['frac']:.3f}")
 
     extra = {}
+    unfused = make_step(dlrt, t, fused=False)
+    for _ in range(3):
+        unfused()
+    torch.cuda.synchronize()
+    extra["unfused_step_ms"] = round(time_events(unfused, 20), 5)
     r18, per_layer = stack_ms(dlrt, dev, "resnet18")
     extra["resnet18_a2w2_conv_stack_ms"] = round(r18["graph_fused_ms"], 5)
     extra["resnet18_a2w2_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in r18.items()}
@@ -276,7 +289,7 @@ def main():
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
            "data": "synthetic",
            "config": {"workload": f"gemm_{c.M}x{c.N}x{c.K}_A{abits}W{wbits} (bit-width sweep config, pair (2,2)): "
-                                  "pack A + pack W + bit-serial GEMM + fp32 scale epilogue",
+                                  "pack A + pack W + bit-serial GEMM with the fp32 scale epilogue fused in",
                       "abits": abits, "wbits": wbits, "enc_a": "unsigned", "enc_w": "twos_complement"},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:

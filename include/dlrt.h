@@ -97,6 +97,20 @@ dlrt_status dlrt_bitserial_gemm(const uint32_t *A, const uint32_t *W, int32_t *C
                                 dlrt_encoding enc_a, dlrt_encoding enc_w, void *stream);
 
 /*
+ * dlrt_bitserial_gemm with the epilogue of Section IV fused in (one launch, the int32 tensor need not
+ * be written):  acc = the int32 result above;  y = fmaf((float)acc, scale[n], bias ? bias[n] : 0.0f);
+ * q = (uint8) min(max(rint(y), 0), 2^qbits - 1);  out_packed = bitplanes of q, [M][qbits][ceil(N/32)]
+ * words (what dlrt_pack_bitplanes would make of q).  Any of the four outputs may be NULL, not all;
+ * scale [N] is required unless only out_acc is given; bias [N] may be NULL; qbits in 1..4 is read when
+ * out_q or out_packed is given; out_packed must be 16-byte aligned.
+ */
+dlrt_status dlrt_bitserial_gemm_fused(const uint32_t *A, const uint32_t *W, const float *scale,
+                                      const float *bias, int64_t M, int64_t N, int64_t K, int abits,
+                                      int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w, int32_t *out_acc,
+                                      float *out_f32, uint8_t *out_q, uint32_t *out_packed, int qbits,
+                                      void *stream);
+
+/*
  * Bit-serial convolution (Section V: the convolution's dot products computed bit-serially), as an
  * implicit im2col over packed NHWC activations; zero padding (an out-of-image tap contributes 0,
  * also for bipolar weights).
@@ -121,8 +135,9 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  *                would write, i.e. the next layer's X.
  * Any of out_acc, out_f32, out_q, out_packed may be NULL, not all of them; scale is required unless
  * only out_acc is given; bias may be NULL; qbits in 1..4 (read when out_q or out_packed is given).
- * out_packed must be 16-byte aligned.  tile_rows and ksplit are tuning hints: 0 lets the library
- * plan; otherwise tile_rows is the number of output pixels per wave tile (8, 16 or 32 for
+ * out_packed must be 16-byte aligned.  tile_rows and ksplit are tuning hints for the latency-oriented
+ * kernel that small layers get: 0 lets the library plan (large problems then take the throughput kernel,
+ * which has no hints); otherwise tile_rows is the number of output pixels per wave tile (8, 16 or 32 for
  * wbits <= 2; 4, 8 or 16 for wbits >= 3) and ksplit (1, 2, 4, 8) the number of waves that split the
  * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
  * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  The result does not depend on the hints.

@@ -48,6 +48,8 @@ def load():
     lib.dlrt_pack_conv_weights.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.dlrt_bitserial_gemm.restype = i32
     lib.dlrt_bitserial_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
+    lib.dlrt_bitserial_gemm_fused.restype = i32
+    lib.dlrt_bitserial_gemm_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
     lib.dlrt_bitserial_conv2d.restype = i32
     lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
     lib.dlrt_bitserial_conv2d_fused.restype = i32
@@ -122,6 +124,16 @@ def dlrt_bitserial_gemm(A: torch.Tensor, W: torch.Tensor, M: int, N: int, K: int
     _check(lib.dlrt_bitserial_gemm(_ptr(A), _ptr(W), _ptr(out), M, N, K, abits, wbits, enc_a, enc_w, _stream()),
            "dlrt_bitserial_gemm")
     return out
+
+
+def dlrt_bitserial_gemm_fused(A: torch.Tensor, W: torch.Tensor, scale: torch.Tensor | None, bias: torch.Tensor | None,
+                              M: int, N: int, K: int, abits: int, wbits: int, enc_a: int, enc_w: int, qbits: int = 2,
+                              out_acc: torch.Tensor | None = None, out_f32: torch.Tensor | None = None,
+                              out_q: torch.Tensor | None = None, out_packed: torch.Tensor | None = None):
+    """One launch: GEMM -> scale/bias -> requant -> bitplanes.  Only the outputs whose buffers are passed are written."""
+    _check(load().dlrt_bitserial_gemm_fused(_ptr(A), _ptr(W), _ptr(scale), _ptr(bias), M, N, K, abits, wbits, enc_a, enc_w,
+                                            _ptr(out_acc), _ptr(out_f32), _ptr(out_q), _ptr(out_packed), qbits, _stream()),
+           "dlrt_bitserial_gemm_fused")
 
 
 def dlrt_bitserial_conv2d(X: torch.Tensor, Wp: torch.Tensor, N: int, H: int, W: int, Ci: int, Co: int, KH: int,

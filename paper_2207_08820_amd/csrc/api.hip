@@ -94,8 +94,33 @@ dlrt_status dlrt_bitserial_gemm(const uint32_t *A, const uint32_t *W, int32_t *C
     const int64_t Kw = (K + 31) / 32;
     if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
     if (!aligned16(A) || !aligned16(W)) return DLRT_ERR_ALIGN;
-    return dlrt::launch_gemm(A, W, C, (int)M, (int)N, (int)Kw, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS,
-                             enc_w == DLRT_BIPOLAR, as_stream(stream));
+    dlrt::FusedOut o{};
+    o.acc = C;
+    o.qbits = 1;
+    return dlrt::launch_gemm(A, W, (int)M, (int)N, (int)Kw, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS,
+                             enc_w == DLRT_BIPOLAR, o, as_stream(stream));
+}
+
+dlrt_status dlrt_bitserial_gemm_fused(const uint32_t *A, const uint32_t *W, const float *scale, const float *bias, int64_t M,
+                                      int64_t N, int64_t K, int abits, int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w,
+                                      int32_t *out_acc, float *out_f32, uint8_t *out_q, uint32_t *out_packed, int qbits,
+                                      void *stream)
+{
+    if (!A || !W) return DLRT_ERR_NULL;
+    if (!out_acc && !out_f32 && !out_q && !out_packed) return DLRT_ERR_NULL;
+    if ((out_f32 || out_q || out_packed) && !scale) return DLRT_ERR_NULL;
+    if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
+    if ((out_q || out_packed) && !bits_ok(qbits)) return DLRT_ERR_BITS;
+    if (M <= 0 || N <= 0 || K <= 0) return DLRT_ERR_SHAPE;
+    const int64_t Kw = (K + 31) / 32;
+    if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(A) || !aligned16(W) || (out_packed && !aligned16(out_packed))) return DLRT_ERR_ALIGN;
+    dlrt::FusedOut o{};
+    o.acc = out_acc; o.y = out_f32; o.q = out_q; o.packed = out_packed;
+    o.scale = scale; o.bias = bias;
+    o.qbits = (out_q || out_packed) ? qbits : 1;
+    return dlrt::launch_gemm(A, W, (int)M, (int)N, (int)Kw, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS,
+                             enc_w == DLRT_BIPOLAR, o, as_stream(stream));
 }
 
 dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t *Y, int N, int H, int W, int Ci,
@@ -114,8 +139,12 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
     // the kernels divide reduction-word indices by Cw and KW with a 32-bit multiply-high
     if ((int64_t)KH * KW * Cw * (Cw > KW ? Cw : KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
     if (!aligned16(X) || !aligned16(Wp)) return DLRT_ERR_ALIGN;
-    return dlrt::launch_conv(X, Wp, Y, N, H, W, (int)Cw, Co, KH, KW, Ho, Wo, stride_h, stride_w, pad_h, pad_w, abits,
-                             wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, as_stream(stream));
+    dlrt::ConvShape c{N, H, W, (int)Cw, Co, KH, KW, Ho, Wo, stride_h, stride_w, pad_h, pad_w};
+    dlrt::FusedOut o{};
+    o.acc = Y;
+    o.qbits = 1;
+    return dlrt::launch_conv(X, Wp, c, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, o, 0, 0,
+                             as_stream(stream));
 }
 
 dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, const float *scale, const float *bias,
@@ -144,8 +173,8 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
     o.acc = out_acc; o.y = out_f32; o.q = out_q; o.packed = out_packed;
     o.scale = scale; o.bias = bias;
     o.qbits = (out_q || out_packed) ? qbits : 1;
-    return dlrt::launch_conv_fused(X, Wp, c, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS,
-                                   enc_w == DLRT_BIPOLAR, o, tile_rows, ksplit, as_stream(stream));
+    return dlrt::launch_conv(X, Wp, c, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, o,
+                             tile_rows, ksplit, as_stream(stream));
 }
 
 dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, int64_t M, int64_t N, int64_t K,

@@ -53,6 +53,7 @@
 namespace {
 
 using dlrt::ContractArgs;
+using dlrt::FusedOut;
 
 constexpr int kThreads = 256;
 constexpr int kK4 = 4;   // 16-byte groups per chunk
@@ -80,7 +81,7 @@ struct SlotMap {
 // parameter rather than a run-time branch: the optimiser merges run-time variants of the same
 // load into the narrowest one.
 template <int AB, int WB, int TM, int TN, int VEC, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(const ContractArgs g)
+__global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(const ContractArgs g, const FusedOut o)
 {
     constexpr int BM = 16 * TM, BN = 16 * TN;
     using MapA = SlotMap<AB, BM>;
@@ -281,15 +282,18 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
         __syncthreads();
     }
 
-    // ---- combine the plane pairs: signs and shifts of Section V's double sum ----
+    // ---- combine the plane pairs (signs and shifts of Section V's double sum), then the optional fused
+    // epilogue of Section IV: scale / bias, requantization, and the bitplanes of the requantized result ----
+    const float qmax = (float)((1 << o.qbits) - 1);
+    const int Cwo = (g.N + 31) / 32;
+    const int wave_row = ty & 3;  // this lane's row among the four rows (ty values) of its wave
 #pragma unroll
     for (int r = 0; r < TM; ++r) {
         const int m = m0 + ty + 16 * r;
-        if (m >= g.M) continue;
+        uint32_t q[TN];
 #pragma unroll
         for (int s = 0; s < TN; ++s) {
             const int n = n0 + tx + 16 * s;
-            if (n >= g.N) continue;
             int total = 0;
 #pragma unroll
             for (int j = 0; j < AB; ++j) {
@@ -306,7 +310,31 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
                 part <<= j;
                 total += (g.a_msb_neg && j == AB - 1) ? -part : part;
             }
-            g.C[(size_t)m * g.N + n] = total;
+            q[s] = 0;
+            if (m < g.M && n < g.N) {
+                const size_t idx = (size_t)m * g.N + n;
+                if (o.acc) o.acc[idx] = total;
+                if (o.scale) {
+                    const float y = __fmaf_rn((float)total, o.scale[n], o.bias ? o.bias[n] : 0.0f);
+                    if (o.y) o.y[idx] = y;
+                    q[s] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
+                    if (o.q) o.q[idx] = (uint8_t)q[s];
+                }
+            }
+        }
+        if (o.packed) {  // block-uniform: every lane takes part in the ballots
+            // A wave holds 4 rows x 16 columns per s: one ballot gives, for each of its rows, the 16-bit
+            // field of columns 16 s .. 16 s + 15; two fields make one output word.
+            for (int p = 0; p < o.qbits; ++p) {
+#pragma unroll
+                for (int c = 0; c < TN / 2; ++c) {
+                    const unsigned long long lo = __ballot((q[2 * c] >> p) & 1u), hi = __ballot((q[2 * c + 1] >> p) & 1u);
+                    const uint32_t word = (uint32_t)((lo >> (16 * wave_row)) & 0xffffu) |
+                                          ((uint32_t)((hi >> (16 * wave_row)) & 0xffffu) << 16);
+                    if (tx == 0 && m < g.M && n0 + 32 * c < g.N)
+                        o.packed[((size_t)m * o.qbits + p) * Cwo + n0 / 32 + c] = word;
+                }
+            }
         }
     }
 }
@@ -314,33 +342,33 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
 template <int B> struct LaneTile { static constexpr int value = B == 1 ? 8 : B == 2 ? 4 : 2; };
 
 template <int WB, int VEC, bool BIPOLAR, bool CONV>
-dlrt_status launch(const ContractArgs &g, hipStream_t stream)
+dlrt_status launch(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
 {
     constexpr int AB = DLRT_ABITS;
     constexpr int TM = LaneTile<AB>::value, TN = LaneTile<WB>::value;
     const int64_t tilesM = (g.M + 16 * TM - 1) / (16 * TM), tilesN = (g.N + 16 * TN - 1) / (16 * TN);
     if (tilesM * tilesN > 0x7fffffffLL) return DLRT_ERR_SHAPE;
     hipLaunchKernelGGL((contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>), dim3((unsigned)(tilesM * tilesN)),
-                       dim3(kThreads), 0, stream, g);
+                       dim3(kThreads), 0, stream, g, o);
     return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
 }
 
 template <int WB, bool BIPOLAR, bool CONV>
-dlrt_status pick_vec(const ContractArgs &g, hipStream_t stream)
+dlrt_status pick_vec(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
 {
-    if (g.vec == 4) return launch<WB, 4, BIPOLAR, CONV>(g, stream);
-    if (g.vec == 2) return launch<WB, 2, BIPOLAR, CONV>(g, stream);
-    return launch<WB, 1, BIPOLAR, CONV>(g, stream);
+    if (g.vec == 4) return launch<WB, 4, BIPOLAR, CONV>(g, o, stream);
+    if (g.vec == 2) return launch<WB, 2, BIPOLAR, CONV>(g, o, stream);
+    return launch<WB, 1, BIPOLAR, CONV>(g, o, stream);
 }
 
 template <bool CONV>
-dlrt_status pick_wbits(const ContractArgs &g, int wbits, bool bipolar, hipStream_t stream)
+dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, hipStream_t stream)
 {
     switch (wbits) {
-    case 1: return bipolar ? pick_vec<1, true, CONV>(g, stream) : pick_vec<1, false, CONV>(g, stream);
-    case 2: return pick_vec<2, false, CONV>(g, stream);
-    case 3: return pick_vec<3, false, CONV>(g, stream);
-    case 4: return pick_vec<4, false, CONV>(g, stream);
+    case 1: return bipolar ? pick_vec<1, true, CONV>(g, o, stream) : pick_vec<1, false, CONV>(g, o, stream);
+    case 2: return pick_vec<2, false, CONV>(g, o, stream);
+    case 3: return pick_vec<3, false, CONV>(g, o, stream);
+    case 4: return pick_vec<4, false, CONV>(g, o, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -352,10 +380,10 @@ namespace dlrt {
 #define DLRT_CAT2(a, b) a##b
 #define DLRT_CAT(a, b) DLRT_CAT2(a, b)
 
-dlrt_status DLRT_CAT(launch_contract_a, DLRT_ABITS)(const ContractArgs &g, int wbits, bool bipolar, bool conv,
-                                                     hipStream_t stream)
+dlrt_status DLRT_CAT(launch_contract_a, DLRT_ABITS)(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar,
+                                                     bool conv, hipStream_t stream)
 {
-    return conv ? pick_wbits<true>(g, wbits, bipolar, stream) : pick_wbits<false>(g, wbits, bipolar, stream);
+    return conv ? pick_wbits<true>(g, o, wbits, bipolar, stream) : pick_wbits<false>(g, o, wbits, bipolar, stream);
 }
 
 }  // namespace dlrt

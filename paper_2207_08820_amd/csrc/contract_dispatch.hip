@@ -19,13 +19,14 @@ int widest_vec(const void *base, int64_t stride_words)
     return 1;
 }
 
-dlrt_status by_abits(const dlrt::ContractArgs &g, int abits, int wbits, bool bipolar, bool conv, hipStream_t stream)
+dlrt_status by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
+                     bool conv, hipStream_t stream)
 {
     switch (abits) {
-    case 1: return dlrt::launch_contract_a1(g, wbits, bipolar, conv, stream);
-    case 2: return dlrt::launch_contract_a2(g, wbits, bipolar, conv, stream);
-    case 3: return dlrt::launch_contract_a3(g, wbits, bipolar, conv, stream);
-    case 4: return dlrt::launch_contract_a4(g, wbits, bipolar, conv, stream);
+    case 1: return dlrt::launch_contract_a1(g, o, wbits, bipolar, conv, stream);
+    case 2: return dlrt::launch_contract_a2(g, o, wbits, bipolar, conv, stream);
+    case 3: return dlrt::launch_contract_a3(g, o, wbits, bipolar, conv, stream);
+    case 4: return dlrt::launch_contract_a4(g, o, wbits, bipolar, conv, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -95,67 +96,43 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
 
 namespace dlrt {
 
-dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int Kw, int abits,
-                        int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream)
+dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int Kw, int abits, int wbits,
+                        bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, hipStream_t stream)
 {
     ContractArgs g{};
-    g.A = A; g.W = W; g.C = C; g.M = M; g.N = N; g.Kw = Kw;
+    g.A = A; g.W = W; g.M = M; g.N = N; g.Kw = Kw;
     g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
     if (prefer_wave_kernel(M, N, abits, wbits)) {
-        FusedOut o{};
-        o.acc = C;
-        o.qbits = 1;
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
         return wave_by_abits(g, o, abits, wbits, bipolar, false, p.tm, p.ksplit, stream);
     }
-    return by_abits(g, abits, wbits, bipolar, false, stream);
+    return by_abits(g, o, abits, wbits, bipolar, false, stream);
 }
 
-dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, int32_t *Y, int N, int H, int W, int Cw, int Co,
-                        int KH, int KW, int Ho, int Wo, int sh, int sw, int ph, int pw, int abits, int wbits,
-                        bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream)
+dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
+                        bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows, int ksplit,
+                        hipStream_t stream)
 {
     ContractArgs g{};
-    g.A = X; g.W = Wp; g.C = Y;
-    g.M = N * Ho * Wo; g.N = Co; g.Kw = KH * KW * Cw;
+    g.A = X; g.W = Wp;
+    g.M = c.N * c.Ho * c.Wo; g.N = c.Co; g.Kw = c.KH * c.KW * c.Cw;
     g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     // a tap's Cw words must not be split by a vector load; the weight rows (KH*KW*Cw words) then
     // allow at least the same width
-    const int va = widest_vec(X, Cw), vw = widest_vec(Wp, g.Kw);
-    g.vec = va < vw ? va : vw;
-    g.H = H; g.Wd = W; g.Cw = Cw; g.KH = KH; g.KW = KW; g.Ho = Ho; g.Wo = Wo;
-    g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
-    g.magicCw = magic_for(Cw);
-    g.magicKW = magic_for(KW);
-    if (prefer_wave_kernel(g.M, g.N, abits, wbits)) {
-        FusedOut o{};
-        o.acc = Y;
-        o.qbits = 1;
-        const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, 0, 0);
-        return wave_by_abits(g, o, abits, wbits, bipolar, true, p.tm, p.ksplit, stream);
-    }
-    return by_abits(g, abits, wbits, bipolar, true, stream);
-}
-
-dlrt_status launch_conv_fused(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
-                              bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows,
-                              int ksplit, hipStream_t stream)
-{
-    ContractArgs g{};
-    g.A = X; g.W = Wp; g.C = nullptr;
-    g.M = c.N * c.Ho * c.Wo; g.N = c.Co; g.Kw = c.KH * c.KW * c.Cw;
-    g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     const int va = widest_vec(X, c.Cw), vw = widest_vec(Wp, g.Kw);
     g.vec = va < vw ? va : vw;
     g.H = c.H; g.Wd = c.W; g.Cw = c.Cw; g.KH = c.KH; g.KW = c.KW; g.Ho = c.Ho; g.Wo = c.Wo;
     g.sh = c.sh; g.sw = c.sw; g.ph = c.ph; g.pw = c.pw;
     g.magicCw = magic_for(c.Cw);
     g.magicKW = magic_for(c.KW);
-    const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
-    if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have
-    return wave_by_abits(g, o, abits, wbits, bipolar, true, p.tm, p.ksplit, stream);
+    if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
+        const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
+        if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have
+        return wave_by_abits(g, o, abits, wbits, bipolar, true, p.tm, p.ksplit, stream);
+    }
+    return by_abits(g, o, abits, wbits, bipolar, true, stream);
 }
 
 }  // namespace dlrt

@@ -8,20 +8,7 @@
 
 namespace dlrt {
 
-// Arguments of one contraction launch (GEMM, or convolution as an implicit im2col GEMM).
-struct ContractArgs {
-    const uint32_t *A;  // GEMM: [M][abits][Kw]; conv: X [N][H][W][abits][Cw]
-    const uint32_t *W;  // [N][wbits][Kw]
-    int32_t *C;         // [M][N]
-    int M, N, Kw;       // Kw: reduction words per plane (conv: KH*KW*Cw)
-    int a_msb_neg, w_msb_neg;
-    int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
-    // convolution geometry (unused by GEMM)
-    int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
-    uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
-};
-
-// Optional outputs of the fused epilogue of the per-wave kernel; any pointer may be null.
+// Optional outputs of the fused epilogue of both contraction kernels; any pointer may be null.
 struct FusedOut {
     int32_t *acc;      // [M][N] accumulators
     float *y;          // [M][N] fma(float(acc), scale[n], bias[n])
@@ -31,11 +18,23 @@ struct FusedOut {
     int qbits;
 };
 
+// Arguments of one contraction launch (GEMM, or convolution as an implicit im2col GEMM).
+struct ContractArgs {
+    const uint32_t *A;  // GEMM: [M][abits][Kw]; conv: X [N][H][W][abits][Cw]
+    const uint32_t *W;  // [N][wbits][Kw]
+    int M, N, Kw;       // Kw: reduction words per plane (conv: KH*KW*Cw)
+    int a_msb_neg, w_msb_neg;
+    int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
+    // convolution geometry (unused by GEMM)
+    int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
+    uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
+};
+
 // One translation unit per activation bit width (contract.hip with -DDLRT_ABITS=n).
-dlrt_status launch_contract_a1(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
-dlrt_status launch_contract_a2(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
-dlrt_status launch_contract_a3(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
-dlrt_status launch_contract_a4(const ContractArgs &g, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
+dlrt_status launch_contract_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
 
 // Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n): tm = rows per lane (1, 2, 4), ksplit = waves
 // per block that split the reduction (1, 2, 4, 8); both as planned by plan_wave().
@@ -49,17 +48,14 @@ struct ConvShape {
     int N, H, W, Cw, Co, KH, KW, Ho, Wo, sh, sw, ph, pw;
 };
 
-// Fused convolution on the per-wave kernel; tile_rows / ksplit are hints (0 = planned by the library).
-dlrt_status launch_conv_fused(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
-                              bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows,
-                              int ksplit, hipStream_t stream);
+// GEMM / convolution with any subset of the fused outputs; the kernel (block or per-wave) is chosen by
+// size.  tile_rows / ksplit are hints for the per-wave kernel (0 = planned); a non-zero hint forces it.
+dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int Kw, int abits, int wbits,
+                        bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, hipStream_t stream);
 
-dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int Kw, int abits,
-                        int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream);
-
-dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, int32_t *Y, int N, int H, int W, int Cw, int Co,
-                        int KH, int KW, int Ho, int Wo, int sh, int sw, int ph, int pw, int abits, int wbits,
-                        bool a_msb_neg, bool w_msb_neg, bool bipolar, hipStream_t stream);
+dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
+                        bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows, int ksplit,
+                        hipStream_t stream);
 
 // rows x K elements (row stride ld) -> dst word (r, p, kw) at dst[r * row_stride + p * plane_stride + kw_off + kw].
 // The generic destination strides let the same kernel emit both the [rows][bits][Kw] tensor and the

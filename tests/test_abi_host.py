@@ -43,7 +43,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_gemm", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
+    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_gemm", "dlrt_bitserial_gemm_fused", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
                      "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -95,6 +95,18 @@ def test_fused_conv_rejects_bad_arguments_before_launch(lib):
     assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, 0, 3, NULL) == ERR_SHAPE
     assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, -1, 0, NULL) == ERR_SHAPE
     assert f(FAKE, FAKE, FAKE, NULL, *shape, 2, 2, UNSIGNED, BIPOLAR, FAKE, NULL, NULL, NULL, 2, 0, 0, NULL) == ERR_ENCODING
+
+
+def test_fused_gemm_rejects_bad_arguments_before_launch(lib):
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+    lib.dlrt_bitserial_gemm_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp, vp, vp, vp, i32, vp]
+    f = lib.dlrt_bitserial_gemm_fused
+    assert f(FAKE, FAKE, FAKE, NULL, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL, NULL, NULL, NULL, 2, NULL) == ERR_NULL
+    assert f(FAKE, FAKE, NULL, NULL, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL, FAKE, NULL, NULL, 2, NULL) == ERR_NULL
+    assert f(FAKE, FAKE, FAKE, NULL, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL, NULL, FAKE, NULL, 0, NULL) == ERR_BITS
+    assert f(FAKE, FAKE, FAKE, NULL, 4, 0, 32, 2, 2, UNSIGNED, TWOS, FAKE, NULL, NULL, NULL, 2, NULL) == ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, NULL, 4, 4, 32, 2, 2, UNSIGNED, TWOS, NULL, NULL, NULL, FAKE + 4, 2, NULL) == ERR_ALIGN
+    assert f(FAKE, FAKE, FAKE, NULL, 4, 4, 32, 2, 2, TWOS, BIPOLAR, FAKE, NULL, NULL, NULL, 2, NULL) == ERR_ENCODING
 
 
 def test_unpacked_gemm_rejects_bad_arguments_before_launch(lib):

@@ -403,6 +403,64 @@ def test_conv_fused_rejects_hints_the_kernels_do_not_have(dlrt):
         assert e.value.code == 3
 
 
+# ---- fused epilogue on the throughput (block) kernel: problems large enough to leave the per-wave kernel ----
+@pytest.mark.parametrize("abits,wbits,ea,ew,qbits,M,N,K", [
+    (2, 2, UNSIGNED, TWOS, 2, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 1, 2900, 2950, 96),
+    (4, 4, UNSIGNED, TWOS, 4, 730, 750, 50), (3, 3, TWOS, TWOS, 3, 760, 710, 330), (2, 4, UNSIGNED, TWOS, 2, 1500, 700, 64)])
+def test_gemm_fused_large_shapes(dlrt, oracle, abits, wbits, ea, ew, qbits, M, N, K):
+    a = inputs.uniform_values((M, K), abits, ea, 41000 + M)
+    w = inputs.uniform_values((N, K), wbits, ew, 42000 + N)
+    ref = (a.astype(np.int64) @ w.astype(np.int64).T).astype(np.int32)
+    rows = rng(M).choice(M, size=16, replace=False)
+    assert np.array_equal(ref[rows], oracle.gemm_i32(a[rows], w))  # the numpy product is only a stand-in for speed
+    scale, bias = calibrate(ref)
+    scale, bias = (scale * (1 << qbits) / 4).astype(np.float32), (bias * (1 << qbits) / 4).astype(np.float32)
+    y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=qbits)
+    A = dlrt.dlrt_pack_bitplanes(src_tensor(a, ea), abits, ea)
+    W = dlrt.dlrt_pack_bitplanes(src_tensor(w, ew), wbits, ew)
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=DEV)
+    y = torch.full((M, N), -7.0, dtype=torch.float32, device=DEV)
+    q = torch.full((M, N), 99, dtype=torch.uint8, device=DEV)
+    packed = torch.full((M, qbits, (N + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), dev(bias), M, N, K, abits, wbits, ea, ew, qbits=qbits, out_acc=acc,
+                                   out_f32=y, out_q=q, out_packed=packed)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), ref)
+    assert np.array_equal(y.cpu().numpy(), y_ref)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(words(packed), oracle.pack_bitplanes(q_ref.astype(np.int8), qbits, UNSIGNED))
+    # only one output requested: the others stay untouched
+    y2 = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), None, M, N, K, abits, wbits, ea, ew, out_f32=y2)
+    torch.cuda.synchronize()
+    assert np.array_equal(y2.cpu().numpy(), oracle.epilogue_f32(ref, scale)[0])
+
+
+def test_gemm_fused_small_shape_takes_the_per_wave_kernel(dlrt, oracle):
+    c, a, w = inputs.config1()
+    ref = oracle.gemm_i32(a, w)
+    scale = inputs.uniform_scale(c.N, 5)
+    A = dlrt.dlrt_pack_bitplanes(src_tensor(a, c.enc_a), 2, c.enc_a)
+    W = dlrt.dlrt_pack_bitplanes(src_tensor(w, c.enc_w), 2, c.enc_w)
+    y = torch.empty((c.M, c.N), dtype=torch.float32, device=DEV)
+    packed = torch.empty((c.M, 2, 2), dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), None, c.M, c.N, c.K, 2, 2, c.enc_a, c.enc_w, out_f32=y, out_packed=packed)
+    torch.cuda.synchronize()
+    y_ref, q_ref = oracle.epilogue_f32(ref, scale, qbits=2)
+    assert np.array_equal(y.cpu().numpy(), y_ref)
+    assert np.array_equal(words(packed), oracle.pack_bitplanes(q_ref.astype(np.int8), 2, UNSIGNED))
+
+
+def test_conv_fused_large_batch_takes_the_block_kernel(dlrt, oracle):
+    """Batch 16 of the 56 x 56 x 64 layer: 784 block tiles, so the throughput kernel runs the fused epilogue."""
+    x = inputs.uniform_values((16, 56, 56, 64), 2, UNSIGNED, 888)
+    w = inputs.uniform_values((64, 3, 3, 64), 2, TWOS, 889)
+    fused_case(dlrt, oracle, x, w, 1, 1, 2, 2, UNSIGNED, TWOS, 2)
+    xb = inputs.uniform_values((9, 40, 40, 96), 2, UNSIGNED, 890)
+    wb = inputs.uniform_values((160, 3, 3, 96), 1, BIPOLAR, 891)
+    fused_case(dlrt, oracle, xb, wb, 2, 1, 2, 1, UNSIGNED, BIPOLAR, 2)
+
+
 # ---- GEMM through both kernels: large shapes take the block kernel, small ones the per-wave kernel ----
 def test_gemm_ragged_large_shape_block_kernel(dlrt, oracle):
     for abits, wbits, ea, ew, M, N, K in [(2, 2, UNSIGNED, TWOS, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 2900, 2950, 96),
