@@ -461,6 +461,40 @@ def test_conv_fused_large_batch_takes_the_block_kernel(dlrt, oracle):
     fused_case(dlrt, oracle, xb, wb, 2, 1, 2, 1, UNSIGNED, BIPOLAR, 2)
 
 
+# ---- sizes at the far ends -------------------------------------------------------------------------------
+def test_gemm_very_tall_output_indexing_beyond_2_31_bytes(dlrt, oracle):
+    """M = 2^24 + 5 rows of 40 outputs: the int32 result is 2.7 GB, so byte offsets pass 2^31; sampled rows
+    against the oracle plus the column-sum identity over everything."""
+    M, N, K = (1 << 24) + 5, 40, 64
+    a = inputs.uniform_values((M, K), 2, UNSIGNED, 51000)
+    w = inputs.uniform_values((N, K), 2, TWOS, 51001)
+    A = dlrt.dlrt_pack_bitplanes(dev(a.astype(np.uint8)), 2, UNSIGNED)
+    W = dlrt.dlrt_pack_bitplanes(dev(w), 2, TWOS)
+    C = dlrt.dlrt_bitserial_gemm(A, W, M, N, K, 2, 2, UNSIGNED, TWOS)
+    torch.cuda.synchronize()
+    rows = np.concatenate([rng(5).choice(M, size=64, replace=False), [0, M - 1, (1 << 23) + 1]])
+    assert np.array_equal(C[torch.as_tensor(rows, device=DEV)].cpu().numpy(), oracle.gemm_i32(a[rows], w))
+    colsum = C.sum(dim=0, dtype=torch.int64).cpu().numpy()
+    assert np.array_equal(colsum, w.astype(np.int64) @ a.astype(np.int64).sum(axis=0))
+
+
+def test_gemm_very_long_reduction(dlrt, oracle):
+    """K = 2^20 + 37 (32769 words per plane, ragged last word), small M and N: many chunks per wave."""
+    M, N, K = 20, 70, (1 << 20) + 37
+    for abits, wbits, ew in ((2, 2, TWOS), (1, 1, BIPOLAR), (4, 4, TWOS)):
+        a = inputs.uniform_values((M, K), abits, UNSIGNED, 52000 + abits)
+        w = inputs.uniform_values((N, K), wbits, ew, 52100 + wbits)
+        assert np.array_equal(gpu_gemm(dlrt, a, w, abits, wbits, UNSIGNED, ew), oracle.gemm_i32(a, w))
+
+
+def test_conv_large_image_single_channel_word(dlrt, oracle):
+    """640 x 640 x 32 input (the YOLO-style stem size), 3x3 stride 2: 102400 output pixels, one word per pixel."""
+    x = inputs.uniform_values((1, 640, 640, 32), 2, UNSIGNED, 53000)
+    w = inputs.uniform_values((32, 3, 3, 32), 1, BIPOLAR, 53001)
+    got = gpu_conv(dlrt, x, w, (2, 2), (1, 1), 2, 1, UNSIGNED, BIPOLAR)
+    assert np.array_equal(got, oracle.conv2d_i32(x, w, (2, 2), (1, 1)))
+
+
 # ---- GEMM through both kernels: large shapes take the block kernel, small ones the per-wave kernel ----
 def test_gemm_ragged_large_shape_block_kernel(dlrt, oracle):
     for abits, wbits, ea, ew, M, N, K in [(2, 2, UNSIGNED, TWOS, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 2900, 2950, 96),
