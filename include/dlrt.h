@@ -151,6 +151,17 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                                         void *stream);
 
 /*
+ * Host-only introspection: which kernel and tile the library would use for a contraction with M outputs
+ * rows (conv: N*Ho*Wo), N output columns (conv: Co) and K reduction elements per output, padded per tap as
+ * the packed formats are (conv: KH*KW*ceil(Ci/32)*32).  Launches nothing.
+ *   *block_kernel = 1: the throughput kernel (one 256-thread block per tile_rows x tile_cols tile, ksplit 1)
+ *   *block_kernel = 0: the latency kernel (one wave per tile_rows x 32 tile, ksplit waves split K)
+ * Any output pointer may be NULL.
+ */
+dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbits, int *block_kernel,
+                            int *tile_rows, int *tile_cols, int *ksplit);
+
+/*
  * Comparison variant, not the bit-serial path: the same integer GEMM as dlrt_bitserial_gemm,
  *   C[m][n] = sum_k A[m][k] * W[n][k]      int32, row-major, leading dimension N,
  * computed on the UNPACKED quantized values (one int8 per element, K-contiguous, any values in

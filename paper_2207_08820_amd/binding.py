@@ -54,6 +54,8 @@ def load():
     lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
     lib.dlrt_bitserial_conv2d_fused.restype = i32
     lib.dlrt_bitserial_conv2d_fused.argtypes = [vp, vp, vp, vp] + [i32] * 15 + [vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.dlrt_query_plan.restype = i32
+    lib.dlrt_query_plan.argtypes = [i64, i64, i64, i32, i32] + [ctypes.POINTER(ctypes.c_int)] * 4
     lib.dlrt_unpacked_gemm_i8.restype = i32
     lib.dlrt_unpacked_gemm_i8.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     lib.dlrt_epilogue_f32.restype = i32
@@ -167,6 +169,13 @@ def dlrt_bitserial_conv2d_fused(X: torch.Tensor, Wp: torch.Tensor, scale: torch.
                                            sh, sw, ph, pw, abits, wbits, enc_a, enc_w, _ptr(out_acc), _ptr(out_f32),
                                            _ptr(out_q), _ptr(out_packed), qbits, tile_rows, ksplit, _stream()),
            "dlrt_bitserial_conv2d_fused")
+
+
+def dlrt_query_plan(M: int, N: int, K: int, abits: int, wbits: int) -> dict:
+    """Kernel and tile the library would use for an M x N x K contraction (host only)."""
+    out = [ctypes.c_int() for _ in range(4)]
+    _check(load().dlrt_query_plan(M, N, K, abits, wbits, *[ctypes.byref(o) for o in out]), "dlrt_query_plan")
+    return dict(block_kernel=bool(out[0].value), tile_rows=out[1].value, tile_cols=out[2].value, ksplit=out[3].value)
 
 
 def dlrt_unpacked_gemm_i8(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

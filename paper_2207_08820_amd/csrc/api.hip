@@ -177,6 +177,17 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                              tile_rows, ksplit, as_stream(stream));
 }
 
+dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbits, int *block_kernel, int *tile_rows,
+                            int *tile_cols, int *ksplit)
+{
+    if (!bits_ok(abits) || !bits_ok(wbits)) return DLRT_ERR_BITS;
+    if (M <= 0 || N <= 0 || K <= 0) return DLRT_ERR_SHAPE;
+    const int64_t Kw = (K + 31) / 32;
+    if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    dlrt::query_plan((int)M, (int)N, (int)Kw, abits, wbits, block_kernel, tile_rows, tile_cols, ksplit);
+    return DLRT_OK;
+}
+
 dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, int64_t M, int64_t N, int64_t K,
                                   void *stream)
 {

@@ -100,6 +100,22 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
 
 namespace dlrt {
 
+void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, int *tile_rows, int *tile_cols, int *ksplit)
+{
+    const bool wave = prefer_wave_kernel(M, N, abits, wbits);
+    int rows = block_tile(abits), cols = block_tile(wbits), ks = 1;
+    if (wave) {
+        const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
+        rows = (wbits <= 2 ? 8 : 4) * p.tm;
+        cols = 32;
+        ks = p.ksplit;
+    }
+    if (block_kernel) *block_kernel = wave ? 0 : 1;
+    if (tile_rows) *tile_rows = rows;
+    if (tile_cols) *tile_cols = cols;
+    if (ksplit) *ksplit = ks;
+}
+
 dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int Kw, int abits, int wbits,
                         bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, hipStream_t stream)
 {

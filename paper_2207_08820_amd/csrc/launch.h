@@ -57,6 +57,9 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
                         bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows, int ksplit,
                         hipStream_t stream);
 
+// What launch_gemm / launch_conv would pick (no hints).
+void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, int *tile_rows, int *tile_cols, int *ksplit);
+
 // rows x K elements (row stride ld) -> dst word (r, p, kw) at dst[r * row_stride + p * plane_stride + kw_off + kw].
 // The generic destination strides let the same kernel emit both the [rows][bits][Kw] tensor and the
 // per-tap padded layout of convolution weights.

@@ -44,7 +44,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_gemm", "dlrt_bitserial_gemm_fused", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
-                     "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
+                     "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_query_plan", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -136,6 +136,49 @@ def test_pack_and_epilogue_reject_bad_arguments_before_launch(lib):
     assert e(FAKE, FAKE, NULL, 0, 4, FAKE, NULL, 2, NULL) == ERR_SHAPE
     assert e(FAKE, FAKE, NULL, 4, 4, NULL, FAKE, 0, NULL) == ERR_BITS
     assert e(FAKE, FAKE, NULL, 4, 4, NULL, FAKE, 9, NULL) == ERR_BITS
+
+
+def query(lib, M, N, K, a, w):
+    out = [ctypes.c_int() for _ in range(4)]
+    lib.dlrt_query_plan.argtypes = [ctypes.c_int64] * 3 + [ctypes.c_int] * 2 + [ctypes.POINTER(ctypes.c_int)] * 4
+    assert lib.dlrt_query_plan(M, N, K, a, w, *[ctypes.byref(o) for o in out]) == OK
+    return tuple(o.value for o in out)
+
+
+def test_planner_choices_for_the_benchmark_workloads(lib):
+    # the 4096^3 sweep takes the throughput kernel with tiles of 16 * {8,4,2,2}[bits]
+    assert query(lib, 4096, 4096, 4096, 2, 2) == (1, 64, 64, 1)
+    assert query(lib, 4096, 4096, 4096, 1, 1) == (1, 128, 128, 1)
+    assert query(lib, 4096, 4096, 4096, 2, 4) == (1, 64, 32, 1)
+    # batch-1 conv layers take the per-wave kernel; deep reductions are split across waves
+    assert query(lib, 64, 64, 576, 2, 2)[0] == 0
+    blk, rows, cols, ks = query(lib, 3136, 64, 576, 2, 2)
+    assert (blk, rows, cols) == (0, 8, 32) and ks in (1, 2)
+    blk, rows, cols, ks = query(lib, 49, 512, 4608, 2, 2)
+    assert (blk, rows, cols) == (0, 8, 32) and ks >= 4
+    assert query(lib, 784, 128, 64, 2, 2) == (0, 8, 32, 1)  # two steps of reduction: nothing to split
+    assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
+    assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
+
+
+def test_planner_always_returns_a_tile_the_kernels_have(lib):
+    import random
+    r = random.Random(3)
+    for _ in range(2000):
+        a, w = r.randint(1, 4), r.randint(1, 4)
+        M, N = r.choice([1, 7, 49, 196, 784, 3136, 25600, 100000]), r.choice([1, 16, 32, 64, 100, 512, 4096])
+        K = r.choice([1, 32, 64, 288, 576, 1152, 4608, 40000])
+        blk, rows, cols, ks = query(lib, M, N, K, a, w)
+        tn = 4 if w <= 2 else 2
+        if blk:
+            assert (rows, cols, ks) == (16 * [8, 4, 2, 2][a - 1], 16 * [8, 4, 2, 2][w - 1], 1)
+            assert -(-M // rows) * -(-N // cols) >= 512
+        else:
+            tm = rows // (2 * tn)
+            assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)
+            assert tm * tn * a * w <= 72                                     # accumulators per lane
+            assert ks * (4 * a * rows + 4 * w * 32) * 16 <= 65536           # LDS of the ks staging regions
+            assert ks == 1 or ks <= -(-(-(-K // 32)) // 4)                   # no more slices than 4-word steps
 
 
 def test_binding_exposes_the_same_names():
