@@ -151,6 +151,32 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                                         void *stream);
 
 /*
+ * Two fused convolutions in ONE launch: layers that do not depend on each other (typically two that read
+ * the same activations, like a stride-2 3x3 conv and the 1x1 downsample conv beside it) share the fixed
+ * cost of a launch, which dominates batch-1 layers.  Each problem computes exactly what
+ * dlrt_bitserial_conv2d_fused computes for the same fields; both use the latency-oriented kernel with its
+ * smallest tile.  abits / wbits / encodings are common to both; everything else is per problem.
+ * `first` and `second` are HOST structs, read before the call returns; their pointers are device pointers.
+ * The two problems must not write buffers the other reads or writes.
+ */
+typedef struct dlrt_conv_problem {
+    const uint32_t *X;
+    const uint32_t *Wp;
+    const float *scale; /* may be NULL if only out_acc is given */
+    const float *bias;  /* may be NULL */
+    int N, H, W, Ci, Co, KH, KW, stride_h, stride_w, pad_h, pad_w;
+    int32_t *out_acc;     /* any of the four outputs may be NULL, not all */
+    float *out_f32;
+    uint8_t *out_q;
+    uint32_t *out_packed;
+    int qbits;
+} dlrt_conv_problem;
+
+dlrt_status dlrt_bitserial_conv2d_fused_pair(const dlrt_conv_problem *first, const dlrt_conv_problem *second,
+                                             int abits, int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w,
+                                             void *stream);
+
+/*
  * Host-only introspection: which kernel and tile the library would use for a contraction with M outputs
  * rows (conv: N*Ho*Wo), N output columns (conv: Co) and K reduction elements per output, padded per tap as
  * the packed formats are (conv: KH*KW*ceil(Ci/32)*32).  Launches nothing.

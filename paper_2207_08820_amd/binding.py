@@ -22,6 +22,14 @@ SRC_U8, SRC_I8, SRC_F32 = 0, 1, 2
 _lib = None
 
 
+class ConvProblem(ctypes.Structure):
+    """Mirror of dlrt_conv_problem."""
+    _fields_ = [("X", ctypes.c_void_p), ("Wp", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p)] + \
+               [(n, ctypes.c_int) for n in ("N", "H", "W", "Ci", "Co", "KH", "KW", "stride_h", "stride_w", "pad_h", "pad_w")] + \
+               [("out_acc", ctypes.c_void_p), ("out_f32", ctypes.c_void_p), ("out_q", ctypes.c_void_p),
+                ("out_packed", ctypes.c_void_p), ("qbits", ctypes.c_int)]
+
+
 class DlrtError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -54,6 +62,9 @@ def load():
     lib.dlrt_bitserial_conv2d.argtypes = [vp, vp, vp] + [i32] * 15 + [vp]
     lib.dlrt_bitserial_conv2d_fused.restype = i32
     lib.dlrt_bitserial_conv2d_fused.argtypes = [vp, vp, vp, vp] + [i32] * 15 + [vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.dlrt_bitserial_conv2d_fused_pair.restype = i32
+    lib.dlrt_bitserial_conv2d_fused_pair.argtypes = [ctypes.POINTER(ConvProblem), ctypes.POINTER(ConvProblem), i32, i32, i32,
+                                                     i32, vp]
     lib.dlrt_query_plan.restype = i32
     lib.dlrt_query_plan.argtypes = [i64, i64, i64, i32, i32] + [ctypes.POINTER(ctypes.c_int)] * 4
     lib.dlrt_unpacked_gemm_i8.restype = i32
@@ -169,6 +180,20 @@ def dlrt_bitserial_conv2d_fused(X: torch.Tensor, Wp: torch.Tensor, scale: torch.
                                            sh, sw, ph, pw, abits, wbits, enc_a, enc_w, _ptr(out_acc), _ptr(out_f32),
                                            _ptr(out_q), _ptr(out_packed), qbits, tile_rows, ksplit, _stream()),
            "dlrt_bitserial_conv2d_fused")
+
+
+def conv_problem(X, Wp, scale, bias, N, H, W, Ci, Co, KH, KW, stride, pad, qbits=2, out_acc=None, out_f32=None,
+                 out_q=None, out_packed=None) -> ConvProblem:
+    """Fill a dlrt_conv_problem from tensors (None = NULL)."""
+    return ConvProblem(_ptr(X), _ptr(Wp), _ptr(scale), _ptr(bias), N, H, W, Ci, Co, KH, KW, stride[0], stride[1], pad[0],
+                       pad[1], _ptr(out_acc), _ptr(out_f32), _ptr(out_q), _ptr(out_packed), qbits)
+
+
+def dlrt_bitserial_conv2d_fused_pair(first: ConvProblem, second: ConvProblem, abits: int, wbits: int, enc_a: int,
+                                     enc_w: int):
+    """Two independent fused convolutions of the same bit widths in one launch."""
+    _check(load().dlrt_bitserial_conv2d_fused_pair(ctypes.byref(first), ctypes.byref(second), abits, wbits, enc_a, enc_w,
+                                                   _stream()), "dlrt_bitserial_conv2d_fused_pair")
 
 
 def dlrt_query_plan(M: int, N: int, K: int, abits: int, wbits: int) -> dict:

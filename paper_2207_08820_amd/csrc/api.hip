@@ -33,6 +33,31 @@ dlrt_status check_pack(const void *src, dlrt_src st, int bits, dlrt_encoding enc
     return DLRT_OK;
 }
 
+// Validation shared by the fused convolution entry points; fills the launcher's shape and outputs.
+dlrt_status check_conv_problem(const dlrt_conv_problem &p, int abits, dlrt::ConvShape &c, dlrt::FusedOut &o)
+{
+    if (!p.X || !p.Wp) return DLRT_ERR_NULL;
+    if (!p.out_acc && !p.out_f32 && !p.out_q && !p.out_packed) return DLRT_ERR_NULL;
+    if ((p.out_f32 || p.out_q || p.out_packed) && !p.scale) return DLRT_ERR_NULL;
+    if ((p.out_q || p.out_packed) && !bits_ok(p.qbits)) return DLRT_ERR_BITS;
+    if (p.N <= 0 || p.H <= 0 || p.W <= 0 || p.Ci <= 0 || p.Co <= 0 || p.KH <= 0 || p.KW <= 0) return DLRT_ERR_SHAPE;
+    if (p.stride_h <= 0 || p.stride_w <= 0 || p.pad_h < 0 || p.pad_w < 0) return DLRT_ERR_SHAPE;
+    if (p.H + 2 * p.pad_h < p.KH || p.W + 2 * p.pad_w < p.KW) return DLRT_ERR_SHAPE;
+    const int Ho = (p.H + 2 * p.pad_h - p.KH) / p.stride_h + 1, Wo = (p.W + 2 * p.pad_w - p.KW) / p.stride_w + 1;
+    const int64_t Cw = (p.Ci + 31) / 32;
+    if ((int64_t)p.N * Ho * Wo > 0x7fffffff || (int64_t)p.KH * p.KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if ((int64_t)p.H * p.W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
+    // the kernels divide reduction-word indices by Cw and KW with a 32-bit multiply-high
+    if ((int64_t)p.KH * p.KW * Cw * (Cw > p.KW ? Cw : p.KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(p.X) || !aligned16(p.Wp) || (p.out_packed && !aligned16(p.out_packed))) return DLRT_ERR_ALIGN;
+    c = dlrt::ConvShape{p.N, p.H, p.W, (int)Cw, p.Co, p.KH, p.KW, Ho, Wo, p.stride_h, p.stride_w, p.pad_h, p.pad_w};
+    o = dlrt::FusedOut{};
+    o.acc = p.out_acc; o.y = p.out_f32; o.q = p.out_q; o.packed = p.out_packed;
+    o.scale = p.scale; o.bias = p.bias;
+    o.qbits = (p.out_q || p.out_packed) ? p.qbits : 1;
+    return DLRT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -153,28 +178,29 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                                         dlrt_encoding enc_w, int32_t *out_acc, float *out_f32, uint8_t *out_q,
                                         uint32_t *out_packed, int qbits, int tile_rows, int ksplit, void *stream)
 {
-    if (!X || !Wp) return DLRT_ERR_NULL;
-    if (!out_acc && !out_f32 && !out_q && !out_packed) return DLRT_ERR_NULL;
-    if ((out_f32 || out_q || out_packed) && !scale) return DLRT_ERR_NULL;
     if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
-    if ((out_q || out_packed) && !bits_ok(qbits)) return DLRT_ERR_BITS;
-    if (N <= 0 || H <= 0 || W <= 0 || Ci <= 0 || Co <= 0 || KH <= 0 || KW <= 0) return DLRT_ERR_SHAPE;
-    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return DLRT_ERR_SHAPE;
-    if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return DLRT_ERR_SHAPE;
     if (tile_rows < 0 || ksplit < 0) return DLRT_ERR_SHAPE;
-    const int Ho = (H + 2 * pad_h - KH) / stride_h + 1, Wo = (W + 2 * pad_w - KW) / stride_w + 1;
-    const int64_t Cw = (Ci + 31) / 32;
-    if ((int64_t)N * Ho * Wo > 0x7fffffff || (int64_t)KH * KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
-    if ((int64_t)H * W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
-    if ((int64_t)KH * KW * Cw * (Cw > KW ? Cw : KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
-    if (!aligned16(X) || !aligned16(Wp) || (out_packed && !aligned16(out_packed))) return DLRT_ERR_ALIGN;
-    dlrt::ConvShape c{N, H, W, (int)Cw, Co, KH, KW, Ho, Wo, stride_h, stride_w, pad_h, pad_w};
+    const dlrt_conv_problem p{X, Wp, scale, bias, N, H, W, Ci, Co, KH, KW, stride_h, stride_w, pad_h, pad_w,
+                              out_acc, out_f32, out_q, out_packed, qbits};
+    dlrt::ConvShape c{};
     dlrt::FusedOut o{};
-    o.acc = out_acc; o.y = out_f32; o.q = out_q; o.packed = out_packed;
-    o.scale = scale; o.bias = bias;
-    o.qbits = (out_q || out_packed) ? qbits : 1;
+    if (dlrt_status s = check_conv_problem(p, abits, c, o)) return s;
     return dlrt::launch_conv(X, Wp, c, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR, o,
                              tile_rows, ksplit, as_stream(stream));
+}
+
+dlrt_status dlrt_bitserial_conv2d_fused_pair(const dlrt_conv_problem *first, const dlrt_conv_problem *second, int abits,
+                                             int wbits, dlrt_encoding enc_a, dlrt_encoding enc_w, void *stream)
+{
+    if (!first || !second) return DLRT_ERR_NULL;
+    if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
+    dlrt::ConvShape c[2];
+    dlrt::FusedOut o[2];
+    if (dlrt_status s = check_conv_problem(*first, abits, c[0], o[0])) return s;
+    if (dlrt_status s = check_conv_problem(*second, abits, c[1], o[1])) return s;
+    const uint32_t *X[2] = {first->X, second->X}, *Wp[2] = {first->Wp, second->Wp};
+    return dlrt::launch_conv_pair(X, Wp, c, abits, wbits, enc_a == DLRT_TWOS, enc_w == DLRT_TWOS, enc_w == DLRT_BIPOLAR,
+                                  o, as_stream(stream));
 }
 
 dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbits, int *block_kernel, int *tile_rows,

@@ -31,16 +31,22 @@ dlrt_status by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int a
     return DLRT_ERR_BITS;
 }
 
+dlrt_status wave_by_abits(const dlrt::ContractArgs *g, const dlrt::FusedOut *o, int count, int abits, int wbits,
+                          bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream)
+{
+    switch (abits) {
+    case 1: return dlrt::launch_wave_a1(g, o, count, wbits, bipolar, conv, tm, ksplit, stream);
+    case 2: return dlrt::launch_wave_a2(g, o, count, wbits, bipolar, conv, tm, ksplit, stream);
+    case 3: return dlrt::launch_wave_a3(g, o, count, wbits, bipolar, conv, tm, ksplit, stream);
+    case 4: return dlrt::launch_wave_a4(g, o, count, wbits, bipolar, conv, tm, ksplit, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
 dlrt_status wave_by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
                           bool conv, int tm, int ksplit, hipStream_t stream)
 {
-    switch (abits) {
-    case 1: return dlrt::launch_wave_a1(g, o, wbits, bipolar, conv, tm, ksplit, stream);
-    case 2: return dlrt::launch_wave_a2(g, o, wbits, bipolar, conv, tm, ksplit, stream);
-    case 3: return dlrt::launch_wave_a3(g, o, wbits, bipolar, conv, tm, ksplit, stream);
-    case 4: return dlrt::launch_wave_a4(g, o, wbits, bipolar, conv, tm, ksplit, stream);
-    }
-    return DLRT_ERR_BITS;
+    return wave_by_abits(&g, &o, 1, abits, wbits, bipolar, conv, tm, ksplit, stream);
 }
 
 // ---- tile planning -----------------------------------------------------------------------------
@@ -131,9 +137,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     return by_abits(g, o, abits, wbits, bipolar, false, stream);
 }
 
-dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
-                        bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows, int ksplit,
-                        hipStream_t stream)
+static ContractArgs conv_args(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, bool a_msb_neg, bool w_msb_neg)
 {
     ContractArgs g{};
     g.A = X; g.W = Wp;
@@ -147,6 +151,30 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
     g.sh = c.sh; g.sw = c.sw; g.ph = c.ph; g.pw = c.pw;
     g.magicCw = magic_for(c.Cw);
     g.magicKW = magic_for(c.KW);
+    return g;
+}
+
+dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const Wp[2], const ConvShape c[2], int abits,
+                             int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut o[2],
+                             hipStream_t stream)
+{
+    ContractArgs g[2];
+    int ksplit = 1;
+    const int rows = wbits <= 2 ? 8 : 4;  // both problems on the smallest wave tile
+    for (int i = 0; i < 2; ++i) {
+        g[i] = conv_args(X[i], Wp[i], c[i], a_msb_neg, w_msb_neg);
+        const WavePlan p = plan_wave(g[i].M, g[i].N, g[i].Kw, abits, wbits, rows, 0);
+        if (!p.found) return DLRT_ERR_SHAPE;
+        if (p.ksplit > ksplit) ksplit = p.ksplit;  // one block shape for both: the deeper reduction decides
+    }
+    return wave_by_abits(g, o, 2, abits, wbits, bipolar, true, 1, ksplit, stream);
+}
+
+dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
+                        bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows, int ksplit,
+                        hipStream_t stream)
+{
+    const ContractArgs g = conv_args(X, Wp, c, a_msb_neg, w_msb_neg);
     if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
         const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
         if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have

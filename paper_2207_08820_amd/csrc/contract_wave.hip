@@ -34,10 +34,17 @@ using dlrt::FusedOut;
 
 template <int WB> struct WaveTN { static constexpr int value = WB <= 2 ? 4 : 2; };
 
+// One launch can carry two independent problems of the same bit widths (e.g. the two convolutions that
+// read the same activations): blocks [0, tiles0) work on problem 0, the rest on problem 1.  The arguments
+// of the block's problem are selected once into scalar registers.
 template <int AB, int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(512) void contract_wave_kernel(const ContractArgs g, const FusedOut o, const int ksplit,
-                                                            const int steps_per_wave)
+__global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair pair, const int ksplit)
 {
+    const bool second = (int)blockIdx.x >= pair.tiles0;
+    const ContractArgs g = second ? pair.g[1] : pair.g[0];
+    const FusedOut o = second ? pair.o[1] : pair.o[0];
+    const int steps_per_wave = second ? pair.steps_per_wave[1] : pair.steps_per_wave[0];
+    const int tile = second ? (int)blockIdx.x - pair.tiles0 : (int)blockIdx.x;
     constexpr int TN = WaveTN<WB>::value;
     constexpr int LX = 32 / TN, LY = 64 / LX;
     constexpr int ROWS = LY * TM;     // rows of the wave tile; it is 32 columns wide
@@ -54,7 +61,7 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const ContractArgs g
     uint4 *const lw = la + UA;
     const int lx = lane % LX, ly = lane / LX;
     const int tilesN = (g.N + 31) / 32;
-    const int tileM = blockIdx.x / tilesN, tileN = blockIdx.x - tileM * tilesN;
+    const int tileM = tile / tilesN, tileN = tile - tileM * tilesN;
     const int m0 = tileM * ROWS, n0 = tileN * 32;
 
     // ---- staging slots: lane + 64 t; four consecutive lanes fetch the 64 contiguous bytes of one
@@ -316,7 +323,7 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const ContractArgs g
 }
 
 template <int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
-dlrt_status launch(const ContractArgs &g, const FusedOut &o, int ksplit, hipStream_t stream)
+dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int ksplit, hipStream_t stream)
 {
     constexpr int AB = DLRT_ABITS;
     constexpr int TN = WaveTN<WB>::value;
@@ -325,44 +332,54 @@ dlrt_status launch(const ContractArgs &g, const FusedOut &o, int ksplit, hipStre
     } else {
         constexpr int ROWS = (64 / (32 / TN)) * TM;
         constexpr int units = 4 * AB * ROWS + 4 * WB * 32;
-        const int64_t tiles = (int64_t)((g.M + ROWS - 1) / ROWS) * ((g.N + 31) / 32);
-        if (tiles > 0x7fffffffLL) return DLRT_ERR_SHAPE;
-        const int steps = (g.Kw + 3) / 4;
-        const int steps_per_wave = (steps + ksplit - 1) / ksplit;
+        dlrt::WavePair pair{};
+        int64_t tiles = 0;
+        for (int i = 0; i < count; ++i) {
+            pair.g[i] = g[i];
+            pair.o[i] = o[i];
+            const int steps = (g[i].Kw + 3) / 4;
+            pair.steps_per_wave[i] = (steps + ksplit - 1) / ksplit;
+            const int64_t t = (int64_t)((g[i].M + ROWS - 1) / ROWS) * ((g[i].N + 31) / 32);
+            if (i == 0) pair.tiles0 = (int)t;
+            tiles += t;
+            if (tiles > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+        }
         const size_t lds_bytes = (size_t)ksplit * units * 16;
         hipLaunchKernelGGL((contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>), dim3((unsigned)tiles),
-                           dim3(64 * ksplit), lds_bytes, stream, g, o, ksplit, steps_per_wave);
+                           dim3(64 * ksplit), lds_bytes, stream, pair, ksplit);
         return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
     }
 }
 
 template <int WB, int TM, bool BIPOLAR, bool CONV>
-dlrt_status pick_vec(const ContractArgs &g, const FusedOut &o, int ksplit, hipStream_t stream)
+dlrt_status pick_vec(const ContractArgs *g, const FusedOut *o, int count, int ksplit, hipStream_t stream)
 {
-    if (g.vec == 4) return launch<WB, TM, 4, BIPOLAR, CONV>(g, o, ksplit, stream);
-    if (g.vec == 2) return launch<WB, TM, 2, BIPOLAR, CONV>(g, o, ksplit, stream);
-    return launch<WB, TM, 1, BIPOLAR, CONV>(g, o, ksplit, stream);
+    int vec = g[0].vec;  // both problems of a pair are loaded with the narrower of their widths
+    if (count > 1 && g[1].vec < vec) vec = g[1].vec;
+    if (vec == 4) return launch<WB, TM, 4, BIPOLAR, CONV>(g, o, count, ksplit, stream);
+    if (vec == 2) return launch<WB, TM, 2, BIPOLAR, CONV>(g, o, count, ksplit, stream);
+    return launch<WB, TM, 1, BIPOLAR, CONV>(g, o, count, ksplit, stream);
 }
 
 template <int WB, bool BIPOLAR, bool CONV>
-dlrt_status pick_tm(const ContractArgs &g, const FusedOut &o, int tm, int ksplit, hipStream_t stream)
+dlrt_status pick_tm(const ContractArgs *g, const FusedOut *o, int count, int tm, int ksplit, hipStream_t stream)
 {
-    if (tm == 4) return pick_vec<WB, 4, BIPOLAR, CONV>(g, o, ksplit, stream);
-    if (tm == 2) return pick_vec<WB, 2, BIPOLAR, CONV>(g, o, ksplit, stream);
-    return pick_vec<WB, 1, BIPOLAR, CONV>(g, o, ksplit, stream);
+    if (tm == 4) return pick_vec<WB, 4, BIPOLAR, CONV>(g, o, count, ksplit, stream);
+    if (tm == 2) return pick_vec<WB, 2, BIPOLAR, CONV>(g, o, count, ksplit, stream);
+    return pick_vec<WB, 1, BIPOLAR, CONV>(g, o, count, ksplit, stream);
 }
 
 template <bool CONV>
-dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, int tm, int ksplit,
+dlrt_status pick_wbits(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, int tm, int ksplit,
                        hipStream_t stream)
 {
     switch (wbits) {
     case 1:
-        return bipolar ? pick_tm<1, true, CONV>(g, o, tm, ksplit, stream)
-                       : pick_tm<1, false, CONV>(g, o, tm, ksplit, stream);
-    case 2: return pick_tm<2, false, CONV>(g, o, tm, ksplit, stream);
-    case 3: return pick_tm<3, false, CONV>(g, o, tm, ksplit, stream);
-    case 4: return pick_tm<4, false, CONV>(g, o, tm, ksplit, stream);
+        return bipolar ? pick_tm<1, true, CONV>(g, o, count, tm, ksplit, stream)
+                       : pick_tm<1, false, CONV>(g, o, count, tm, ksplit, stream);
+    case 2: return pick_tm<2, false, CONV>(g, o, count, tm, ksplit, stream);
+    case 3: return pick_tm<3, false, CONV>(g, o, count, tm, ksplit, stream);
+    case 4: return pick_tm<4, false, CONV>(g, o, count, tm, ksplit, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -374,11 +391,11 @@ namespace dlrt {
 #define DLRT_CAT2(a, b) a##b
 #define DLRT_CAT(a, b) DLRT_CAT2(a, b)
 
-dlrt_status DLRT_CAT(launch_wave_a, DLRT_ABITS)(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar,
-                                                 bool conv, int tm, int ksplit, hipStream_t stream)
+dlrt_status DLRT_CAT(launch_wave_a, DLRT_ABITS)(const ContractArgs *g, const FusedOut *o, int count, int wbits,
+                                                 bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream)
 {
-    return conv ? pick_wbits<true>(g, o, wbits, bipolar, tm, ksplit, stream)
-                : pick_wbits<false>(g, o, wbits, bipolar, tm, ksplit, stream);
+    return conv ? pick_wbits<true>(g, o, count, wbits, bipolar, tm, ksplit, stream)
+                : pick_wbits<false>(g, o, count, wbits, bipolar, tm, ksplit, stream);
 }
 
 }  // namespace dlrt

@@ -36,12 +36,21 @@ dlrt_status launch_contract_a2(const ContractArgs &g, const FusedOut &o, int wbi
 dlrt_status launch_contract_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
 dlrt_status launch_contract_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
 
-// Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n): tm = rows per lane (1, 2, 4), ksplit = waves
+// Kernel argument of the per-wave kernel: one problem, or two of the same bit widths in one launch
+// (blocks [0, tiles0) belong to the first).
+struct WavePair {
+    ContractArgs g[2];
+    FusedOut o[2];
+    int steps_per_wave[2];
+    int tiles0;
+};
+
+// Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n); g / o point at `count` (1 or 2) problems.: tm = rows per lane (1, 2, 4), ksplit = waves
 // per block that split the reduction (1, 2, 4, 8); both as planned by plan_wave().
-dlrt_status launch_wave_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
-dlrt_status launch_wave_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
-dlrt_status launch_wave_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
-dlrt_status launch_wave_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a1(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a2(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a3(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
+dlrt_status launch_wave_a4(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 
 // Conv geometry handed from the C ABI to the launcher.
 struct ConvShape {
@@ -56,6 +65,11 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
 dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
                         bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut &o, int tile_rows, int ksplit,
                         hipStream_t stream);
+
+// Two fused convolutions of the same bit widths in ONE launch of the per-wave kernel.
+dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const Wp[2], const ConvShape c[2], int abits,
+                             int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut o[2],
+                             hipStream_t stream);
 
 // What launch_gemm / launch_conv would pick (no hints).
 void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, int *tile_rows, int *tile_cols, int *ksplit);

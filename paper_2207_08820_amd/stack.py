@@ -43,8 +43,9 @@ class ConvStack:
     of the layers that read it (they must agree); a layer nobody reads keeps its own width."""
 
     def __init__(self, layers, weights_i8, scales, biases, abits, wbits, enc_w, device="cuda:0",
-                 fused: bool = True, keep_outputs: bool = True):
+                 fused: bool = True, keep_outputs: bool = True, pair_launches: bool = True):
         n = len(layers)
+        self.pair_launches = pair_launches
         self.abits, self.wbits, self.enc_w = _per_layer(abits, n), _per_layer(wbits, n), _per_layer(enc_w, n)
         self.qbits = list(self.abits)
         for i in range(n):
@@ -97,6 +98,33 @@ class ConvStack:
                                             out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
                                             out_packed=pl.out_packed, tile_rows=tile_rows, ksplit=ksplit)
 
+    def problem(self, i: int):
+        pl = self.layers[i]
+        L = pl.spec
+        return binding.conv_problem(self.layer_input(i), pl.wp, pl.scale, pl.bias, 1, L.H, L.W, L.Ci, L.Co, L.k, L.k,
+                                    (L.stride, L.stride), (L.pad, L.pad), qbits=self.qbits[i],
+                                    out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
+                                    out_packed=pl.out_packed)
+
+    def pairs(self):
+        """Launch schedule of the fused chain: a layer goes out together with a later layer that reads the
+        same input and has the same bit widths (a stride-2 conv with the 1x1 conv beside it, two 1x1 convs
+        on one tensor); the later one simply runs early, its readers still come after it.  Everything else
+        is a launch of its own."""
+        plan, done, n = [], set(), len(self.layers)
+        for i in range(n):
+            if i in done:
+                continue
+            key = (self.layers[i].spec.src, self.abits[i], self.wbits[i], self.enc_w[i])
+            mate = next((j for j in range(i + 1, n) if j not in done and
+                         (self.layers[j].spec.src, self.abits[j], self.wbits[j], self.enc_w[j]) == key), None)
+            if mate is None:
+                plan.append((i,))
+            else:
+                plan.append((i, mate))
+                done.add(mate)
+        return plan
+
     def layer_input(self, i: int):
         src = self.layers[i].spec.src
         return self.x0_packed if src < 0 else self.layers[src].out_packed
@@ -107,8 +135,13 @@ class ConvStack:
             # one stream on purpose: forking the side-branch 1x1 convs onto a second stream was
             # measured slower (0.170 against 0.128 ms), the cross-queue waits cost more than they hide
             binding.dlrt_pack_bitplanes(x0_u8, self.abits[0], binding.UNSIGNED, out=self.x0_packed)
-            for i in range(len(self.layers)):
-                self.run_layer_fused(i, self.layer_input(i))
+            for group in self.pairs() if self.pair_launches else [(i,) for i in range(len(self.layers))]:
+                if len(group) == 2:
+                    i, j = group
+                    binding.dlrt_bitserial_conv2d_fused_pair(self.problem(i), self.problem(j), self.abits[i],
+                                                             self.wbits[i], binding.UNSIGNED, self.enc_w[i])
+                else:
+                    self.run_layer_fused(group[0], self.layer_input(group[0]))
         else:
             for i, pl in enumerate(self.layers):
                 src = pl.spec.src

@@ -43,7 +43,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_gemm", "dlrt_bitserial_gemm_fused", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
+    assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_conv2d_fused_pair", "dlrt_bitserial_gemm", "dlrt_bitserial_gemm_fused", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
                      "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_query_plan", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
     for n in names:
         assert getattr(lib, n) is not None

@@ -392,6 +392,40 @@ def test_conv_fused_every_tile_height_and_reduction_split_gives_the_same_result(
         fused_case(dlrt, oracle, xb, wb, 1, 1, 2, 1, UNSIGNED, BIPOLAR, 2, 8, ksplit)
 
 
+def test_conv_fused_pair_two_problems_in_one_launch(dlrt, oracle):
+    """A stride-2 3x3 conv and the 1x1 stride-2 conv beside it (different reduction depths, so different
+    numbers of waves would be planned), then two unrelated problems with ragged shapes; bipolar too."""
+    cases = [((1, 28, 28, 128), (256, 3, 3, 128), 2, 1, (1, 28, 28, 128), (256, 1, 1, 128), 2, 0, 2, 2, TWOS),
+             ((2, 9, 7, 40), (70, 3, 3, 40), 1, 1, (1, 12, 12, 96), (33, 1, 1, 96), 1, 0, 2, 2, TWOS),
+             ((1, 20, 20, 256), (128, 1, 1, 256), 1, 0, (1, 20, 20, 256), (256, 1, 1, 256), 1, 0, 2, 1, BIPOLAR),
+             ((1, 10, 10, 64), (16, 3, 3, 64), 1, 1, (1, 6, 6, 512), (40, 3, 3, 512), 1, 1, 4, 4, TWOS)]
+    for idx, (xs0, ws0, st0, pd0, xs1, ws1, st1, pd1, abits, wbits, ew) in enumerate(cases):
+        probs, refs, keep = [], [], []
+        for k, (xs, ws, st, pd) in enumerate(((xs0, ws0, st0, pd0), (xs1, ws1, st1, pd1))):
+            x = inputs.uniform_values(xs, abits, UNSIGNED, 61000 + 10 * idx + k)
+            w = inputs.uniform_values(ws, wbits, ew, 62000 + 10 * idx + k)
+            ref = oracle.conv2d_i32(x, w, (st, st), (pd, pd))
+            scale, bias = calibrate(ref)
+            y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=2)
+            X = dlrt.dlrt_pack_bitplanes(src_tensor(x, UNSIGNED), abits, UNSIGNED)
+            Wp = dlrt.dlrt_pack_conv_weights(src_tensor(w, ew), wbits, ew)
+            Co, Mo = ws[0], ref.shape[0] * ref.shape[1] * ref.shape[2]
+            acc = torch.full(ref.shape, -7, dtype=torch.int32, device=DEV)
+            y = torch.full(ref.shape, -7.0, dtype=torch.float32, device=DEV)
+            packed = torch.full((Mo, 2, (Co + 31) // 32), -1, dtype=torch.int32, device=DEV)
+            sc, bs = dev(scale), dev(bias)
+            probs.append(dlrt.conv_problem(X, Wp, sc, bs, xs[0], xs[1], xs[2], xs[3], Co, ws[1], ws[2], (st, st), (pd, pd),
+                                           qbits=2, out_acc=acc, out_f32=y, out_packed=packed))
+            refs.append((ref, y_ref, oracle.pack_bitplanes(q_ref.reshape(Mo, Co).astype(np.int8), 2, UNSIGNED)))
+            keep.append((X, Wp, sc, bs, acc, y, packed))
+        dlrt.dlrt_bitserial_conv2d_fused_pair(probs[0], probs[1], abits, wbits, UNSIGNED, ew)
+        torch.cuda.synchronize()
+        for (ref, y_ref, p_ref), (_, _, _, _, acc, y, packed) in zip(refs, keep):
+            assert np.array_equal(acc.cpu().numpy(), ref), idx
+            assert np.array_equal(y.cpu().numpy(), y_ref), idx
+            assert np.array_equal(words(packed), p_ref), idx
+
+
 def test_conv_fused_rejects_hints_the_kernels_do_not_have(dlrt):
     X = torch.zeros((64, 4, 1), dtype=torch.int32, device=DEV)
     Wp = torch.zeros((8, 4, 9), dtype=torch.int32, device=DEV)
