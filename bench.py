@@ -44,6 +44,27 @@ def time_events(fn, iters):
     return start.elapsed_time(stop) / iters
 
 
+def time_graph(fn, reps=20, replays=5):
+    """Average milliseconds of one fn() when `reps` of them are recorded back to back into a HIP graph:
+    the time of the kernels themselves plus the gap between dependent launches, without the host's
+    enqueue cost (which exceeds the kernel time for the small layers)."""
+    import torch
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(reps):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
+    return time_events(graph.replay, replays) / reps
+
+
 def gemm_workload(abits, wbits, size, dev):
     import torch
 
@@ -90,12 +111,25 @@ def make_step(dlrt, t, gemm_events=None, fused=True):
     return step
 
 
-def stack_ms(dlrt, dev, which, iters=50):
+HBM_PEAK_BYTES = 8e12
+
+
+def layer_floors(L, abits, wbits, qbits, batch=1):
+    """Lower bounds of one fused conv layer in microseconds: its AND/BCNT lane-ops at the VALU peak,
+    and its algorithmic HBM bytes (packed input, packed weights, packed output) at the HBM peak."""
+    cw_in, cw_out = (L.Ci + 31) // 32, (L.Co + 31) // 32
+    nbytes = 4 * (batch * L.H * L.W * abits * cw_in + L.Co * wbits * L.k * L.k * cw_in
+                  + batch * L.Ho * L.Wo * qbits * cw_out)
+    return abits * wbits * batch * L.macs / 16.0 / VALU_PEAK_LANE_OPS * 1e6, nbytes / HBM_PEAK_BYTES * 1e6
+
+
+def stack_ms(dlrt, dev, which, iters=50, batch=1):
     """Whole conv chain of a model-shaped stack ("resnet18": 19 convs A2W2; "yolo": 16 convs A2 / bipolar
     W1).  Scale and bias come from the closed-form mean / deviation of a uniform-input layer; timing
     does not depend on the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
     conv launch per layer), the same chain enqueued eagerly from Python, and the unfused chain
-    (pack + conv + epilogue per layer); per-layer times are of the fused kernel alone."""
+    (pack + conv + epilogue per layer); per-layer times are of the fused kernel alone, launched back to
+    back from a HIP graph at batch 1 (so they include the gap between dependent launches, about 2.5 us)."""
     import torch
 
     from paper_2207_08820_amd import inputs
@@ -110,10 +144,11 @@ def stack_ms(dlrt, dev, which, iters=50):
     weights = inputs.stack_weights(config, layers, wbits, enc_w)
     scales = [np.full(L.Co, 1.0 / (sigma * np.sqrt(L.K)), np.float32) for L in layers]
     biases = [np.full(L.Co, 1.5 - mean * L.K / (sigma * np.sqrt(L.K)), np.float32) for L in layers]
-    x0 = torch.as_tensor(inputs.stack_input(config, layers).astype(np.uint8), device=dev)
+    x0 = torch.as_tensor(inputs.stack_input(config, layers, batch).astype(np.uint8), device=dev)
     out = {}
 
-    stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=True, keep_outputs=False)
+    stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=True, keep_outputs=False,
+                      batch=batch)
     stack.capture(x0)
     for _ in range(5):
         stack.replay()
@@ -123,8 +158,24 @@ def stack_ms(dlrt, dev, which, iters=50):
     per_layer = []
     for i, pl in enumerate(stack.layers):
         xin = stack.layer_input(i)
-        ms = time_events(lambda: stack.run_layer_fused(i, xin), iters)
-        per_layer.append({"layer": pl.spec.name, "M": pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K, "ms": round(ms, 5)})
+        ms = time_graph(lambda: stack.run_layer_fused(i, xin)) if batch == 1 else \
+            time_events(lambda: stack.run_layer_fused(i, xin), iters)
+        valu_us, hbm_us = layer_floors(pl.spec, 2, wbits, stack.qbits[i], batch)
+        plan = dlrt.dlrt_query_plan(batch * pl.spec.M, pl.spec.Co, pl.spec.k * pl.spec.k * (((pl.spec.Ci + 31) // 32) * 32),
+                                    2, wbits)
+        per_layer.append({"layer": pl.spec.name, "M": batch * pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K,
+                          "ms": round(ms, 5), "valu_floor_us": round(valu_us, 3), "hbm_floor_us": round(hbm_us, 3),
+                          "valu_frac": round(valu_us / (ms * 1e3), 4),
+                          "kernel": "block" if plan["block_kernel"] else "wave",
+                          "tile": [plan["tile_rows"], plan["tile_cols"]], "ksplit": plan["ksplit"]})
+    out["sum_valu_floor_us"] = sum(p["valu_floor_us"] for p in per_layer)
+    if batch > 1:
+        macs = batch * sum(L.macs for L in layers)
+        out["batch"] = batch
+        out["images_per_s"] = batch / (out["graph_fused_ms"] * 1e-3)
+        out["effective_tops"] = 2.0 * macs / (out["graph_fused_ms"] * 1e-3) / 1e12
+        out["valu_frac"] = out["sum_valu_floor_us"] / (out["graph_fused_ms"] * 1e3)
+        return out, per_layer
 
     unfused = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=False)
     for _ in range(3):
@@ -241,6 +292,13 @@ def main():
     extra["yolo_style_a2w1_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in yolo.items()}
     extra["yolo_style_per_layer"] = per_layer
     log(f"YOLOv5s-style A2W1 conv stack (16 convs): {yolo}")
+
+    # throughput of the same chains with many images per pass (large enough for the block kernel)
+    for name, which, b in (("resnet18_a2w2_conv_stack_batch64", "resnet18", 64), ("yolo_style_a2w1_conv_stack_batch16", "yolo", 16)):
+        res, per_layer = stack_ms(dlrt, dev, which, iters=10, batch=b)
+        extra[name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()}
+        extra[name + "_per_layer"] = per_layer
+        log(f"{name}: {res}")
 
     # comparison variant (not the judged path): the same GEMM on the unpacked int8 values with matrix instructions
     a_i8 = t["a"].view(torch.int8)

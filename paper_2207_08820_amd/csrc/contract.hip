@@ -163,6 +163,9 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     };
 
     const int nchunks = (g.Kw + kKC - 1) / kKC, nfull = g.Kw / kKC;
+    // 16-byte steps of the last chunk that hold any reduction words: a short or ragged reduction (a 1x1
+    // conv over 64 channels is 2 words) does not pay for the zero padding of a whole chunk
+    const int last_steps = (g.Kw - (nchunks - 1) * kKC + 3) / 4;
     auto fetch = [&](int chunk) {
         const int kbase = chunk * kKC;
         if (CONV) {
@@ -270,10 +273,13 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
             __builtin_amdgcn_sched_barrier(0);
         }
 #else
+        const int nsteps = chunk + 1 < nchunks ? kK4 : last_steps;  // block-uniform
 #pragma unroll
         for (int k4 = 0; k4 < kK4; ++k4) {
-            lds_load(0, k4);
-            mac(0);
+            if (k4 < nsteps) {
+                lds_load(0, k4);
+                mac(0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
 #endif

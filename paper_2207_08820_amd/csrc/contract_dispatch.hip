@@ -161,6 +161,16 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     ContractArgs g[2];
     int ksplit = 1;
     const int rows = wbits <= 2 ? 8 : 4;  // both problems on the smallest wave tile
+    // sharing a launch pays while a problem cannot fill the chip; one that is large enough for the block
+    // kernel (large batch) runs faster there, so such a pair goes out as two ordinary launches
+    if (!prefer_wave_kernel((int64_t)c[0].N * c[0].Ho * c[0].Wo, c[0].Co, abits, wbits) ||
+        !prefer_wave_kernel((int64_t)c[1].N * c[1].Ho * c[1].Wo, c[1].Co, abits, wbits)) {
+        for (int i = 0; i < 2; ++i) {
+            const dlrt_status st = launch_conv(X[i], Wp[i], c[i], abits, wbits, a_msb_neg, w_msb_neg, bipolar, o[i], 0, 0, stream);
+            if (st != DLRT_OK) return st;
+        }
+        return DLRT_OK;
+    }
     for (int i = 0; i < 2; ++i) {
         g[i] = conv_args(X[i], Wp[i], c[i], a_msb_neg, w_msb_neg);
         const WavePlan p = plan_wave(g[i].M, g[i].N, g[i].Kw, abits, wbits, rows, 0);

@@ -160,9 +160,9 @@ def yolo_style_stack():
     return layers
 
 
-def stack_input(config: int, layers) -> np.ndarray:
+def stack_input(config: int, layers, batch: int = 1) -> np.ndarray:
     L = layers[0]
-    return uniform_values((1, L.H, L.W, L.Ci), 2, UNSIGNED, seed_for(config, 0))
+    return uniform_values((batch, L.H, L.W, L.Ci), 2, UNSIGNED, seed_for(config, 0))
 
 
 def stack_weights(config: int, layers, wbits: int, enc_w: int):

@@ -43,9 +43,10 @@ class ConvStack:
     of the layers that read it (they must agree); a layer nobody reads keeps its own width."""
 
     def __init__(self, layers, weights_i8, scales, biases, abits, wbits, enc_w, device="cuda:0",
-                 fused: bool = True, keep_outputs: bool = True, pair_launches: bool = True):
+                 fused: bool = True, keep_outputs: bool = True, pair_launches: bool = True, batch: int = 1):
         n = len(layers)
         self.pair_launches = pair_launches
+        self.batch = B = int(batch)  # images per pass; the layer list describes one image
         self.abits, self.wbits, self.enc_w = _per_layer(abits, n), _per_layer(wbits, n), _per_layer(enc_w, n)
         self.qbits = list(self.abits)
         for i in range(n):
@@ -64,17 +65,17 @@ class ConvStack:
             pl = PackedLayer(L, wp, torch.as_tensor(s, device=self.device),
                              None if b is None else torch.as_tensor(b, device=self.device))
             if fused:
-                pl.out_packed = torch.empty((L.Ho * L.Wo, self.qbits[i], (L.Co + 31) // 32), dtype=torch.int32,
+                pl.out_packed = torch.empty((B * L.Ho * L.Wo, self.qbits[i], (L.Co + 31) // 32), dtype=torch.int32,
                                             device=self.device)
             else:
-                pl.xp = torch.empty((L.H * L.W, self.abits[i], (L.Ci + 31) // 32), dtype=torch.int32,
+                pl.xp = torch.empty((B * L.H * L.W, self.abits[i], (L.Ci + 31) // 32), dtype=torch.int32,
                                     device=self.device)
             if keep_outputs or not fused:
-                pl.acc = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.int32, device=self.device)
-                pl.q = torch.empty((1, L.Ho, L.Wo, L.Co), dtype=torch.uint8, device=self.device)
+                pl.acc = torch.empty((B, L.Ho, L.Wo, L.Co), dtype=torch.int32, device=self.device)
+                pl.q = torch.empty((B, L.Ho, L.Wo, L.Co), dtype=torch.uint8, device=self.device)
             self.layers.append(pl)
         L0 = layers[0]
-        self.x0_packed = torch.empty((L0.H * L0.W, self.abits[0], (L0.Ci + 31) // 32), dtype=torch.int32,
+        self.x0_packed = torch.empty((B * L0.H * L0.W, self.abits[0], (L0.Ci + 31) // 32), dtype=torch.int32,
                                      device=self.device)
 
     # ---- unfused: three launches per layer ----
@@ -82,7 +83,7 @@ class ConvStack:
         pl = self.layers[i]
         L = pl.spec
         binding.dlrt_pack_bitplanes(x_u8, self.abits[i], binding.UNSIGNED, out=pl.xp)
-        binding.dlrt_bitserial_conv2d(pl.xp, pl.wp, 1, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
+        binding.dlrt_bitserial_conv2d(pl.xp, pl.wp, self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
                                       (L.pad, L.pad), self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
                                       out=pl.acc)
         binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=False, qbits=self.qbits[i], out_q=pl.q)
@@ -92,8 +93,8 @@ class ConvStack:
         pl = self.layers[i]
         L = pl.spec
         binding.dlrt_bitserial_conv2d_fused(pl.xp if x_packed is None else x_packed, pl.wp, pl.scale, pl.bias,
-                                            1, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride), (L.pad, L.pad),
-                                            self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
+                                            self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
+                                            (L.pad, L.pad), self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
                                             qbits=self.qbits[i],
                                             out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
                                             out_packed=pl.out_packed, tile_rows=tile_rows, ksplit=ksplit)
@@ -101,7 +102,7 @@ class ConvStack:
     def problem(self, i: int):
         pl = self.layers[i]
         L = pl.spec
-        return binding.conv_problem(self.layer_input(i), pl.wp, pl.scale, pl.bias, 1, L.H, L.W, L.Ci, L.Co, L.k, L.k,
+        return binding.conv_problem(self.layer_input(i), pl.wp, pl.scale, pl.bias, self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k,
                                     (L.stride, L.stride), (L.pad, L.pad), qbits=self.qbits[i],
                                     out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
                                     out_packed=pl.out_packed)
