@@ -338,6 +338,22 @@ def main():
                           "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
                           "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
             log(sweep[-1])
+            if (ab, wb) == (2, 2):  # the same pair with two's-complement activations (only the sign of the MSB planes differs)
+                a_twos = torch.as_tensor(inputs.uniform_values((cs.M, cs.K), ab, inputs.TWOS, inputs.seed_for(5, 0) + 3), device=dev)
+                dlrt.dlrt_pack_bitplanes(a_twos, ab, inputs.TWOS, out=ts["A"])
+
+                def twos_gemm(ts=ts, cs=cs):
+                    dlrt.dlrt_bitserial_gemm(ts["A"], ts["W"], cs.M, cs.N, cs.K, cs.abits, cs.wbits, inputs.TWOS, cs.enc_w,
+                                             out=ts["C"])
+
+                for _ in range(3):
+                    twos_gemm()
+                torch.cuda.synchronize()
+                ms = time_events(twos_gemm, 20)
+                sweep.append({"abits": ab, "wbits": wb, "enc_a": "twos_complement", "gemm_ms": round(ms, 5),
+                              "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
+                              "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
+                log(sweep[-1])
             del ts
         extra["sweep_4096"] = sweep
 

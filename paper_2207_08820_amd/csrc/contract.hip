@@ -46,6 +46,9 @@
 #ifndef DLRT_WAVES_PER_EU
 #define DLRT_WAVES_PER_EU 2
 #endif
+#ifndef DLRT_PRIO_RAMP
+#define DLRT_PRIO_RAMP 0
+#endif
 #ifndef DLRT_REG_DOUBLE_BUFFER
 #define DLRT_REG_DOUBLE_BUFFER 0
 #endif
@@ -223,6 +226,12 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
 
     for (int chunk = 0; chunk < nchunks; ++chunk) {
         const int buf = chunk & 1;
+#if DLRT_PRIO_RAMP
+        // the wave that is further along its tile gets the issue slots first
+        if (4 * chunk >= 3 * nchunks) __builtin_amdgcn_s_setprio(3);
+        else if (2 * chunk >= nchunks) __builtin_amdgcn_s_setprio(2);
+        else if (4 * chunk >= nchunks) __builtin_amdgcn_s_setprio(1);
+#endif
         if (chunk + 1 < nchunks) fetch(chunk + 1);
 
         const uint4 *la = ldsA + buf * kTileA + ty;

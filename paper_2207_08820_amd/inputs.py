@@ -143,10 +143,12 @@ def resnet18_stack():
 
 
 # ---- config 4: YOLOv5s-style backbone shapes at 640x640 ----------------------------------------
-def yolo_style_stack():
+def yolo_style_stack(bottlenecks: bool = False):
     """16 convs built from the widths 32/64/128/256/512 at strides 2..32 only: per stage one 3x3
     stride-2 conv C/2 -> C, then three 1x1 convs C -> C/2, C/2 -> C/2 and C -> C.  A synthetic
-    stand-in for the shapes of such a backbone, not a copy of any model definition."""
+    stand-in for the shapes of such a backbone, not a copy of any model definition.
+    bottlenecks: each stage also gets a 3x3 stride-1 conv C/2 -> C/2 on the inner 1x1 conv's output
+    (20 convs)."""
     layers = []
     side, prev = 320, -1
     for C in (64, 128, 256, 512):
@@ -155,6 +157,8 @@ def yolo_style_stack():
         side //= 2
         layers.append(ConvLayer(f"c{C}_split_1x1", side, side, C, C // 2, 1, 1, 0, down))
         layers.append(ConvLayer(f"c{C}_inner_1x1", side, side, C // 2, C // 2, 1, 1, 0, down + 1))
+        if bottlenecks:
+            layers.append(ConvLayer(f"c{C}_bneck_3x3", side, side, C // 2, C // 2, 3, 1, 1, down + 2))
         layers.append(ConvLayer(f"c{C}_merge_1x1", side, side, C, C, 1, 1, 0, down))
         prev = len(layers) - 1
     return layers

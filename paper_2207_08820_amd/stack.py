@@ -8,6 +8,10 @@ just enough to run a list of quantized conv layers back to back.  Two ways to ru
   stack input goes through ``dlrt_pack_bitplanes``.
 * ``fused=False``: ``dlrt_pack_bitplanes`` -> ``dlrt_bitserial_conv2d`` -> ``dlrt_epilogue_f32`` per layer.
 
+A layer listed in ``f32_layers`` keeps its output in float32 (the dequantized ``y``), the way the paper
+leaves precision-sensitive layers unquantized (Section VII-D); its readers get it through the quantizer of
+Section IV fused into ``dlrt_pack_bitplanes`` (float32 source, the activation step size in ``act_scales``).
+
 ``capture()`` records the chain once into a HIP graph so that replays cost one launch from the host.
 All arithmetic happens in the library's kernels; this module only owns the buffers and the call order.
 """
@@ -31,6 +35,8 @@ class PackedLayer:
     acc: torch.Tensor = None     # int32 accumulators (unfused, or fused with keep_outputs)
     q: torch.Tensor = None       # uint8 requantized output (unfused, or fused with keep_outputs)
     out_packed: torch.Tensor = None  # fused: packed requantized output = input of the consumers
+    y: torch.Tensor = None       # float32 output of a layer that stays unquantized
+    act_scale: torch.Tensor = None   # step size its readers quantize y with (one value)
 
 
 def _per_layer(v, n):
@@ -43,8 +49,11 @@ class ConvStack:
     of the layers that read it (they must agree); a layer nobody reads keeps its own width."""
 
     def __init__(self, layers, weights_i8, scales, biases, abits, wbits, enc_w, device="cuda:0",
-                 fused: bool = True, keep_outputs: bool = True, pair_launches: bool = True, batch: int = 1):
+                 fused: bool = True, keep_outputs: bool = True, pair_launches: bool = True, batch: int = 1,
+                 f32_layers=(), act_scales=None):
         n = len(layers)
+        self.f32_layers = set(f32_layers)
+        act_scales = act_scales or {}
         self.pair_launches = pair_launches
         self.batch = B = int(batch)  # images per pass; the layer list describes one image
         self.abits, self.wbits, self.enc_w = _per_layer(abits, n), _per_layer(wbits, n), _per_layer(enc_w, n)
@@ -64,10 +73,13 @@ class ConvStack:
             wp = binding.dlrt_pack_conv_weights(wt, self.wbits[i], self.enc_w[i])
             pl = PackedLayer(L, wp, torch.as_tensor(s, device=self.device),
                              None if b is None else torch.as_tensor(b, device=self.device))
-            if fused:
+            if i in self.f32_layers:
+                pl.y = torch.empty((B, L.Ho, L.Wo, L.Co), dtype=torch.float32, device=self.device)
+                pl.act_scale = torch.tensor([act_scales[i]], dtype=torch.float32, device=self.device)
+            if fused or i in self.f32_layers:
                 pl.out_packed = torch.empty((B * L.Ho * L.Wo, self.qbits[i], (L.Co + 31) // 32), dtype=torch.int32,
                                             device=self.device)
-            else:
+            if not fused:
                 pl.xp = torch.empty((B * L.H * L.W, self.abits[i], (L.Ci + 31) // 32), dtype=torch.int32,
                                     device=self.device)
             if keep_outputs or not fused:
@@ -79,19 +91,39 @@ class ConvStack:
                                      device=self.device)
 
     # ---- unfused: three launches per layer ----
+    def requantize_f32(self, i: int):
+        """Quantize layer i's float32 output to its readers' activation width and pack it (one launch)."""
+        pl = self.layers[i]
+        binding.dlrt_pack_bitplanes(pl.y, self.qbits[i], binding.UNSIGNED, scale=pl.act_scale, out=pl.out_packed)
+
     def run_layer(self, i: int, x_u8: torch.Tensor):
         pl = self.layers[i]
         L = pl.spec
-        binding.dlrt_pack_bitplanes(x_u8, self.abits[i], binding.UNSIGNED, out=pl.xp)
-        binding.dlrt_bitserial_conv2d(pl.xp, pl.wp, self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
+        if L.src >= 0 and L.src in self.f32_layers:
+            xp = self.layers[L.src].out_packed  # quantized and packed from float32 when the source ran
+        else:
+            xp = binding.dlrt_pack_bitplanes(x_u8, self.abits[i], binding.UNSIGNED, out=pl.xp)
+        binding.dlrt_bitserial_conv2d(xp, pl.wp, self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
                                       (L.pad, L.pad), self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
                                       out=pl.acc)
-        binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=False, qbits=self.qbits[i], out_q=pl.q)
+        if i in self.f32_layers:
+            binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=True, out_f32=pl.y)
+            self.requantize_f32(i)
+        else:
+            binding.dlrt_epilogue_f32(pl.acc, pl.scale, pl.bias, want_f32=False, qbits=self.qbits[i], out_q=pl.q)
 
     # ---- fused: one launch per layer ----
     def run_layer_fused(self, i: int, x_packed: torch.Tensor, tile_rows: int = 0, ksplit: int = 0):
         pl = self.layers[i]
         L = pl.spec
+        if i in self.f32_layers:
+            binding.dlrt_bitserial_conv2d_fused(x_packed, pl.wp, pl.scale, pl.bias, self.batch, L.H, L.W, L.Ci, L.Co,
+                                                L.k, L.k, (L.stride, L.stride), (L.pad, L.pad), self.abits[i],
+                                                self.wbits[i], binding.UNSIGNED, self.enc_w[i], qbits=self.qbits[i],
+                                                out_acc=pl.acc if self.keep else None, out_f32=pl.y,
+                                                tile_rows=tile_rows, ksplit=ksplit)
+            self.requantize_f32(i)
+            return
         binding.dlrt_bitserial_conv2d_fused(pl.xp if x_packed is None else x_packed, pl.wp, pl.scale, pl.bias,
                                             self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k, (L.stride, L.stride),
                                             (L.pad, L.pad), self.abits[i], self.wbits[i], binding.UNSIGNED, self.enc_w[i],
@@ -116,8 +148,11 @@ class ConvStack:
         for i in range(n):
             if i in done:
                 continue
+            if i in self.f32_layers:
+                plan.append((i,))
+                continue
             key = (self.layers[i].spec.src, self.abits[i], self.wbits[i], self.enc_w[i])
-            mate = next((j for j in range(i + 1, n) if j not in done and
+            mate = next((j for j in range(i + 1, n) if j not in done and j not in self.f32_layers and
                          (self.layers[j].spec.src, self.abits[j], self.wbits[j], self.enc_w[j]) == key), None)
             if mate is None:
                 plan.append((i,))

@@ -245,7 +245,10 @@ def calibrate(acc):
     return scale, bias
 
 
-def oracle_stack(oracle, config, layers, wbits, enc_w, abits=2, batch=1):
+ACT_SCALE = 0.8  # step size of the quantizer that reads a float32 layer
+
+
+def oracle_stack(oracle, config, layers, wbits, enc_w, abits=2, batch=1, f32_layers=()):
     """Oracle pass, layer by layer, producing the frozen scale / bias arrays both sides use.  abits,
     wbits and enc_w are one value or one per layer; a layer's output takes the width its readers expect."""
     n = len(layers)
@@ -257,26 +260,34 @@ def oracle_stack(oracle, config, layers, wbits, enc_w, abits=2, batch=1):
     x0 = inputs.uniform_values((batch, L0.H, L0.W, L0.Ci), ab[0], UNSIGNED, inputs.seed_for(config, 0))
     weights = [inputs.uniform_values((L.Co, L.k, L.k, L.Ci), wb[i], ew[i], inputs.seed_for(config, 1, layer=i))
                for i, L in enumerate(layers)]
-    ref_acc, ref_q, scales, biases = [], [], [], []
+    ref_acc, ref_q, scales, biases, ref_y = [], [], [], [], {}
     for i, L in enumerate(layers):
         xin = x0 if L.src < 0 else ref_q[L.src]
         acc = oracle.conv2d_i32(xin.astype(np.int8), weights[i], (L.stride, L.stride), (L.pad, L.pad))
         s, b = calibrate(acc)
         levels = 1 << qb[i]
         s, b = (s * levels / 4).astype(np.float32), (b * levels / 4).astype(np.float32)
-        _, q = oracle.epilogue_f32(acc, s, b, qbits=qb[i])
+        if i in f32_layers:  # the layer stays float32; its readers quantize it (Section IV)
+            ref_y[i], _ = oracle.epilogue_f32(acc, s, b)
+            q = oracle.quantize(ref_y[i].reshape(-1, L.Co), np.float32(ACT_SCALE), qb[i], UNSIGNED)
+            q = q.reshape(acc.shape).astype(np.uint8)
+        else:
+            _, q = oracle.epilogue_f32(acc, s, b, qbits=qb[i])
         hist = np.bincount(q.ravel(), minlength=levels) / q.size
         # the chain must not degenerate to a constant: the values stay spread over the levels
         assert hist.max() < 0.75 and (hist >= 0.02).sum() >= min(levels, 4), (L.name, hist)
         ref_acc.append(acc), ref_q.append(q), scales.append(s), biases.append(b)
-    return x0, weights, ref_acc, ref_q, scales, biases, qb
+    return x0, weights, ref_acc, ref_q, scales, biases, qb, ref_y
 
 
-def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, graph=False, abits=2, batch=1):
+def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, graph=False, abits=2, batch=1,
+                             f32_layers=()):
     from paper_2207_08820_amd.stack import ConvStack
 
-    x0, weights, ref_acc, ref_q, scales, biases, qb = oracle_stack(oracle, config, layers, wbits, enc_w, abits, batch)
-    stack = ConvStack(layers, weights, scales, biases, abits, wbits, enc_w, device=DEV, fused=fused, batch=batch)
+    x0, weights, ref_acc, ref_q, scales, biases, qb, ref_y = oracle_stack(oracle, config, layers, wbits, enc_w, abits,
+                                                                          batch, f32_layers)
+    stack = ConvStack(layers, weights, scales, biases, abits, wbits, enc_w, device=DEV, fused=fused, batch=batch,
+                      f32_layers=f32_layers, act_scales={i: ACT_SCALE for i in f32_layers})
     assert stack.qbits == qb
     x0_dev = dev(x0.astype(np.uint8))
     if graph:
@@ -293,8 +304,11 @@ def run_stack_against_oracle(dlrt, oracle, config, layers, wbits, enc_w, fused, 
         torch.cuda.synchronize()
         for i, L in enumerate(layers):
             assert np.array_equal(stack.layers[i].acc.cpu().numpy(), ref_acc[i]), (L.name, rep)
-            assert np.array_equal(stack.layers[i].q.cpu().numpy(), ref_q[i]), (L.name, rep)
-            if fused:
+            if i in f32_layers:
+                assert np.array_equal(stack.layers[i].y.cpu().numpy(), ref_y[i]), (L.name, rep)
+            else:
+                assert np.array_equal(stack.layers[i].q.cpu().numpy(), ref_q[i]), (L.name, rep)
+            if fused or i in f32_layers:
                 want = oracle.pack_bitplanes(ref_q[i].reshape(-1, L.Co).astype(np.int8), qb[i], UNSIGNED)
                 assert np.array_equal(words(stack.layers[i].out_packed), want), (L.name, rep)
 
@@ -336,6 +350,21 @@ def test_resnet18_stack_batched(dlrt, oracle, fused, batch):
     """Several images per pass: batch 3 stays on the per-wave kernel (with paired launches), batch 20
     moves the first stages to the block kernel and splits their pairs into two launches."""
     run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS, fused, batch=batch)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_resnet18_stack_with_float32_pass_through_layers(dlrt, oracle, fused):
+    """Layers kept in float32 (the paper leaves precision-sensitive layers unquantized, Section VII-D):
+    the first conv, a stride-2 conv with a paired 1x1 beside it, and the last conv emit the dequantized
+    float32 result; the quantizer of Section IV, fused into the packer, feeds their readers."""
+    run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS, fused, f32_layers=(0, 4, 18))
+
+
+@pytest.mark.parametrize("batch", [1, 2])
+def test_yolo_style_stack_with_3x3_stride1_bottleneck_convs(dlrt, oracle, batch):
+    layers = inputs.yolo_style_stack(bottlenecks=True)
+    assert len(layers) == 20
+    run_stack_against_oracle(dlrt, oracle, 4, layers, 1, BIPOLAR, True, batch=batch)
 
 
 def test_yolo_style_stack_batched(dlrt, oracle):
