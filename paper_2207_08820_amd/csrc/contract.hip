@@ -298,60 +298,100 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     }
 
     // ---- combine the plane pairs (signs and shifts of Section V's double sum), then the optional fused
-    // epilogue of Section IV: scale / bias, requantization, and the bitplanes of the requantized result ----
+    // epilogue of Section IV: scale / bias, requantization, and the bitplanes of the requantized result.
+    // (x ^ mask) - mask negates x when mask is -1; the masks are uniform and live in scalar registers. ----
+    const int wneg = g.w_msb_neg ? -1 : 0, aneg = g.a_msb_neg ? -1 : 0;
+    auto combine = [&](int r, int s) {
+        int total = 0;
+#pragma unroll
+        for (int j = 0; j < AB; ++j) {
+            int part = 0;
+            if (BIPOLAR) {
+                part = 2 * acc[r][j][s] - rowpc[r][j];
+            } else {
+#pragma unroll
+                for (int i = 0; i + 1 < WB; ++i) part += acc[r][j][s * WB + i] << i;
+                const int msb = acc[r][j][s * WB + WB - 1] << (WB - 1);
+                part += (msb ^ wneg) - wneg;
+            }
+            part <<= j;
+            total += j + 1 < AB ? part : (part ^ aneg) - aneg;
+        }
+        return total;
+    };
+
     const float qmax = (float)((1 << o.qbits) - 1);
     const int Cwo = (g.N + 31) / 32;
     const int wave_row = ty & 3;  // this lane's row among the four rows (ty values) of its wave
-#pragma unroll
-    for (int r = 0; r < TM; ++r) {
-        const int m = m0 + ty + 16 * r;
-        uint32_t q[TN];
+    float sc[TN], bs[TN];
+    if (o.scale) {
 #pragma unroll
         for (int s = 0; s < TN; ++s) {
-            const int n = n0 + tx + 16 * s;
-            int total = 0;
-#pragma unroll
-            for (int j = 0; j < AB; ++j) {
-                int part = 0;
-                if (BIPOLAR) {
-                    part = 2 * acc[r][j][s] - rowpc[r][j];
-                } else {
-#pragma unroll
-                    for (int i = 0; i < WB; ++i) {
-                        const int term = acc[r][j][s * WB + i] << i;
-                        part += (g.w_msb_neg && i == WB - 1) ? -term : term;
-                    }
-                }
-                part <<= j;
-                total += (g.a_msb_neg && j == AB - 1) ? -part : part;
-            }
-            q[s] = 0;
-            if (m < g.M && n < g.N) {
-                const size_t idx = (size_t)m * g.N + n;
-                if (o.acc) o.acc[idx] = total;
-                if (o.scale) {
-                    const float y = __fmaf_rn((float)total, o.scale[n], o.bias ? o.bias[n] : 0.0f);
-                    if (o.y) o.y[idx] = y;
-                    q[s] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
-                    if (o.q) o.q[idx] = (uint8_t)q[s];
-                }
-            }
-        }
-        if (o.packed) {  // block-uniform: every lane takes part in the ballots
-            // A wave holds 4 rows x 16 columns per s: one ballot gives, for each of its rows, the 16-bit
-            // field of columns 16 s .. 16 s + 15; two fields make one output word.
-            for (int p = 0; p < o.qbits; ++p) {
-#pragma unroll
-                for (int c = 0; c < TN / 2; ++c) {
-                    const unsigned long long lo = __ballot((q[2 * c] >> p) & 1u), hi = __ballot((q[2 * c + 1] >> p) & 1u);
-                    const uint32_t word = (uint32_t)((lo >> (16 * wave_row)) & 0xffffu) |
-                                          ((uint32_t)((hi >> (16 * wave_row)) & 0xffffu) << 16);
-                    if (tx == 0 && m < g.M && n0 + 32 * c < g.N)
-                        o.packed[((size_t)m * o.qbits + p) * Cwo + n0 / 32 + c] = word;
-                }
-            }
+            const int n = min(n0 + tx + 16 * s, g.N - 1);
+            sc[s] = o.scale[n];
+            bs[s] = o.bias ? o.bias[n] : 0.0f;
         }
     }
+    // FULL: the tile lies wholly inside the output (block-uniform), so no element needs a bounds check;
+    // which outputs exist is uniform too, so each is one scalar branch per tile row, not one per element
+    auto write_tile = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+#pragma unroll
+        for (int r = 0; r < TM; ++r) {
+            const int m = m0 + ty + 16 * r;
+            const bool row_ok = FULL || m < g.M;
+            bool ok[TN];
+            int total[TN];
+#pragma unroll
+            for (int s = 0; s < TN; ++s) {
+                ok[s] = FULL || (row_ok && n0 + tx + 16 * s < g.N);
+                total[s] = combine(r, s);
+            }
+            const size_t row = (size_t)m * g.N + n0 + tx;  // element (m, n0 + tx); column s is 16 s further
+            if (o.acc) {
+#pragma unroll
+                for (int s = 0; s < TN; ++s)
+                    if (ok[s]) o.acc[row + 16 * s] = total[s];
+            }
+            uint32_t q[TN];
+#pragma unroll
+            for (int s = 0; s < TN; ++s) q[s] = 0;
+            if (o.scale) {
+                float y[TN];
+#pragma unroll
+                for (int s = 0; s < TN; ++s) {
+                    y[s] = __fmaf_rn((float)total[s], sc[s], bs[s]);
+                    if (ok[s]) q[s] = (uint32_t)fminf(fmaxf(rintf(y[s]), 0.0f), qmax);
+                }
+                if (o.y) {
+#pragma unroll
+                    for (int s = 0; s < TN; ++s)
+                        if (ok[s]) o.y[row + 16 * s] = y[s];
+                }
+                if (o.q) {
+#pragma unroll
+                    for (int s = 0; s < TN; ++s)
+                        if (ok[s]) o.q[row + 16 * s] = (uint8_t)q[s];
+                }
+            }
+            if (o.packed) {  // block-uniform: every lane takes part in the ballots
+                // A wave holds 4 rows x 16 columns per s: one ballot gives, for each of its rows, the 16-bit
+                // field of columns 16 s .. 16 s + 15; two fields make one output word.
+                for (int p = 0; p < o.qbits; ++p) {
+#pragma unroll
+                    for (int c = 0; c < TN / 2; ++c) {
+                        const unsigned long long lo = __ballot((q[2 * c] >> p) & 1u), hi = __ballot((q[2 * c + 1] >> p) & 1u);
+                        const uint32_t word = (uint32_t)((lo >> (16 * wave_row)) & 0xffffu) |
+                                              ((uint32_t)((hi >> (16 * wave_row)) & 0xffffu) << 16);
+                        if (tx == 0 && row_ok && (FULL || n0 + 32 * c < g.N))
+                            o.packed[((size_t)m * o.qbits + p) * Cwo + n0 / 32 + c] = word;
+                    }
+                }
+            }
+        }
+    };
+    if (m0 + BM <= g.M && n0 + BN <= g.N) write_tile(std::true_type{});
+    else write_tile(std::false_type{});
 }
 
 template <int B> struct LaneTile { static constexpr int value = B == 1 ? 8 : B == 2 ? 4 : 2; };
