@@ -117,8 +117,8 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
         iw0[t] = 0;
         if (CONV) {
             const int hw = g.Ho * g.Wo;
-            const int n = m / hw, rem = m - n * hw;
-            const int oh = rem / g.Wo, ow = rem - oh * g.Wo;
+            const int n = checked_div(m, hw, g.magicHW), rem = m - n * hw;
+            const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
             ih0[t] = oh * g.sh - g.ph;
             iw0[t] = ow * g.sw - g.pw;
             // plane `plane` of pixel (n, 0, 0); pixel and channel-word offsets are added per load

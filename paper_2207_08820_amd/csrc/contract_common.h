@@ -108,4 +108,8 @@ __device__ __forceinline__ void popc_acc(int &acc, uint32_t a)
 // n / d for 0 <= n, n * d < 2^32, with magic = ceil(2^32 / d) computed on the host (0 stands for d = 1).
 __device__ __forceinline__ int fast_div(int n, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)n, magic) : n; }
 
+// n / d where the host could not promise n * d < 2^32: magic 1 (no divisor has it) asks for the hardware's
+// division sequence instead, about ten times as many instructions.
+__device__ __forceinline__ int checked_div(int n, int d, uint32_t magic) { return magic == 1u ? n / d : fast_div(n, magic); }
+
 }  // namespace

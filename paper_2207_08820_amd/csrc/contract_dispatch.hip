@@ -151,6 +151,11 @@ static ContractArgs conv_args(const uint32_t *X, const uint32_t *Wp, const ConvS
     g.sh = c.sh; g.sw = c.sw; g.ph = c.ph; g.pw = c.pw;
     g.magicCw = magic_for(c.Cw);
     g.magicKW = magic_for(c.KW);
+    // row m < M is divided by Ho * Wo, the remainder (< Ho * Wo) by Wo: the multiply-high division is exact
+    // while dividend * divisor stays below 2^32
+    const int64_t hw = (int64_t)c.Ho * c.Wo;
+    g.magicHW = (int64_t)g.M * hw < (1LL << 32) ? magic_for((int)hw) : 1u;
+    g.magicWo = hw * c.Wo < (1LL << 32) ? magic_for(c.Wo) : 1u;
     return g;
 }
 

@@ -34,6 +34,25 @@ using dlrt::FusedOut;
 
 template <int WB> struct WaveTN { static constexpr int value = WB <= 2 ? 4 : 2; };
 
+// OR of `v` over each aligned group of LX (8 or 16) consecutive lanes, left in every lane of the group.
+// DPP lane swaps within a row of 16 lanes: the two quad permutations give every lane its quad's OR, the
+// half-row mirror (lane i <-> 7 - i) then brings in the other quad of the group of 8, the row mirror
+// (i <-> 15 - i) the other half of a group of 16.  No LDS round trip, unlike a shuffle.
+template <int LX>
+__device__ __forceinline__ uint32_t or_across(uint32_t v)
+{
+    static_assert(LX == 8 || LX == 16, "lane groups of 8 or 16");
+    constexpr int kSwap1 = 0xB1;        // quad_perm [1, 0, 3, 2]
+    constexpr int kSwap2 = 0x4E;        // quad_perm [2, 3, 0, 1]
+    constexpr int kHalfMirror = 0x141;  // row_half_mirror
+    constexpr int kMirror = 0x140;      // row_mirror
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kSwap1, 0xf, 0xf, false);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kSwap2, 0xf, 0xf, false);
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kHalfMirror, 0xf, 0xf, false);
+    if (LX == 16) v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kMirror, 0xf, 0xf, false);
+    return v;
+}
+
 // One launch can carry two independent problems of the same bit widths (e.g. the two convolutions that
 // read the same activations): blocks [0, tiles0) work on problem 0, the rest on problem 1.  The arguments
 // of the block's problem are selected once into scalar registers.
@@ -80,8 +99,8 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
         iw0[t] = 0;
         if (CONV) {
             const int hw = g.Ho * g.Wo;
-            const int n = m / hw, rem = m - n * hw;
-            const int oh = rem / g.Wo, ow = rem - oh * g.Wo;
+            const int n = checked_div(m, hw, g.magicHW), rem = m - n * hw;
+            const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
             ih0[t] = oh * g.sh - g.ph;
             iw0[t] = ow * g.sw - g.pw;
             srcA[t] = g.A + (size_t)n * g.H * g.Wd * AB * g.Cw + plane * g.Cw;
@@ -241,7 +260,9 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
         if (more) commit();
     }
 
-    // ---- plane pairs -> one integer per output (signs and shifts of Section V's double sum) ----
+    // ---- plane pairs -> one integer per output (signs and shifts of Section V's double sum);
+    // (x ^ mask) - mask negates x when mask is -1 ----
+    const int wneg = g.w_msb_neg ? -1 : 0, aneg = g.a_msb_neg ? -1 : 0;
     int total[TM][TN];
 #pragma unroll
     for (int r = 0; r < TM; ++r)
@@ -255,13 +276,12 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
                     part = 2 * acc[r][j][s] - rowpc[r][j];
                 } else {
 #pragma unroll
-                    for (int i = 0; i < WB; ++i) {
-                        const int term = acc[r][j][s * WB + i] << i;
-                        part += (g.w_msb_neg && i == WB - 1) ? -term : term;
-                    }
+                    for (int i = 0; i + 1 < WB; ++i) part += acc[r][j][s * WB + i] << i;
+                    const int msb = acc[r][j][s * WB + WB - 1] << (WB - 1);
+                    part += (msb ^ wneg) - wneg;
                 }
                 part <<= j;
-                sum += (g.a_msb_neg && j == AB - 1) ? -part : part;
+                sum += j + 1 < AB ? part : (part ^ aneg) - aneg;
             }
             total[r][s] = sum;
         }
@@ -286,36 +306,63 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
         }
     }
 
-    // ---- fused epilogue on the registers of wave 0 ----
+    // ---- fused epilogue on the registers of wave 0.  A wave at batch 1 is alone on its SIMD, so every taken
+    // branch and every LDS round trip here is exposed latency: the chained-layer case (only the packed
+    // output) is straight-line code, and the OR across the lanes of a row goes through DPP lane swaps. ----
     const float qmax = (float)((1 << o.qbits) - 1);
     const int Cwo = (g.N + 31) / 32;
+    bool live[TM][TN];
+    uint32_t q[TM][TN];
 #pragma unroll
-    for (int r = 0; r < TM; ++r) {
-        const int m = m0 + ly + LY * r;
-        uint32_t q[TN];
+    for (int r = 0; r < TM; ++r)
 #pragma unroll
         for (int s = 0; s < TN; ++s) {
-            const int n = n0 + lx * TN + s;
-            const bool live = m < g.M && n < g.N;
-            q[s] = 0;
-            if (live) {
-                const size_t idx = (size_t)m * g.N + n;
-                if (o.acc) o.acc[idx] = total[r][s];
-                if (o.scale) {
-                    const float y = __fmaf_rn((float)total[r][s], sc[s], bs[s]);
-                    if (o.y) o.y[idx] = y;
-                    q[s] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
-                    if (o.q) o.q[idx] = (uint8_t)q[s];
-                }
-            }
+            live[r][s] = m0 + ly + LY * r < g.M && n0 + lx * TN + s < g.N;
+            q[r][s] = 0;
         }
-        if (o.packed) {  // uniform: every lane takes part in the shuffles
-            for (int p = 0; p < o.qbits; ++p) {
+    if (o.acc) {
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int s = 0; s < TN; ++s)
+                if (live[r][s]) o.acc[(size_t)(m0 + ly + LY * r) * g.N + n0 + lx * TN + s] = total[r][s];
+    }
+    if (o.scale) {
+        float y[TM][TN];
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int s = 0; s < TN; ++s) {
+                y[r][s] = __fmaf_rn((float)total[r][s], sc[s], bs[s]);
+                const uint32_t v = (uint32_t)fminf(fmaxf(rintf(y[r][s]), 0.0f), qmax);
+                q[r][s] = live[r][s] ? v : 0u;  // columns beyond N are the zero padding of the packed words
+            }
+        if (o.y) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int s = 0; s < TN; ++s)
+                    if (live[r][s]) o.y[(size_t)(m0 + ly + LY * r) * g.N + n0 + lx * TN + s] = y[r][s];
+        }
+        if (o.q) {
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int s = 0; s < TN; ++s)
+                    if (live[r][s]) o.q[(size_t)(m0 + ly + LY * r) * g.N + n0 + lx * TN + s] = (uint8_t)q[r][s];
+        }
+    }
+    if (o.packed) {  // uniform: every lane takes part in the lane swaps
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (p >= o.qbits) break;
+#pragma unroll
+            for (int r = 0; r < TM; ++r) {
                 uint32_t word = 0;
 #pragma unroll
-                for (int s = 0; s < TN; ++s) word |= ((q[s] >> p) & 1u) << (lx * TN + s);
-#pragma unroll
-                for (int off = 1; off < LX; off <<= 1) word |= (uint32_t)__shfl_xor((int)word, off);
+                for (int s = 0; s < TN; ++s) word |= ((q[r][s] >> p) & 1u) << (lx * TN + s);
+                word = or_across<LX>(word);
+                const int m = m0 + ly + LY * r;
                 if (lx == 0 && m < g.M) o.packed[((size_t)m * o.qbits + p) * Cwo + tileN] = word;
             }
         }

@@ -28,6 +28,7 @@ struct ContractArgs {
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
+    uint32_t magicHW, magicWo;  // the same for Ho * Wo and Wo (output row -> image, pixel); 1: divide in hardware
 };
 
 // One translation unit per activation bit width (contract.hip with -DDLRT_ABITS=n).
