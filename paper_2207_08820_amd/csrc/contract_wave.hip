@@ -54,16 +54,24 @@ __device__ __forceinline__ uint32_t or_across(uint32_t v)
 }
 
 // One launch can carry two independent problems of the same bit widths (e.g. the two convolutions that
-// read the same activations): blocks [0, tiles0) work on problem 0, the rest on problem 1.  The arguments
-// of the block's problem are selected once into scalar registers.
+// read the same activations): blockIdx.y picks the problem.
 template <int AB, int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
 __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair pair, const int ksplit)
 {
-    const bool second = (int)blockIdx.x >= pair.tiles0;
-    const ContractArgs g = second ? pair.g[1] : pair.g[0];
-    const FusedOut o = second ? pair.o[1] : pair.o[0];
-    const int steps_per_wave = second ? pair.steps_per_wave[1] : pair.steps_per_wave[0];
-    const int tile = second ? (int)blockIdx.x - pair.tiles0 : (int)blockIdx.x;
+    const int which = blockIdx.y;
+    const int tile = blockIdx.x;
+    // All arguments are fetched here, in one batch of scalar loads: left to itself the compiler loads each
+    // field where it is first used, and a wave that is alone on its SIMD then waits out a round trip to
+    // the scalar cache a dozen times before its first global load is even issued.
+    const ContractArgs g = pair.g[which];
+    const FusedOut o = pair.o[which];
+    const int steps_per_wave = pair.steps_per_wave[which], tiles = pair.tiles[which];
+    const uint32_t magicTilesN = pair.magicTilesN[which];
+    asm volatile("" ::"s"(tiles), "s"(magicTilesN), "s"(g.A), "s"(g.W), "s"(g.M), "s"(g.N), "s"(g.Kw), "s"(g.a_msb_neg), "s"(g.w_msb_neg), "s"(g.H),
+                 "s"(g.Wd), "s"(g.Cw), "s"(g.KW), "s"(g.Ho), "s"(g.Wo), "s"(g.sh), "s"(g.sw), "s"(g.ph), "s"(g.pw),
+                 "s"(g.magicCw), "s"(g.magicKW), "s"(g.magicHW), "s"(g.magicWo), "s"(o.acc), "s"(o.y), "s"(o.q),
+                 "s"(o.packed), "s"(o.scale), "s"(o.bias), "s"(o.qbits), "s"(steps_per_wave));
+    if (tile >= tiles) return;  // the other problem of the pair has more tiles
     constexpr int TN = WaveTN<WB>::value;
     constexpr int LX = 32 / TN, LY = 64 / LX;
     constexpr int ROWS = LY * TM;     // rows of the wave tile; it is 32 columns wide
@@ -80,7 +88,7 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     uint4 *const lw = la + UA;
     const int lx = lane % LX, ly = lane / LX;
     const int tilesN = (g.N + 31) / 32;
-    const int tileM = tile / tilesN, tileN = tile - tileM * tilesN;
+    const int tileM = checked_div(tile, tilesN, magicTilesN), tileN = tile - tileM * tilesN;
     const int m0 = tileM * ROWS, n0 = tileN * 32;
 
     // ---- staging slots: lane + 64 t; four consecutive lanes fetch the 64 contiguous bytes of one
@@ -387,12 +395,14 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
             const int steps = (g[i].Kw + 3) / 4;
             pair.steps_per_wave[i] = (steps + ksplit - 1) / ksplit;
             const int64_t t = (int64_t)((g[i].M + ROWS - 1) / ROWS) * ((g[i].N + 31) / 32);
-            if (i == 0) pair.tiles0 = (int)t;
-            tiles += t;
-            if (tiles > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+            if (t > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+            pair.tiles[i] = (int)t;
+            const int64_t tn = (g[i].N + 31) / 32;  // tile index < t is divided by tn
+            pair.magicTilesN[i] = t * tn >= (1LL << 32) ? 1u : tn == 1 ? 0u : (uint32_t)(((1ULL << 32) + tn - 1) / tn);
+            if (t > tiles) tiles = t;
         }
         const size_t lds_bytes = (size_t)ksplit * units * 16;
-        hipLaunchKernelGGL((contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>), dim3((unsigned)tiles),
+        hipLaunchKernelGGL((contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>), dim3((unsigned)tiles, (unsigned)count),
                            dim3(64 * ksplit), lds_bytes, stream, pair, ksplit);
         return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
     }

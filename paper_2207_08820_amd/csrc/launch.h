@@ -37,13 +37,16 @@ dlrt_status launch_contract_a2(const ContractArgs &g, const FusedOut &o, int wbi
 dlrt_status launch_contract_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
 dlrt_status launch_contract_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
 
-// Kernel argument of the per-wave kernel: one problem, or two of the same bit widths in one launch
-// (blocks [0, tiles0) belong to the first).
+// Kernel argument of the per-wave kernel: one problem, or two of the same bit widths in one launch.
+// blockIdx.y names the problem, so a wave knows from its first instruction where its arguments lie and
+// fetches them in one round trip; the grid is as wide as the larger problem and the surplus blocks of
+// the smaller one leave at once.
 struct WavePair {
     ContractArgs g[2];
     FusedOut o[2];
     int steps_per_wave[2];
-    int tiles0;
+    int tiles[2];
+    uint32_t magicTilesN[2];  // for tile / ceil(N / 32); same convention as ContractArgs::magicHW
 };
 
 // Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n); g / o point at `count` (1 or 2) problems.: tm = rows per lane (1, 2, 4), ksplit = waves
