@@ -65,12 +65,12 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     // the scalar cache a dozen times before its first global load is even issued.
     const ContractArgs g = pair.g[which];
     const FusedOut o = pair.o[which];
-    const int steps_per_wave = pair.steps_per_wave[which], tiles = pair.tiles[which];
+    const int steps_base = pair.steps_base[which], steps_rem = pair.steps_rem[which], tiles = pair.tiles[which];
     const uint32_t magicTilesN = pair.magicTilesN[which];
     asm volatile("" ::"s"(tiles), "s"(magicTilesN), "s"(g.A), "s"(g.W), "s"(g.M), "s"(g.N), "s"(g.Kw), "s"(g.a_msb_neg), "s"(g.w_msb_neg), "s"(g.H),
                  "s"(g.Wd), "s"(g.Cw), "s"(g.KW), "s"(g.Ho), "s"(g.Wo), "s"(g.sh), "s"(g.sw), "s"(g.ph), "s"(g.pw),
                  "s"(g.magicCw), "s"(g.magicKW), "s"(g.magicHW), "s"(g.magicWo), "s"(o.acc), "s"(o.y), "s"(o.q),
-                 "s"(o.packed), "s"(o.scale), "s"(o.bias), "s"(o.qbits), "s"(steps_per_wave));
+                 "s"(o.packed), "s"(o.scale), "s"(o.bias), "s"(o.qbits), "s"(steps_base), "s"(steps_rem));
     if (tile >= tiles) return;  // the other problem of the pair has more tiles
     constexpr int TN = WaveTN<WB>::value;
     constexpr int LX = 32 / TN, LY = 64 / LX;
@@ -212,7 +212,9 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
 
     // this wave's slice of the reduction, in steps of 4 words
     const int steps = (g.Kw + 3) / 4;
-    const int s_begin = min(ks * steps_per_wave, steps), s_end = min(s_begin + steps_per_wave, steps);
+    // The waves that start first (they are alone on their SIMD until the block's later waves arrive) take
+    // the odd steps, so that the waves sharing a SIMD finish together.
+    const int s_begin = ks * steps_base + min(ks, steps_rem), s_end = s_begin + steps_base + (ks < steps_rem ? 1 : 0);
 
     if (s_begin < s_end) {
         fetch(s_begin * 4);
@@ -393,7 +395,8 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
             pair.g[i] = g[i];
             pair.o[i] = o[i];
             const int steps = (g[i].Kw + 3) / 4;
-            pair.steps_per_wave[i] = (steps + ksplit - 1) / ksplit;
+            pair.steps_base[i] = steps / ksplit;
+            pair.steps_rem[i] = steps % ksplit;
             const int64_t t = (int64_t)((g[i].M + ROWS - 1) / ROWS) * ((g[i].N + 31) / 32);
             if (t > 0x7fffffffLL) return DLRT_ERR_SHAPE;
             pair.tiles[i] = (int)t;

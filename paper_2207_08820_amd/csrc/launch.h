@@ -44,7 +44,7 @@ dlrt_status launch_contract_a4(const ContractArgs &g, const FusedOut &o, int wbi
 struct WavePair {
     ContractArgs g[2];
     FusedOut o[2];
-    int steps_per_wave[2];
+    int steps_base[2], steps_rem[2];  // 4-word steps per wave: base, and one more for the first `rem` waves
     int tiles[2];
     uint32_t magicTilesN[2];  // for tile / ceil(N / 32); same convention as ContractArgs::magicHW
 };
