@@ -191,11 +191,11 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
             if (!CONV) {
 #pragma unroll
                 for (int t = 0; t < MapA::kPerThread; ++t)
-                    stageA[t] = load4_tail(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
+                    stageA[t] = load4_tail<VEC>(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
             }
 #pragma unroll
             for (int t = 0; t < MapW::kPerThread; ++t)
-                stageW[t] = load4_tail(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
+                stageW[t] = load4_tail<VEC>(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
         }
     };
     auto commit = [&](int buf) {

@@ -17,16 +17,27 @@ __device__ __forceinline__ uint4 load4(const uint32_t *p)
     return make_uint4(p[0], p[1], p[2], p[3]);
 }
 
-// p points at word k0 of a plane of kend words; words at or beyond kend read as zero.  Branch-free:
-// out-of-range words are fetched from the plane's last word and then discarded.
+// p points at word k0 of a plane of kend words; words at or beyond kend read as zero.  k0 and kend are
+// multiples of VEC (the launch code picks VEC so), so a group of VEC words lies wholly inside or wholly
+// outside the plane.  Branch-free: an outside group is fetched from the plane's last group and discarded.
+template <int VEC>
 __device__ __forceinline__ uint4 load4_tail(const uint32_t *p, int k0, int kend)
 {
     uint32_t w[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int k = k0 + e;
-        const uint32_t t = p[(k < kend ? k : kend - 1) - k0];
-        w[e] = k < kend ? t : 0u;
+    for (int e = 0; e < 4; e += VEC) {
+        const bool ok = k0 + e < kend;
+        const uint32_t *q = p + (ok ? e : kend - VEC - k0);
+        if (VEC == 4) {
+            const uint4 t = *reinterpret_cast<const uint4 *>(q);
+            w[0] = ok ? t.x : 0u; w[1] = ok ? t.y : 0u; w[2] = ok ? t.z : 0u; w[3] = ok ? t.w : 0u;
+        } else if (VEC == 2) {
+            const uint2 t = *reinterpret_cast<const uint2 *>(q);
+            w[e] = ok ? t.x : 0u; w[e + 1] = ok ? t.y : 0u;
+        } else {
+            const uint32_t t = *q;
+            w[e] = ok ? t : 0u;
+        }
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
@@ -106,7 +117,13 @@ __device__ __forceinline__ void popc_acc(int &acc, uint32_t a)
 }
 
 // n / d for 0 <= n, n * d < 2^32, with magic = ceil(2^32 / d) computed on the host (0 stands for d = 1).
-__device__ __forceinline__ int fast_div(int n, uint32_t magic) { return magic ? (int)__umulhi((uint32_t)n, magic) : n; }
+// Branch-free on purpose (the mask adds n back when d = 1): the magic is uniform, and the compiler
+// otherwise turns the two cases into a branch, which a wave that is alone on its SIMD pays for in full.
+__device__ __forceinline__ int fast_div(int n, uint32_t magic)
+{
+    const uint32_t one = (uint32_t)-(int)(magic == 0u);
+    return (int)(__umulhi((uint32_t)n, magic) + ((uint32_t)n & one));
+}
 
 // n / d where the host could not promise n * d < 2^32: magic 1 (no divisor has it) asks for the hardware's
 // division sequence instead, about ten times as many instructions.

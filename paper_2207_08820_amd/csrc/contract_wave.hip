@@ -172,10 +172,10 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
         } else {
             if (!CONV) {
 #pragma unroll
-                for (int t = 0; t < NA; ++t) stageA[t] = load4_tail(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
+                for (int t = 0; t < NA; ++t) stageA[t] = load4_tail<VEC>(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
             }
 #pragma unroll
-            for (int t = 0; t < NW; ++t) stageW[t] = load4_tail(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
+            for (int t = 0; t < NW; ++t) stageW[t] = load4_tail<VEC>(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
         }
     };
     auto commit = [&]() {
@@ -204,10 +204,14 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     // scale / bias of this lane's columns: fetched now so that their latency hides behind the reduction
     float sc[TN], bs[TN];
 #pragma unroll
-    for (int s = 0; s < TN; ++s) {
-        const int n = min(n0 + lx * TN + s, g.N - 1);
-        sc[s] = (o.scale && ks == 0) ? o.scale[n] : 0.0f;
-        bs[s] = (o.bias && ks == 0) ? o.bias[n] : 0.0f;
+    for (int s = 0; s < TN; ++s) sc[s] = bs[s] = 0.0f;
+    if (ks == 0 && o.scale) {
+#pragma unroll
+        for (int s = 0; s < TN; ++s) sc[s] = o.scale[min(n0 + lx * TN + s, g.N - 1)];
+        if (o.bias) {
+#pragma unroll
+            for (int s = 0; s < TN; ++s) bs[s] = o.bias[min(n0 + lx * TN + s, g.N - 1)];
+        }
     }
 
     // this wave's slice of the reduction, in steps of 4 words
