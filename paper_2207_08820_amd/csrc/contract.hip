@@ -43,6 +43,9 @@
 // .74 .82 .83 .87 .85 either way.  One block per tile lets the hardware hand tiles to whichever compute
 // unit frees up first, which is worth more than the saved set-up.  Half-height lane tiles (twice as many,
 // shorter blocks): .77 .86 .91 .95 .91, no better.
+// The two waves that share a SIMD start together, take the same time and so run prologue, loop and epilogue
+// in lockstep; DLRT_PRIO_RAMP raises a wave's priority along its K loop to pull them apart.  Measured: no
+// change at any K (the pair falls back into step within a tile), so it is off.
 #ifndef DLRT_WAVES_PER_EU
 #define DLRT_WAVES_PER_EU 2
 #endif
