@@ -166,7 +166,7 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1):
         per_layer.append({"layer": pl.spec.name, "M": batch * pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K,
                           "ms": round(ms, 5), "valu_floor_us": round(valu_us, 3), "hbm_floor_us": round(hbm_us, 3),
                           "valu_frac": round(valu_us / (ms * 1e3), 4),
-                          "kernel": "block" if plan["block_kernel"] else "wave",
+                          "kernel": plan["kernel"],
                           "tile": [plan["tile_rows"], plan["tile_cols"]], "ksplit": plan["ksplit"]})
     out["sum_valu_floor_us"] = sum(p["valu_floor_us"] for p in per_layer)
     if batch > 1:

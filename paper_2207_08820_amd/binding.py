@@ -200,7 +200,9 @@ def dlrt_query_plan(M: int, N: int, K: int, abits: int, wbits: int) -> dict:
     """Kernel and tile the library would use for an M x N x K contraction (host only)."""
     out = [ctypes.c_int() for _ in range(4)]
     _check(load().dlrt_query_plan(M, N, K, abits, wbits, *[ctypes.byref(o) for o in out]), "dlrt_query_plan")
-    return dict(block_kernel=bool(out[0].value), tile_rows=out[1].value, tile_cols=out[2].value, ksplit=out[3].value)
+    kind = ("wave", "block", "rows")[out[0].value]
+    return dict(kernel=kind, block_kernel=kind == "block", tile_rows=out[1].value, tile_cols=out[2].value,
+                ksplit=out[3].value)
 
 
 def dlrt_unpacked_gemm_i8(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:

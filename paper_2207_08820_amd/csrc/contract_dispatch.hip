@@ -102,6 +102,27 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
     return best;
 }
 
+// The row kernel (one output row per lane, whole reduction in registers) wins where the tiled kernels are
+// mostly padding: a reduction of a few words, few output columns, and enough rows to fill the chip with one
+// lane per row.  Measured on 1x1 conv layers of 32 .. 512 channels at batch 1 .. 64: with N * Kw <= 256 it is
+// 1.3 to 5 times faster than the better of the other two from about 16 K rows on; beyond that product the
+// block kernel catches up.
+bool prefer_rows_kernel(int64_t M, int N, int Kw)
+{
+    return Kw <= dlrt::kRowKernelMaxWords && M >= 16384 && (int64_t)N * Kw <= 256;
+}
+
+// Row kernel: a wave covers 64 rows x ncols columns.  One column group per row block amortises the row's
+// load and set-up best; the columns are split further (down to 32) while there are fewer waves than would
+// fill the chip twice.
+int plan_rows(int M, int N)
+{
+    const int64_t row_blocks = ((int64_t)M + 63) / 64;
+    int ncols = (N + 31) / 32 * 32;
+    while (ncols > 32 && row_blocks * ((N + ncols - 1) / ncols) < 2048) ncols = (ncols / 2 + 31) / 32 * 32;
+    return ncols;
+}
+
 }  // namespace
 
 namespace dlrt {
@@ -110,6 +131,13 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
 {
     const bool wave = prefer_wave_kernel(M, N, abits, wbits);
     int rows = block_tile(abits), cols = block_tile(wbits), ks = 1;
+    if (prefer_rows_kernel(M, N, Kw)) {
+        if (block_kernel) *block_kernel = 2;
+        if (tile_rows) *tile_rows = 64;
+        if (tile_cols) *tile_cols = plan_rows(M, N);
+        if (ksplit) *ksplit = 1;
+        return;
+    }
     if (wave) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
         rows = (wbits <= 2 ? 8 : 4) * p.tm;
@@ -130,6 +158,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
+    if (prefer_rows_kernel(M, N, Kw)) return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N), stream);
     if (prefer_wave_kernel(M, N, abits, wbits)) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
         return wave_by_abits(g, o, abits, wbits, bipolar, false, p.tm, p.ksplit, stream);
@@ -190,6 +219,13 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
                         hipStream_t stream)
 {
     const ContractArgs g = conv_args(X, Wp, c, a_msb_neg, w_msb_neg);
+    const bool rows_fit = c.KH == 1 && c.KW == 1 && c.ph == 0 && c.pw == 0 && g.Kw <= kRowKernelMaxWords;
+    if (tile_rows == 64) {  // hint: the row kernel, ksplit groups of 32 columns per wave
+        if (!rows_fit || ksplit < 0 || ksplit > 2048) return DLRT_ERR_SHAPE;
+        return launch_rows(g, o, abits, wbits, bipolar, true, ksplit > 0 ? 32 * ksplit : plan_rows(g.M, g.N), stream);
+    }
+    if (tile_rows == 0 && ksplit == 0 && rows_fit && prefer_rows_kernel(g.M, g.N, g.Kw))
+        return launch_rows(g, o, abits, wbits, bipolar, true, plan_rows(g.M, g.N), stream);
     if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
         const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
         if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have

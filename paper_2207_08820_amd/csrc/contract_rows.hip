@@ -1,0 +1,212 @@
+// Bit-serial contraction for SHORT reductions (at most 8 packed words, i.e. 256 elements): GEMMs and
+// 1x1 convolutions over few channels, where the tiled kernels are mostly padding (their reduction step
+// is 4 words, their tiles 32 or more columns wide, and their per-tile set-up outweighs the work).
+//
+// Same arithmetic as contract.hip (Section V of arXiv 2207.08820: popcount(W[i] & A[j]) per plane pair,
+// shifts and signs applied once per output), decomposed the other way round: a LANE owns one output
+// row.  It keeps the row's activation planes in registers (abits x KW words) and walks over the output
+// columns; the weight words, scale and bias of a column are the same for every lane of the wave, so
+// they are fetched with uniform (scalar) loads and feed the VALU as scalar operands: no LDS, no barrier,
+// no lane-to-lane traffic.  The fused epilogue (Section IV: y = acc * scale + bias, requantization)
+// runs per output, and the lane assembles the bitplane words of ITS row of the next layer's packed
+// activations bit by bit, so the packed output needs no ballot or shuffle either.
+//
+// A wave covers 64 rows x `ncols` columns (a multiple of 32, so that waves own whole output words);
+// the grid is rows/64 x N/ncols.  int32 / float / uint8 outputs are written one element per lane with
+// a row stride between lanes: correct, but only the packed output is a fast path.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "contract_common.h"
+#include "dlrt.h"
+#include "launch.h"
+
+namespace {
+
+using dlrt::ContractArgs;
+using dlrt::FusedOut;
+
+constexpr int kRowsPerBlock = 64;
+
+template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
+__global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
+                                                                       const int ncols,
+                                                                       const uint32_t *__restrict__ Wp,
+                                                                       const float *__restrict__ scale,
+                                                                       const float *__restrict__ bias)
+{
+    // Wp / scale / bias repeat g.W / o.scale / o.bias as parameters of their own: only a read-only
+    // pointer that provably aliases none of the stores is loaded through the scalar unit.
+    const int m = blockIdx.x * kRowsPerBlock + threadIdx.x;
+    const int mc = min(m, g.M - 1);  // rows beyond the matrix are computed on the last row, never stored
+    const int n0 = blockIdx.y * ncols, n1 = min(n0 + ncols, g.N);
+
+    // ---- this lane's activation row: abits planes of Kw words, zero beyond Kw ----
+    const uint32_t *arow;
+    if (CONV) {  // 1x1 convolution without padding: output pixel (oh, ow) reads input pixel (oh*sh, ow*sw)
+        const int hw = g.Ho * g.Wo;
+        const int img = checked_div(mc, hw, g.magicHW), rem = mc - img * hw;
+        const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
+        arow = g.A + ((size_t)(img * g.H + oh * g.sh) * g.Wd + ow * g.sw) * (AB * g.Kw);
+    } else {
+        arow = g.A + (size_t)mc * (AB * g.Kw);
+    }
+    uint32_t a[AB][KW];
+    int rowpc[AB];
+#pragma unroll
+    for (int j = 0; j < AB; ++j) {
+        rowpc[j] = 0;
+#pragma unroll
+        for (int k = 0; k < KW; ++k) {
+            a[j][k] = k < g.Kw ? arow[j * g.Kw + k] : 0u;
+            if (BIPOLAR) rowpc[j] += __popc(a[j][k]);
+        }
+    }
+
+    const int wneg = g.w_msb_neg ? -1 : 0, aneg = g.a_msb_neg ? -1 : 0;  // (x ^ mask) - mask negates when mask is -1
+    const float qmax = (float)((1 << o.qbits) - 1);
+    const int Cwo = (g.N + 31) / 32;
+    const bool row_ok = m < g.M;
+    const bool packed_only = !o.acc && !o.y && !o.q;  // the chained-layer case: nothing but the packed words
+
+    // One output.  n is uniform over the wave, so the weight words, scale and bias come through
+    // scalar loads and the AND takes them as scalar operands.
+    auto output = [&](int n) {
+        const uint32_t *w = Wp + (size_t)n * (WB * g.Kw);
+        int total = 0;
+#pragma unroll
+        for (int j = 0; j < AB; ++j) {
+            int part = 0;
+#pragma unroll
+            for (int i = 0; i < WB; ++i) {
+                int acc = 0;
+#pragma unroll
+                for (int k = 0; k < KW; ++k)  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
+                    acc += __popc(a[j][k] & w[i * g.Kw + (k < g.Kw ? k : g.Kw - 1)]);
+                if (BIPOLAR) part = 2 * acc - rowpc[j];
+                else if (i + 1 < WB) part += acc << i;
+                else part += ((acc << i) ^ wneg) - wneg;
+            }
+            part <<= j;
+            total += j + 1 < AB ? part : (part ^ aneg) - aneg;
+        }
+        return total;
+    };
+
+    uint32_t word[4] = {0u, 0u, 0u, 0u};
+    auto add_bits = [&](int n, uint32_t q) {
+        const int bit = n & 31;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) word[p] |= ((q >> p) & 1u) << bit;
+        if (bit == 31 || n == n1 - 1) {  // uniform: this row's word is complete (or the row ends)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if (p < o.qbits && row_ok) o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)] = word[p];
+                word[p] = 0u;
+            }
+        }
+    };
+    // bias may be absent: read a valid address anyway and select, so that the column loop has no branch
+    const float *const bias_or_scale = bias ? bias : scale;
+    auto bias_of = [&](int n) {
+        const float b = bias_or_scale[n];
+        return bias ? b : 0.0f;
+    };
+    if (packed_only) {
+        // Columns in groups of CB with no branch inside a group: the scalar loads of a whole group (weights,
+        // scale, bias) are issued together and waited for once, instead of one round trip to the scalar
+        // cache per column.  Groups never straddle an output word (n0 and 32 are multiples of CB).
+        constexpr int CB = WB * KW <= 8 ? 4 : WB * KW <= 16 ? 2 : 1;
+        int n = n0;
+        for (; n + CB <= n1; n += CB) {
+            uint32_t q[CB];
+#pragma unroll
+            for (int c = 0; c < CB; ++c) {
+                const float y = __fmaf_rn((float)output(n + c), scale[n + c], bias_of(n + c));
+                q[c] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
+            }
+#pragma unroll
+            for (int c = 0; c < CB; ++c)
+#pragma unroll
+                for (int p = 0; p < 4; ++p) word[p] |= ((q[c] >> p) & 1u) << ((n + c) & 31);
+            if (((n + CB) & 31) == 0 || n + CB == n1) {
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    if (p < o.qbits && row_ok) o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)] = word[p];
+                    word[p] = 0u;
+                }
+            }
+        }
+        for (; n < n1; ++n) {  // the last columns of a ragged N
+            const float y = __fmaf_rn((float)output(n), scale[n], bias_of(n));
+            add_bits(n, (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax));
+        }
+    } else {
+        for (int n = n0; n < n1; ++n) {
+            const int total = output(n);
+            const size_t idx = (size_t)m * g.N + n;
+            uint32_t q = 0;
+            if (o.acc && row_ok) o.acc[idx] = total;
+            if (scale) {
+                const float y = __fmaf_rn((float)total, scale[n], bias_of(n));
+                q = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
+                if (o.y && row_ok) o.y[idx] = y;
+                if (o.q && row_ok) o.q[idx] = (uint8_t)q;
+            }
+            if (o.packed) add_bits(n, q);
+        }
+    }
+}
+
+template <int AB, int WB, int KW, bool BIPOLAR>
+dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
+{
+    const int64_t bx = ((int64_t)g.M + kRowsPerBlock - 1) / kRowsPerBlock, by = (g.N + ncols - 1) / ncols;
+    if (bx > 0x7fffffffLL || by > 65535) return DLRT_ERR_SHAPE;
+    const dim3 grid((unsigned)bx, (unsigned)by), block(kRowsPerBlock);
+    if (conv) hipLaunchKernelGGL((contract_rows_kernel<AB, WB, KW, BIPOLAR, true>), grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
+    else hipLaunchKernelGGL((contract_rows_kernel<AB, WB, KW, BIPOLAR, false>), grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
+    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+}
+
+template <int AB, int WB, bool BIPOLAR>
+dlrt_status pick_kw(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
+{
+    if (g.Kw <= 1) return launch_conv_or_gemm<AB, WB, 1, BIPOLAR>(g, o, conv, ncols, stream);
+    if (g.Kw <= 2) return launch_conv_or_gemm<AB, WB, 2, BIPOLAR>(g, o, conv, ncols, stream);
+    if (g.Kw <= 4) return launch_conv_or_gemm<AB, WB, 4, BIPOLAR>(g, o, conv, ncols, stream);
+    if (g.Kw <= 8) return launch_conv_or_gemm<AB, WB, 8, BIPOLAR>(g, o, conv, ncols, stream);
+    return DLRT_ERR_SHAPE;  // never planned: the reduction is too long for a lane's registers
+}
+
+template <int AB>
+dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols,
+                       hipStream_t stream)
+{
+    switch (wbits) {
+    case 1:
+        return bipolar ? pick_kw<AB, 1, true>(g, o, conv, ncols, stream) : pick_kw<AB, 1, false>(g, o, conv, ncols, stream);
+    case 2: return pick_kw<AB, 2, false>(g, o, conv, ncols, stream);
+    case 3: return pick_kw<AB, 3, false>(g, o, conv, ncols, stream);
+    case 4: return pick_kw<AB, 4, false>(g, o, conv, ncols, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
+}  // namespace
+
+namespace dlrt {
+
+dlrt_status launch_rows(const ContractArgs &g, const FusedOut &o, int abits, int wbits, bool bipolar, bool conv,
+                        int ncols, hipStream_t stream)
+{
+    switch (abits) {
+    case 1: return pick_wbits<1>(g, o, wbits, bipolar, conv, ncols, stream);
+    case 2: return pick_wbits<2>(g, o, wbits, bipolar, conv, ncols, stream);
+    case 3: return pick_wbits<3>(g, o, wbits, bipolar, conv, ncols, stream);
+    case 4: return pick_wbits<4>(g, o, wbits, bipolar, conv, ncols, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
+}  // namespace dlrt

@@ -157,6 +157,12 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     blk, rows, cols, ks = query(lib, 49, 512, 4608, 2, 2)
     assert (blk, rows, cols) == (0, 8, 32) and ks >= 4
     assert query(lib, 784, 128, 64, 2, 2) == (0, 8, 32, 1)  # two steps of reduction: nothing to split
+    # many rows, few columns, a reduction of a word or two: one output row per lane
+    assert query(lib, 409600, 32, 32, 2, 1) == (2, 64, 32, 1)
+    assert query(lib, 50176, 128, 64, 2, 2) == (2, 64, 32, 1)    # 784 row blocks: the columns are split to get more waves
+    assert query(lib, 1 << 20, 128, 64, 2, 2) == (2, 64, 128, 1)  # enough row blocks: a wave keeps all columns of its rows
+    assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # too few rows
+    assert query(lib, 409600, 64, 288, 2, 1)[0] == 1              # nine words do not fit a lane's registers
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
 
@@ -170,7 +176,11 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
         K = r.choice([1, 32, 64, 288, 576, 1152, 4608, 40000])
         blk, rows, cols, ks = query(lib, M, N, K, a, w)
         tn = 4 if w <= 2 else 2
-        if blk:
+        if blk == 2:  # the row kernel: the reduction fits a lane's registers, whole output words per wave
+            Kw = -(-K // 32)
+            assert Kw <= 8 and M >= 16384 and N * Kw <= 256
+            assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= -(-N // 32) * 32
+        elif blk:
             assert (rows, cols, ks) == (16 * [8, 4, 2, 2][a - 1], 16 * [8, 4, 2, 2][w - 1], 1)
             assert -(-M // rows) * -(-N // cols) >= 512
         else:

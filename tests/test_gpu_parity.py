@@ -376,7 +376,8 @@ def test_config3_stack_as_hip_graph_every_replay_bit_exact(dlrt, oracle):
 
 
 # ---- fused convolution: conv + scale/bias + requant + bitplanes of the result in one launch -------------
-def fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=0, ksplit=0, seed=0):
+def fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=0, ksplit=0, seed=0,
+               packed_only=False):
     N, H, W_, Ci = x.shape
     Co, KH, KW, _ = w.shape
     ref = oracle.conv2d_i32(x, w, (stride, stride), (pad, pad))
@@ -391,11 +392,19 @@ def fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, til
     y = torch.full(ref.shape, -7.0, dtype=torch.float32, device=DEV)
     q = torch.full(ref.shape, 99, dtype=torch.uint8, device=DEV)
     packed = torch.full((Mo, qbits, (Co + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    tag = (abits, wbits, ea, ew, qbits, tile_rows, ksplit)
+    if packed_only:  # the chained-layer call: nothing but the next layer's packed activations
+        dlrt.dlrt_bitserial_conv2d_fused(X, Wp, dev(scale), dev(bias), N, H, W_, Ci, Co, KH, KW, (stride, stride),
+                                         (pad, pad), abits, wbits, ea, ew, qbits=qbits, out_packed=packed,
+                                         tile_rows=tile_rows, ksplit=ksplit)
+        torch.cuda.synchronize()
+        want = oracle.pack_bitplanes(q_ref.reshape(Mo, Co).astype(np.int8), qbits, UNSIGNED)
+        assert np.array_equal(words(packed), want), tag
+        return
     dlrt.dlrt_bitserial_conv2d_fused(X, Wp, dev(scale), dev(bias), N, H, W_, Ci, Co, KH, KW, (stride, stride),
                                      (pad, pad), abits, wbits, ea, ew, qbits=qbits, out_acc=acc, out_f32=y, out_q=q,
                                      out_packed=packed, tile_rows=tile_rows, ksplit=ksplit)
     torch.cuda.synchronize()
-    tag = (abits, wbits, ea, ew, qbits, tile_rows, ksplit)
     assert np.array_equal(acc.cpu().numpy(), ref), tag
     assert np.array_equal(y.cpu().numpy(), y_ref), tag
     assert np.array_equal(q.cpu().numpy(), q_ref), tag
@@ -411,6 +420,51 @@ def test_conv_fused_edge_shapes_all_encodings(dlrt, oracle, shape):
         x = inputs.uniform_values((N, H, W, Ci), abits, ea, 18000 + idx + H)
         w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 19000 + idx + Ci)
         fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits)
+
+
+ROW_KERNEL_SHAPES = [
+    # N, H, W, Ci, Co, stride: 1x1 convs without padding whose reduction fits a lane's registers (<= 8 words)
+    (1, 9, 7, 32, 32, 1),      # one word, one output word
+    (2, 10, 10, 33, 20, 2),    # ragged channels (2 words, the second nearly empty), stride 2, batch 2
+    (1, 12, 12, 64, 70, 1),    # ragged output columns: three column words, the last partly filled
+    (1, 8, 6, 128, 64, 2),     # four words
+    (1, 6, 6, 96, 33, 1),      # three words in a four-word register row
+    (1, 5, 5, 160, 129, 1),    # five words in an eight-word register row, 129 columns
+    (3, 7, 5, 256, 40, 1),     # eight words, batch 3
+    (1, 20, 20, 8, 3, 1),      # a quarter word of channels, three columns, rows beyond one wave
+]
+
+
+@pytest.mark.parametrize("shape", ROW_KERNEL_SHAPES)
+def test_conv_fused_row_kernel_all_encodings(dlrt, oracle, shape):
+    """tile_rows = 64 selects the kernel with one output row per lane; ksplit then is the number of
+    32-column groups a wave covers (0: planned).  Every output kind, and the packed-only fast path."""
+    N, H, W, Ci, Co, stride = shape
+    cases = [(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2), (1, 1, UNSIGNED, TWOS, 1),
+             (4, 4, UNSIGNED, TWOS, 4), (3, 2, TWOS, UNSIGNED, 3), (2, 4, UNSIGNED, TWOS, 2), (3, 3, TWOS, TWOS, 2)]
+    for idx, (abits, wbits, ea, ew, qbits) in enumerate(cases):
+        x = inputs.uniform_values((N, H, W, Ci), abits, ea, 28000 + idx + H)
+        w = inputs.uniform_values((Co, 1, 1, Ci), wbits, ew, 29000 + idx + Ci)
+        for groups in (0, 1, 3):
+            fused_case(dlrt, oracle, x, w, stride, 0, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups)
+            fused_case(dlrt, oracle, x, w, stride, 0, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
+                       packed_only=True)
+
+
+def test_conv_fused_row_kernel_rejects_what_it_cannot_hold(dlrt):
+    def call(Ci, k, pad):
+        x = torch.zeros((1, 8, 8, Ci), dtype=torch.uint8, device=DEV)
+        w = torch.zeros((16, k, k, Ci), dtype=torch.int8, device=DEV)
+        X, Wp = dlrt.dlrt_pack_bitplanes(x, 2, UNSIGNED), dlrt.dlrt_pack_conv_weights(w, 2, TWOS)
+        s = torch.ones(16, device=DEV)
+        dlrt.dlrt_bitserial_conv2d_fused(X, Wp, s, None, 1, 8, 8, Ci, 16, k, k, (1, 1), (pad, pad), 2, 2, UNSIGNED, TWOS,
+                                         qbits=2, out_q=torch.empty((1, 8 + 2 * pad - k + 1, 8 + 2 * pad - k + 1, 16),
+                                                                    dtype=torch.uint8, device=DEV), tile_rows=64)
+    call(64, 1, 0)  # fits
+    for Ci, k, pad in ((64, 3, 1), (288, 1, 0), (64, 1, 1)):  # a 3x3 conv, nine words of channels, padding
+        with pytest.raises(dlrt.DlrtError):
+            call(Ci, k, pad)
+    torch.cuda.synchronize()
 
 
 def test_conv_fused_every_tile_height_and_reduction_split_gives_the_same_result(dlrt, oracle):
