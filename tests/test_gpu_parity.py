@@ -578,6 +578,41 @@ def test_gemm_fused_small_shape_takes_the_per_wave_kernel(dlrt, oracle):
     assert np.array_equal(words(packed), oracle.pack_bitplanes(q_ref.astype(np.int8), 2, UNSIGNED))
 
 
+@pytest.mark.parametrize("abits,wbits,ea,ew,qbits,M,N,K", [
+    (2, 2, UNSIGNED, TWOS, 2, 20000, 40, 50), (2, 1, UNSIGNED, BIPOLAR, 2, 16400, 33, 200),
+    (4, 4, TWOS, TWOS, 4, 16384, 7, 256), (1, 3, UNSIGNED, UNSIGNED, 1, 70001, 64, 31), (3, 2, TWOS, UNSIGNED, 3, 33000, 128, 64)])
+def test_gemm_tall_skinny_takes_the_row_kernel(dlrt, oracle, abits, wbits, ea, ew, qbits, M, N, K):
+    """Many rows, few columns and a reduction of at most 8 words: the planner picks the kernel with one
+    output row per lane, for the plain GEMM and for every output of the fused one."""
+    assert dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"] == "rows"
+    a = inputs.uniform_values((M, K), abits, ea, 41000 + M % 97)
+    w = inputs.uniform_values((N, K), wbits, ew, 42000 + N)
+    ref = oracle.gemm_i32(a, w)
+    assert np.array_equal(gpu_gemm(dlrt, a, w, abits, wbits, ea, ew), ref)
+    scale, bias = calibrate(ref)
+    scale, bias = (scale * (1 << qbits) / 4).astype(np.float32), (bias * (1 << qbits) / 4).astype(np.float32)
+    y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=qbits)
+    want = oracle.pack_bitplanes(q_ref.astype(np.int8), qbits, UNSIGNED)
+    A = dlrt.dlrt_pack_bitplanes(src_tensor(a, ea), abits, ea)
+    W = dlrt.dlrt_pack_bitplanes(src_tensor(w, ew), wbits, ew)
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=DEV)
+    y = torch.full((M, N), -7.0, dtype=torch.float32, device=DEV)
+    q = torch.full((M, N), 99, dtype=torch.uint8, device=DEV)
+    packed = torch.full((M, qbits, (N + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), dev(bias), M, N, K, abits, wbits, ea, ew, qbits=qbits, out_acc=acc,
+                                   out_f32=y, out_q=q, out_packed=packed)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), ref)
+    assert np.array_equal(y.cpu().numpy(), y_ref)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(words(packed), want)
+    packed.fill_(-1)
+    dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), None, M, N, K, abits, wbits, ea, ew, qbits=qbits, out_packed=packed)
+    torch.cuda.synchronize()
+    _, q_nobias = oracle.epilogue_f32(ref, scale, None, qbits=qbits)
+    assert np.array_equal(words(packed), oracle.pack_bitplanes(q_nobias.astype(np.int8), qbits, UNSIGNED))
+
+
 def test_conv_fused_large_batch_takes_the_block_kernel(dlrt, oracle):
     """Batch 16 of the 56 x 56 x 64 layer: 784 block tiles, so the throughput kernel runs the fused epilogue."""
     x = inputs.uniform_values((16, 56, 56, 64), 2, UNSIGNED, 888)
