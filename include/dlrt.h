@@ -141,7 +141,7 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  * wbits <= 2; 4, 8 or 16 for wbits >= 3) and ksplit (1, 2, 4, 8) the number of waves that split the
  * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
  * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  tile_rows = 64 asks for the row kernel (one output
- * pixel per lane; 1x1 convolutions without padding over at most 256 channels, DLRT_ERR_SHAPE otherwise);
+ * pixel per lane; convolutions with KH*KW*ceil(Ci/32) <= 16, DLRT_ERR_SHAPE otherwise);
  * ksplit then is the number of 32-column groups a wave covers (0: planned).  The result does not depend on
  * the hints.
  */
@@ -188,9 +188,8 @@ dlrt_status dlrt_bitserial_conv2d_fused_pair(const dlrt_conv_problem *first, con
  *   *block_kernel = 1: the throughput kernel (one 256-thread block per tile_rows x tile_cols tile, ksplit 1)
  *   *block_kernel = 0: the latency kernel (one wave per tile_rows x 32 tile, ksplit waves split K)
  *   *block_kernel = 2: the row kernel (one output row per lane: a wave covers 64 rows x tile_cols columns);
- *                      taken by GEMMs and by 1x1 convolutions without padding whose reduction is at most
- *                      256 elements, when there are many rows and few columns.  The answer assumes such a
- *                      problem; other convolutions of the same M, N, K get one of the tiled kernels.
+ *                      taken when the reduction is at most 16 packed words and there are many rows and few
+ *                      columns.
  * Any output pointer may be NULL.
  */
 dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbits, int *block_kernel,

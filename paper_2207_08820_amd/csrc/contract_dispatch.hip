@@ -54,12 +54,14 @@ dlrt_status wave_by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, 
 int block_tile(int bits) { return 16 * (bits == 1 ? 8 : bits == 2 ? 4 : 2); }
 
 // The block kernel needs enough 256-thread blocks to occupy 256 compute units twice over; below
-// that the per-wave kernel spreads the same work over more, smaller waves.
+// that the per-wave kernel spreads the same work over more, smaller waves.  It also needs its tiles
+// filled: with N at most half a tile wide (64 of the 128 columns of a 1-bit-weight tile, say) the
+// per-wave kernel with its 32-column tiles measured 1.5 to 2.5 times faster at any number of rows.
 bool prefer_wave_kernel(int M, int N, int abits, int wbits)
 {
     const int64_t blocks = (int64_t)((M + block_tile(abits) - 1) / block_tile(abits)) *
                            ((N + block_tile(wbits) - 1) / block_tile(wbits));
-    return blocks < 512;
+    return blocks < 512 || 2 * N <= block_tile(wbits);
 }
 
 struct WavePlan {
@@ -104,12 +106,14 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
 
 // The row kernel (one output row per lane, whole reduction in registers) wins where the tiled kernels are
 // mostly padding: a reduction of a few words, few output columns, and enough rows to fill the chip with one
-// lane per row.  Measured on 1x1 conv layers of 32 .. 512 channels at batch 1 .. 64: with N * Kw <= 256 it is
-// 1.3 to 5 times faster than the better of the other two from about 16 K rows on; beyond that product the
-// block kernel catches up.
+// lane per row.  Measured on 1x1 convs of 32 .. 512 channels and 3x3 convs of up to 32 channels at batch
+// 1 .. 64: up to 9 words and N * Kw <= 576 it is 1.2 to 6 times faster than the better of the other two,
+// from 16 K rows on for one or two words and from 64 K rows on for more; with longer reductions or more
+// columns the tiled kernels catch up.
 bool prefer_rows_kernel(int64_t M, int N, int Kw)
 {
-    return Kw <= dlrt::kRowKernelMaxWords && M >= 16384 && (int64_t)N * Kw <= 256;
+    if (Kw > 9 || (int64_t)N * Kw > 576) return false;
+    return M >= (Kw <= 2 ? 16384 : 65536);
 }
 
 // Row kernel: a wave covers 64 rows x ncols columns.  One column group per row block amortises the row's
@@ -219,7 +223,7 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
                         hipStream_t stream)
 {
     const ContractArgs g = conv_args(X, Wp, c, a_msb_neg, w_msb_neg);
-    const bool rows_fit = c.KH == 1 && c.KW == 1 && c.ph == 0 && c.pw == 0 && g.Kw <= kRowKernelMaxWords;
+    const bool rows_fit = g.Kw <= kRowKernelMaxWords;
     if (tile_rows == 64) {  // hint: the row kernel, ksplit groups of 32 columns per wave
         if (!rows_fit || ksplit < 0 || ksplit > 2048) return DLRT_ERR_SHAPE;
         return launch_rows(g, o, abits, wbits, bipolar, true, ksplit > 0 ? 32 * ksplit : plan_rows(g.M, g.N), stream);

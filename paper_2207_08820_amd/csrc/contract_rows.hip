@@ -1,6 +1,7 @@
-// Bit-serial contraction for SHORT reductions (at most 8 packed words, i.e. 256 elements): GEMMs and
-// 1x1 convolutions over few channels, where the tiled kernels are mostly padding (their reduction step
-// is 4 words, their tiles 32 or more columns wide, and their per-tile set-up outweighs the work).
+// Bit-serial contraction for SHORT reductions (at most 16 packed words): GEMMs over up to 512 elements,
+// 1x1 convolutions over few channels, 3x3 convolutions over up to 32 channels (9 words), where the tiled
+// kernels are mostly padding (their reduction step is 4 words, their tiles 32 or more columns wide, and
+// their per-tile set-up outweighs the work).
 //
 // Same arithmetic as contract.hip (Section V of arXiv 2207.08820: popcount(W[i] & A[j]) per plane pair,
 // shifts and signs applied once per output), decomposed the other way round: a LANE owns one output
@@ -16,6 +17,8 @@
 // a row stride between lanes: correct, but only the packed output is a fast path.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "contract_common.h"
 #include "dlrt.h"
@@ -41,26 +44,46 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
     const int mc = min(m, g.M - 1);  // rows beyond the matrix are computed on the last row, never stored
     const int n0 = blockIdx.y * ncols, n1 = min(n0 + ncols, g.N);
 
-    // ---- this lane's activation row: abits planes of Kw words, zero beyond Kw ----
-    const uint32_t *arow;
-    if (CONV) {  // 1x1 convolution without padding: output pixel (oh, ow) reads input pixel (oh*sh, ow*sw)
-        const int hw = g.Ho * g.Wo;
-        const int img = checked_div(mc, hw, g.magicHW), rem = mc - img * hw;
-        const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
-        arow = g.A + ((size_t)(img * g.H + oh * g.sh) * g.Wd + ow * g.sw) * (AB * g.Kw);
-    } else {
-        arow = g.A + (size_t)mc * (AB * g.Kw);
-    }
+    // ---- this lane's activation row: abits planes of Kw words, zero beyond Kw.  For a convolution the
+    // row is the im2col row of the lane's output pixel: word k is channel word c of tap (kh, kw), zero where
+    // the tap lies outside the image (the address is clamped into the image and the word discarded). ----
     uint32_t a[AB][KW];
     int rowpc[AB];
 #pragma unroll
-    for (int j = 0; j < AB; ++j) {
-        rowpc[j] = 0;
+    for (int j = 0; j < AB; ++j) rowpc[j] = 0;
+    if (CONV) {
+        const int hw = g.Ho * g.Wo;
+        const int img = checked_div(mc, hw, g.magicHW), rem = mc - img * hw;
+        const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
+        const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
+        const uint32_t *image = g.A + (size_t)img * g.H * g.Wd * (AB * g.Cw);
 #pragma unroll
         for (int k = 0; k < KW; ++k) {
-            a[j][k] = k < g.Kw ? arow[j * g.Kw + k] : 0u;
-            if (BIPOLAR) rowpc[j] += __popc(a[j][k]);
+            const int kc = k < g.Kw ? k : 0;
+            const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
+            const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
+            const int ih = ih0 + kh, iw = iw0 + kw;
+            const bool ok = k < g.Kw && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
+            const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
+            const uint32_t *pixel = image + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
+#pragma unroll
+            for (int j = 0; j < AB; ++j) {
+                const uint32_t v = pixel[j * g.Cw];
+                a[j][k] = ok ? v : 0u;
+            }
         }
+    } else {
+        const uint32_t *arow = g.A + (size_t)mc * (AB * g.Kw);
+#pragma unroll
+        for (int j = 0; j < AB; ++j)
+#pragma unroll
+            for (int k = 0; k < KW; ++k) a[j][k] = k < g.Kw ? arow[j * g.Kw + k] : 0u;
+    }
+    if (BIPOLAR) {
+#pragma unroll
+        for (int j = 0; j < AB; ++j)
+#pragma unroll
+            for (int k = 0; k < KW; ++k) rowpc[j] += __popc(a[j][k]);
     }
 
     const int wneg = g.w_msb_neg ? -1 : 0, aneg = g.a_msb_neg ? -1 : 0;  // (x ^ mask) - mask negates when mask is -1
@@ -70,9 +93,13 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
     const bool packed_only = !o.acc && !o.y && !o.q;  // the chained-layer case: nothing but the packed words
 
     // One output.  n is uniform over the wave, so the weight words, scale and bias come through
-    // scalar loads and the AND takes them as scalar operands.
-    auto output = [&](int n) {
-        const uint32_t *w = Wp + (size_t)n * (WB * g.Kw);
+    // scalar loads and the AND takes them as scalar operands.  EXACT: the reduction has exactly KW words,
+    // so every weight index is a compile-time offset from n * WB * KW and the loads of neighbouring
+    // columns merge into wide scalar loads.
+    auto output = [&](int n, auto exact_tag) {
+        constexpr bool EXACT = decltype(exact_tag)::value;
+        const int kw = EXACT ? KW : g.Kw;
+        const uint32_t *w = Wp + (size_t)n * (WB * kw);
         int total = 0;
 #pragma unroll
         for (int j = 0; j < AB; ++j) {
@@ -82,7 +109,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
                 int acc = 0;
 #pragma unroll
                 for (int k = 0; k < KW; ++k)  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
-                    acc += __popc(a[j][k] & w[i * g.Kw + (k < g.Kw ? k : g.Kw - 1)]);
+                    acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
                 if (BIPOLAR) part = 2 * acc - rowpc[j];
                 else if (i + 1 < WB) part += acc << i;
                 else part += ((acc << i) ^ wneg) - wneg;
@@ -112,7 +139,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
         const float b = bias_or_scale[n];
         return bias ? b : 0.0f;
     };
-    if (packed_only) {
+    auto packed_columns = [&](auto exact_tag) {
         // Columns in groups of CB with no branch inside a group: the scalar loads of a whole group (weights,
         // scale, bias) are issued together and waited for once, instead of one round trip to the scalar
         // cache per column.  Groups never straddle an output word (n0 and 32 are multiples of CB).
@@ -122,7 +149,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             uint32_t q[CB];
 #pragma unroll
             for (int c = 0; c < CB; ++c) {
-                const float y = __fmaf_rn((float)output(n + c), scale[n + c], bias_of(n + c));
+                const float y = __fmaf_rn((float)output(n + c, exact_tag), scale[n + c], bias_of(n + c));
                 q[c] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
             }
 #pragma unroll
@@ -138,12 +165,16 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             }
         }
         for (; n < n1; ++n) {  // the last columns of a ragged N
-            const float y = __fmaf_rn((float)output(n), scale[n], bias_of(n));
+            const float y = __fmaf_rn((float)output(n, exact_tag), scale[n], bias_of(n));
             add_bits(n, (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax));
         }
+    };
+    if (packed_only) {
+        if (g.Kw == KW) packed_columns(std::true_type{});
+        else packed_columns(std::false_type{});
     } else {
         for (int n = n0; n < n1; ++n) {
-            const int total = output(n);
+            const int total = output(n, std::false_type{});
             const size_t idx = (size_t)m * g.N + n;
             uint32_t q = 0;
             if (o.acc && row_ok) o.acc[idx] = total;
@@ -176,6 +207,8 @@ dlrt_status pick_kw(const ContractArgs &g, const FusedOut &o, bool conv, int nco
     if (g.Kw <= 2) return launch_conv_or_gemm<AB, WB, 2, BIPOLAR>(g, o, conv, ncols, stream);
     if (g.Kw <= 4) return launch_conv_or_gemm<AB, WB, 4, BIPOLAR>(g, o, conv, ncols, stream);
     if (g.Kw <= 8) return launch_conv_or_gemm<AB, WB, 8, BIPOLAR>(g, o, conv, ncols, stream);
+    if (g.Kw == 9) return launch_conv_or_gemm<AB, WB, 9, BIPOLAR>(g, o, conv, ncols, stream);  // 3x3 taps of one word
+    if (g.Kw <= 16) return launch_conv_or_gemm<AB, WB, 16, BIPOLAR>(g, o, conv, ncols, stream);
     return DLRT_ERR_SHAPE;  // never planned: the reduction is too long for a lane's registers
 }
 

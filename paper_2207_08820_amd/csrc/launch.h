@@ -56,9 +56,9 @@ dlrt_status launch_wave_a2(const ContractArgs *g, const FusedOut *o, int count, 
 dlrt_status launch_wave_a3(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 dlrt_status launch_wave_a4(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 
-// Row kernel (contract_rows.hip): one output row per lane, for reductions of at most 8 words; GEMM, or a
-// 1x1 convolution without padding.  ncols: output columns per wave, a multiple of 32.
-constexpr int kRowKernelMaxWords = 8;
+// Row kernel (contract_rows.hip): one output row per lane, for reductions of at most 16 words; GEMM or any
+// convolution (a conv's words are those of its im2col row).  ncols: output columns per wave, a multiple of 32.
+constexpr int kRowKernelMaxWords = 16;
 dlrt_status launch_rows(const ContractArgs &g, const FusedOut &o, int abits, int wbits, bool bipolar, bool conv,
                         int ncols, hipStream_t stream);
 

@@ -162,7 +162,9 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     assert query(lib, 50176, 128, 64, 2, 2) == (2, 64, 32, 1)    # 784 row blocks: the columns are split to get more waves
     assert query(lib, 1 << 20, 128, 64, 2, 2) == (2, 64, 128, 1)  # enough row blocks: a wave keeps all columns of its rows
     assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # too few rows
-    assert query(lib, 409600, 64, 288, 2, 1)[0] == 1              # nine words do not fit a lane's registers
+    assert query(lib, 409600, 64, 288, 2, 1)[0] == 2              # a 3x3 conv over 32 channels: nine words
+    assert query(lib, 409600, 64, 576, 2, 1)[0] == 0              # eighteen words; 64 columns are half a 128-column block tile
+    assert query(lib, 409600, 128, 576, 2, 1)[0] == 1
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
 
@@ -178,11 +180,11 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
         tn = 4 if w <= 2 else 2
         if blk == 2:  # the row kernel: the reduction fits a lane's registers, whole output words per wave
             Kw = -(-K // 32)
-            assert Kw <= 8 and M >= 16384 and N * Kw <= 256
+            assert Kw <= 9 and N * Kw <= 576 and M >= (16384 if Kw <= 2 else 65536)
             assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= -(-N // 32) * 32
         elif blk:
             assert (rows, cols, ks) == (16 * [8, 4, 2, 2][a - 1], 16 * [8, 4, 2, 2][w - 1], 1)
-            assert -(-M // rows) * -(-N // cols) >= 512
+            assert -(-M // rows) * -(-N // cols) >= 512 and 2 * N > cols
         else:
             tm = rows // (2 * tn)
             assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)

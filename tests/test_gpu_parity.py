@@ -423,15 +423,21 @@ def test_conv_fused_edge_shapes_all_encodings(dlrt, oracle, shape):
 
 
 ROW_KERNEL_SHAPES = [
-    # N, H, W, Ci, Co, stride: 1x1 convs without padding whose reduction fits a lane's registers (<= 8 words)
-    (1, 9, 7, 32, 32, 1),      # one word, one output word
-    (2, 10, 10, 33, 20, 2),    # ragged channels (2 words, the second nearly empty), stride 2, batch 2
-    (1, 12, 12, 64, 70, 1),    # ragged output columns: three column words, the last partly filled
-    (1, 8, 6, 128, 64, 2),     # four words
-    (1, 6, 6, 96, 33, 1),      # three words in a four-word register row
-    (1, 5, 5, 160, 129, 1),    # five words in an eight-word register row, 129 columns
-    (3, 7, 5, 256, 40, 1),     # eight words, batch 3
-    (1, 20, 20, 8, 3, 1),      # a quarter word of channels, three columns, rows beyond one wave
+    # N, H, W, Ci, Co, k, stride, pad: convs whose im2col row fits a lane's registers (<= 16 words)
+    (1, 9, 7, 32, 32, 1, 1, 0),      # one word, one output word
+    (2, 10, 10, 33, 20, 1, 2, 0),    # ragged channels (2 words, the second nearly empty), stride 2, batch 2
+    (1, 12, 12, 64, 70, 1, 1, 0),    # ragged output columns: three column words, the last partly filled
+    (1, 8, 6, 128, 64, 1, 2, 0),     # four words
+    (1, 6, 6, 96, 33, 1, 1, 0),      # three words in a four-word register row
+    (1, 5, 5, 160, 129, 1, 1, 0),    # five words in an eight-word register row, 129 columns
+    (3, 7, 5, 256, 40, 1, 1, 0),     # eight words, batch 3
+    (1, 20, 20, 8, 3, 1, 1, 0),      # a quarter word of channels, three columns, rows beyond one wave
+    (1, 11, 9, 32, 40, 3, 1, 1),     # 3x3 over one word of channels: nine words, zero padding at the border
+    (2, 10, 10, 20, 33, 3, 2, 1),    # 3x3 stride 2, ragged channels, batch 2
+    (1, 9, 9, 3, 16, 3, 1, 0),       # three channels (a stem-like conv), no padding
+    (1, 8, 8, 40, 24, 2, 2, 0),      # 2x2 taps of two words: eight words
+    (1, 7, 6, 8, 10, 4, 1, 2),       # 4x4 taps: sixteen words, padding wider than one pixel
+    (1, 6, 6, 500, 12, 1, 1, 1),     # sixteen words of channels, 1x1 with padding (border outputs are the bias)
 ]
 
 
@@ -439,15 +445,15 @@ ROW_KERNEL_SHAPES = [
 def test_conv_fused_row_kernel_all_encodings(dlrt, oracle, shape):
     """tile_rows = 64 selects the kernel with one output row per lane; ksplit then is the number of
     32-column groups a wave covers (0: planned).  Every output kind, and the packed-only fast path."""
-    N, H, W, Ci, Co, stride = shape
+    N, H, W, Ci, Co, k, stride, pad = shape
     cases = [(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2), (1, 1, UNSIGNED, TWOS, 1),
              (4, 4, UNSIGNED, TWOS, 4), (3, 2, TWOS, UNSIGNED, 3), (2, 4, UNSIGNED, TWOS, 2), (3, 3, TWOS, TWOS, 2)]
     for idx, (abits, wbits, ea, ew, qbits) in enumerate(cases):
         x = inputs.uniform_values((N, H, W, Ci), abits, ea, 28000 + idx + H)
-        w = inputs.uniform_values((Co, 1, 1, Ci), wbits, ew, 29000 + idx + Ci)
+        w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 29000 + idx + Ci)
         for groups in (0, 1, 3):
-            fused_case(dlrt, oracle, x, w, stride, 0, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups)
-            fused_case(dlrt, oracle, x, w, stride, 0, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups)
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
                        packed_only=True)
 
 
@@ -460,8 +466,9 @@ def test_conv_fused_row_kernel_rejects_what_it_cannot_hold(dlrt):
         dlrt.dlrt_bitserial_conv2d_fused(X, Wp, s, None, 1, 8, 8, Ci, 16, k, k, (1, 1), (pad, pad), 2, 2, UNSIGNED, TWOS,
                                          qbits=2, out_q=torch.empty((1, 8 + 2 * pad - k + 1, 8 + 2 * pad - k + 1, 16),
                                                                     dtype=torch.uint8, device=DEV), tile_rows=64)
-    call(64, 1, 0)  # fits
-    for Ci, k, pad in ((64, 3, 1), (288, 1, 0), (64, 1, 1)):  # a 3x3 conv, nine words of channels, padding
+    call(64, 1, 0)  # two words: fits
+    call(32, 3, 1)  # nine words: fits
+    for Ci, k, pad in ((64, 3, 1), (544, 1, 0)):  # eighteen and seventeen words
         with pytest.raises(dlrt.DlrtError):
             call(Ci, k, pad)
     torch.cuda.synchronize()
@@ -579,8 +586,8 @@ def test_gemm_fused_small_shape_takes_the_per_wave_kernel(dlrt, oracle):
 
 
 @pytest.mark.parametrize("abits,wbits,ea,ew,qbits,M,N,K", [
-    (2, 2, UNSIGNED, TWOS, 2, 20000, 40, 50), (2, 1, UNSIGNED, BIPOLAR, 2, 16400, 33, 200),
-    (4, 4, TWOS, TWOS, 4, 16384, 7, 256), (1, 3, UNSIGNED, UNSIGNED, 1, 70001, 64, 31), (3, 2, TWOS, UNSIGNED, 3, 33000, 128, 64)])
+    (2, 2, UNSIGNED, TWOS, 2, 20000, 40, 50), (2, 1, UNSIGNED, BIPOLAR, 2, 70000, 33, 200),
+    (4, 4, TWOS, TWOS, 4, 65536, 7, 256), (1, 3, UNSIGNED, UNSIGNED, 1, 70001, 64, 31), (3, 2, TWOS, UNSIGNED, 3, 33000, 128, 64)])
 def test_gemm_tall_skinny_takes_the_row_kernel(dlrt, oracle, abits, wbits, ea, ew, qbits, M, N, K):
     """Many rows, few columns and a reduction of at most 8 words: the planner picks the kernel with one
     output row per lane, for the plain GEMM and for every output of the fused one."""
