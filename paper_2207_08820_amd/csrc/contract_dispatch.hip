@@ -57,11 +57,14 @@ int block_tile(int bits) { return 16 * (bits == 1 ? 8 : bits == 2 ? 4 : 2); }
 // that the per-wave kernel spreads the same work over more, smaller waves.  It also needs its tiles
 // filled: with N at most half a tile wide (64 of the 128 columns of a 1-bit-weight tile, say) the
 // per-wave kernel with its 32-column tiles measured 1.5 to 2.5 times faster at any number of rows.
+int64_t block_tiles(int M, int N, int abits, int wbits)
+{
+    return (int64_t)((M + block_tile(abits) - 1) / block_tile(abits)) * ((N + block_tile(wbits) - 1) / block_tile(wbits));
+}
+
 bool prefer_wave_kernel(int M, int N, int abits, int wbits)
 {
-    const int64_t blocks = (int64_t)((M + block_tile(abits) - 1) / block_tile(abits)) *
-                           ((N + block_tile(wbits) - 1) / block_tile(wbits));
-    return blocks < 512 || 2 * N <= block_tile(wbits);
+    return block_tiles(M, N, abits, wbits) < 512 || 2 * N <= block_tile(wbits);
 }
 
 struct WavePlan {
@@ -199,10 +202,15 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     ContractArgs g[2];
     int ksplit = 1;
     const int rows = wbits <= 2 ? 8 : 4;  // both problems on the smallest wave tile
-    // sharing a launch pays while a problem cannot fill the chip; one that is large enough for the block
-    // kernel (large batch) runs faster there, so such a pair goes out as two ordinary launches
-    if (!prefer_wave_kernel((int64_t)c[0].N * c[0].Ho * c[0].Wo, c[0].Co, abits, wbits) ||
-        !prefer_wave_kernel((int64_t)c[1].N * c[1].Ho * c[1].Wo, c[1].Co, abits, wbits)) {
+    // sharing a launch (on the smallest wave tile) pays while neither problem can fill the chip; larger ones
+    // run faster on a kernel and tile of their own, so such a pair goes out as two ordinary launches
+    bool pairable = true;
+    for (int i = 0; i < 2; ++i) {
+        const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
+        const int Kw = c[i].KH * c[i].KW * c[i].Cw;
+        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < 512 && !prefer_rows_kernel(M, c[i].Co, Kw);
+    }
+    if (!pairable) {
         for (int i = 0; i < 2; ++i) {
             const dlrt_status st = launch_conv(X[i], Wp[i], c[i], abits, wbits, a_msb_neg, w_msb_neg, bipolar, o[i], 0, 0, stream);
             if (st != DLRT_OK) return st;
