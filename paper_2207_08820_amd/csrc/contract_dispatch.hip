@@ -1,5 +1,6 @@
-// Host-side set-up of a contraction launch: operand alignment, convolution geometry, and the
-// choice of the per-bit-width translation unit of contract.hip.
+// Host-side set-up of a contraction launch: operand alignment, convolution geometry, the choice between
+// the three contraction kernels (block kernel contract.hip, per-wave kernel contract_wave.hip, row kernel
+// contract_rows.hip) and of their tiles, and the per-bit-width translation unit.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
