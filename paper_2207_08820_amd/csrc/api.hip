@@ -8,6 +8,11 @@
 
 namespace {
 
+// Rows and columns are 32-bit in the kernels, which also index up to one tile (at most 128 rows or
+// columns) past the end before clamping: leave that much headroom.
+constexpr int64_t kMaxDim = 0x7fffffffLL - 1024;
+
+
 bool bits_ok(int b) { return b >= 1 && b <= 4; }
 bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
@@ -45,7 +50,7 @@ dlrt_status check_conv_problem(const dlrt_conv_problem &p, int abits, dlrt::Conv
     if (p.H + 2 * p.pad_h < p.KH || p.W + 2 * p.pad_w < p.KW) return DLRT_ERR_SHAPE;
     const int Ho = (p.H + 2 * p.pad_h - p.KH) / p.stride_h + 1, Wo = (p.W + 2 * p.pad_w - p.KW) / p.stride_w + 1;
     const int64_t Cw = (p.Ci + 31) / 32;
-    if ((int64_t)p.N * Ho * Wo > 0x7fffffff || (int64_t)p.KH * p.KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if ((int64_t)p.N * Ho * Wo > kMaxDim || (int64_t)p.KH * p.KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
     if ((int64_t)p.H * p.W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
     // the kernels divide reduction-word indices by Cw and KW with a 32-bit multiply-high
     if ((int64_t)p.KH * p.KW * Cw * (Cw > p.KW ? Cw : p.KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
@@ -117,7 +122,7 @@ dlrt_status dlrt_bitserial_gemm(const uint32_t *A, const uint32_t *W, int32_t *C
     if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
     if (M <= 0 || N <= 0 || K <= 0) return DLRT_ERR_SHAPE;
     const int64_t Kw = (K + 31) / 32;
-    if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if (M > kMaxDim || N > kMaxDim || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
     if (!aligned16(A) || !aligned16(W)) return DLRT_ERR_ALIGN;
     dlrt::FusedOut o{};
     o.acc = C;
@@ -138,7 +143,7 @@ dlrt_status dlrt_bitserial_gemm_fused(const uint32_t *A, const uint32_t *W, cons
     if ((out_q || out_packed) && !bits_ok(qbits)) return DLRT_ERR_BITS;
     if (M <= 0 || N <= 0 || K <= 0) return DLRT_ERR_SHAPE;
     const int64_t Kw = (K + 31) / 32;
-    if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if (M > kMaxDim || N > kMaxDim || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
     if (!aligned16(A) || !aligned16(W) || (out_packed && !aligned16(out_packed))) return DLRT_ERR_ALIGN;
     dlrt::FusedOut o{};
     o.acc = out_acc; o.y = out_f32; o.q = out_q; o.packed = out_packed;
@@ -159,7 +164,7 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
     if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return DLRT_ERR_SHAPE;
     const int Ho = (H + 2 * pad_h - KH) / stride_h + 1, Wo = (W + 2 * pad_w - KW) / stride_w + 1;
     const int64_t Cw = (Ci + 31) / 32;
-    if ((int64_t)N * Ho * Wo > 0x7fffffff || (int64_t)KH * KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if ((int64_t)N * Ho * Wo > kMaxDim || (int64_t)KH * KW * Cw > 0x7ffffff) return DLRT_ERR_SHAPE;
     if ((int64_t)H * W * abits * Cw > 0x7fffffff) return DLRT_ERR_SHAPE;
     // the kernels divide reduction-word indices by Cw and KW with a 32-bit multiply-high
     if ((int64_t)KH * KW * Cw * (Cw > KW ? Cw : KW) > 0x7fffffff) return DLRT_ERR_SHAPE;
@@ -209,7 +214,7 @@ dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbit
     if (!bits_ok(abits) || !bits_ok(wbits)) return DLRT_ERR_BITS;
     if (M <= 0 || N <= 0 || K <= 0) return DLRT_ERR_SHAPE;
     const int64_t Kw = (K + 31) / 32;
-    if (M > 0x7fffffff || N > 0x7fffffff || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
+    if (M > kMaxDim || N > kMaxDim || Kw > 0x7ffffff) return DLRT_ERR_SHAPE;
     dlrt::query_plan((int)M, (int)N, (int)Kw, abits, wbits, block_kernel, tile_rows, tile_cols, ksplit);
     return DLRT_OK;
 }
@@ -219,7 +224,7 @@ dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, 
 {
     if (!A || !W || !C) return DLRT_ERR_NULL;
     if (M <= 0 || N <= 0 || K <= 0 || K % 16 != 0) return DLRT_ERR_SHAPE;
-    if (M > 0x7fffffff || N > 0x7fffffff || K > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (M > kMaxDim || N > kMaxDim || K > 0x7fffffff) return DLRT_ERR_SHAPE;
     if (!aligned16(A) || !aligned16(W)) return DLRT_ERR_ALIGN;
     return dlrt::launch_unpacked_gemm_i8(A, W, C, (int)M, (int)N, (int)K, as_stream(stream));
 }
