@@ -129,7 +129,7 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1):
     does not depend on the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
     conv launch per layer), the same chain enqueued eagerly from Python, and the unfused chain
     (pack + conv + epilogue per layer); per-layer times are of the fused kernel alone, launched back to
-    back from a HIP graph at batch 1 (so they include the gap between dependent launches, about 2.5 us)."""
+    back from a HIP graph (so they include the gap between dependent launches)."""
     import torch
 
     from paper_2207_08820_amd import inputs
@@ -158,8 +158,7 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1):
     per_layer = []
     for i, pl in enumerate(stack.layers):
         xin = stack.layer_input(i)
-        ms = time_graph(lambda: stack.run_layer_fused(i, xin)) if batch == 1 else \
-            time_events(lambda: stack.run_layer_fused(i, xin), iters)
+        ms = time_graph(lambda: stack.run_layer_fused(i, xin), reps=20 if batch == 1 else 5)
         valu_us, hbm_us = layer_floors(pl.spec, 2, wbits, stack.qbits[i], batch)
         plan = dlrt.dlrt_query_plan(batch * pl.spec.M, pl.spec.Co, pl.spec.k * pl.spec.k * (((pl.spec.Ci + 31) // 32) * 32),
                                     2, wbits)

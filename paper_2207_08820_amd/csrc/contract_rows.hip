@@ -31,6 +31,26 @@ using dlrt::FusedOut;
 
 constexpr int kRowsPerBlock = 64;
 
+__device__ __forceinline__ uint32_t dot4(uint32_t a, uint32_t b, uint32_t c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_udot4(a, b, c, false);
+#else
+    (void)a; (void)b;
+    return c;  // host pass of the single-source compile: never executed
+#endif
+}
+
+// clamp(x, 0, hi) in one instruction (x is finite here)
+__device__ __forceinline__ float clamp0(float x, float hi)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_fmed3f(x, 0.0f, hi);
+#else
+    return fminf(fmaxf(x, 0.0f), hi);
+#endif
+}
+
 template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
 __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
                                                                        const int ncols,
@@ -86,7 +106,14 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             for (int k = 0; k < KW; ++k) rowpc[j] += __popc(a[j][k]);
     }
 
-    const int wneg = g.w_msb_neg ? -1 : 0, aneg = g.a_msb_neg ? -1 : 0;  // (x ^ mask) - mask negates when mask is -1
+    // Plane weights with their signs (Section V's double sum): +-2^i, +-2^j, negative for the MSB plane of a
+    // two's-complement operand.  Popcount sums stay below 2^10 and partial sums below 2^14 here, so the
+    // combine is a chain of 24-bit multiply-adds (one full-rate instruction per plane pair).
+    int wcoef[WB], acoef[AB];
+#pragma unroll
+    for (int i = 0; i < WB; ++i) wcoef[i] = (g.w_msb_neg && i == WB - 1) ? -(1 << i) : (1 << i);
+#pragma unroll
+    for (int j = 0; j < AB; ++j) acoef[j] = (g.a_msb_neg && j == AB - 1) ? -(1 << j) : (1 << j);
     const float qmax = (float)((1 << o.qbits) - 1);
     const int Cwo = (g.N + 31) / 32;
     const bool row_ok = m < g.M;
@@ -103,19 +130,16 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
         int total = 0;
 #pragma unroll
         for (int j = 0; j < AB; ++j) {
-            int part = 0;
+            int part = BIPOLAR ? -rowpc[j] : 0;
 #pragma unroll
             for (int i = 0; i < WB; ++i) {
                 int acc = 0;
 #pragma unroll
                 for (int k = 0; k < KW; ++k)  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
                     acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
-                if (BIPOLAR) part = 2 * acc - rowpc[j];
-                else if (i + 1 < WB) part += acc << i;
-                else part += ((acc << i) ^ wneg) - wneg;
+                part += __mul24(acc, BIPOLAR ? 2 : wcoef[i]);
             }
-            part <<= j;
-            total += j + 1 < AB ? part : (part ^ aneg) - aneg;
+            total += __mul24(part, acoef[j]);
         }
         return total;
     };
@@ -139,24 +163,34 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
         const float b = bias_or_scale[n];
         return bias ? b : 0.0f;
     };
+    auto quantized = [&](int total, int n) {
+        const float y = __fmaf_rn((float)total, scale[n], bias_of(n));
+        return (uint32_t)clamp0(rintf(y), qmax);
+    };
     auto packed_columns = [&](auto exact_tag) {
-        // Columns in groups of CB with no branch inside a group: the scalar loads of a whole group (weights,
-        // scale, bias) are issued together and waited for once, instead of one round trip to the scalar
-        // cache per column.  Groups never straddle an output word (n0 and 32 are multiples of CB).
+        // Eight columns at a time, in groups of CB with no branch inside a group: the scalar loads of a
+        // group (weights, scale, bias) are issued together and waited for once, instead of one round trip
+        // to the scalar cache per column.  The eight results are kept as bytes; one byte of each plane word
+        // is then gathered with two dot products per plane, as the packing kernel does.
         constexpr int CB = WB * KW <= 8 ? 4 : WB * KW <= 16 ? 2 : 1;
         int n = n0;
-        for (; n + CB <= n1; n += CB) {
-            uint32_t q[CB];
+        for (; n + 8 <= n1; n += 8) {
+            uint32_t x[2] = {0u, 0u};
 #pragma unroll
-            for (int c = 0; c < CB; ++c) {
-                const float y = __fmaf_rn((float)output(n + c, exact_tag), scale[n + c], bias_of(n + c));
-                q[c] = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
+            for (int c0 = 0; c0 < 8; c0 += CB) {
+#pragma unroll
+                for (int c = c0; c < c0 + CB; ++c) x[c >> 2] |= quantized(output(n + c, exact_tag), n + c) << (8 * (c & 3));
+                __builtin_amdgcn_sched_barrier(0);  // keep the next group's scalar loads out of this group
             }
+            const int shift = n & 24;  // which byte of the 32-column word these eight columns are
 #pragma unroll
-            for (int c = 0; c < CB; ++c)
-#pragma unroll
-                for (int p = 0; p < 4; ++p) word[p] |= ((q[c] >> p) & 1u) << ((n + c) & 31);
-            if (((n + CB) & 31) == 0 || n + CB == n1) {
+            for (int p = 0; p < 4; ++p) {
+                if (p < o.qbits) {
+                    const uint32_t even = (x[0] >> p) & 0x01010101u, odd = (x[1] >> p) & 0x01010101u;
+                    word[p] |= dot4(odd, 0x80402010u, dot4(even, 0x08040201u, 0u)) << shift;
+                }
+            }
+            if (shift == 24 || n + 8 == n1) {
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     if (p < o.qbits && row_ok) o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)] = word[p];
@@ -164,10 +198,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
                 }
             }
         }
-        for (; n < n1; ++n) {  // the last columns of a ragged N
-            const float y = __fmaf_rn((float)output(n, exact_tag), scale[n], bias_of(n));
-            add_bits(n, (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax));
-        }
+        for (; n < n1; ++n) add_bits(n, quantized(output(n, exact_tag), n));  // the last columns of a ragged N
     };
     if (packed_only) {
         if (g.Kw == KW) packed_columns(std::true_type{});
@@ -180,7 +211,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             if (o.acc && row_ok) o.acc[idx] = total;
             if (scale) {
                 const float y = __fmaf_rn((float)total, scale[n], bias_of(n));
-                q = (uint32_t)fminf(fmaxf(rintf(y), 0.0f), qmax);
+                q = (uint32_t)clamp0(rintf(y), qmax);
                 if (o.y && row_ok) o.y[idx] = y;
                 if (o.q && row_ok) o.q[idx] = (uint8_t)q;
             }
