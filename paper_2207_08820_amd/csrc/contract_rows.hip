@@ -10,7 +10,8 @@
 // they are fetched with uniform (scalar) loads and feed the VALU as scalar operands: no LDS, no barrier,
 // no lane-to-lane traffic.  The fused epilogue (Section IV: y = acc * scale + bias, requantization)
 // runs per output, and the lane assembles the bitplane words of ITS row of the next layer's packed
-// activations bit by bit, so the packed output needs no ballot or shuffle either.
+// activations itself (eight results at a time, gathered with dot products as the packing kernel does), so
+// the packed output needs no ballot or shuffle either.
 //
 // A wave covers 64 rows x `ncols` columns (a multiple of 32, so that waves own whole output words);
 // the grid is rows/64 x N/ncols.  int32 / float / uint8 outputs are written one element per lane with
