@@ -620,6 +620,74 @@ def test_gemm_tall_skinny_takes_the_row_kernel(dlrt, oracle, abits, wbits, ea, e
     assert np.array_equal(words(packed), oracle.pack_bitplanes(q_nobias.astype(np.int8), qbits, UNSIGNED))
 
 
+def test_random_gemms_across_the_kernel_choice_boundaries(dlrt, oracle):
+    """Seeded random shapes, bit widths and encodings, drawn around the sizes where the planner switches
+    between the row, per-wave and block kernels; every output of the fused GEMM against the oracle."""
+    r = np.random.default_rng(20220708)
+    kinds = set()
+    for case in range(48):
+        abits, wbits = int(r.integers(1, 5)), int(r.integers(1, 5))
+        ea = int(r.choice([UNSIGNED, TWOS]))
+        ew = BIPOLAR if wbits == 1 and r.random() < 0.5 else int(r.choice([UNSIGNED, TWOS]))
+        M = int(r.choice([1, 63, 64, 65, 1000, 16383, 16384, 16385, 40000, 65535, 65536, 70000]))
+        N = int(r.choice([1, 31, 32, 33, 64, 65, 96, 128, 200, 288]))
+        K = int(r.choice([1, 31, 32, 33, 64, 65, 128, 256, 257, 288, 289, 512, 513, 600]))
+        if M * N * K > 3e9:   # keep the oracle's share of the test short
+            M = 16385
+        qbits = int(r.integers(1, 5))
+        kinds.add(dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"])
+        a = inputs.uniform_values((M, K), abits, ea, 51000 + case)
+        w = inputs.uniform_values((N, K), wbits, ew, 52000 + case)
+        ref = oracle.gemm_i32(a, w)
+        scale, bias = calibrate(ref)
+        scale, bias = (scale * (1 << qbits) / 4).astype(np.float32), (bias * (1 << qbits) / 4).astype(np.float32)
+        y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=qbits)
+        A = dlrt.dlrt_pack_bitplanes(src_tensor(a, ea), abits, ea)
+        W = dlrt.dlrt_pack_bitplanes(src_tensor(w, ew), wbits, ew)
+        acc = torch.full((M, N), -7, dtype=torch.int32, device=DEV)
+        y = torch.full((M, N), -7.0, dtype=torch.float32, device=DEV)
+        packed = torch.full((M, qbits, (N + 31) // 32), -1, dtype=torch.int32, device=DEV)
+        dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), dev(bias), M, N, K, abits, wbits, ea, ew, qbits=qbits,
+                                       out_acc=acc, out_f32=y)
+        dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), dev(bias), M, N, K, abits, wbits, ea, ew, qbits=qbits,
+                                       out_packed=packed)
+        torch.cuda.synchronize()
+        tag = (case, M, N, K, abits, wbits, ea, ew, qbits)
+        assert np.array_equal(acc.cpu().numpy(), ref), tag
+        assert np.array_equal(y.cpu().numpy(), y_ref), tag
+        assert np.array_equal(words(packed), oracle.pack_bitplanes(q_ref.astype(np.int8), qbits, UNSIGNED)), tag
+    assert kinds == {"rows", "wave", "block"}
+
+
+def test_random_convs_across_the_kernel_choice_boundaries(dlrt, oracle):
+    """The same for convolutions: kernel size, stride, padding, batch and channel counts drawn so that all
+    three kernels and ragged words / tiles occur; all four outputs, then the packed-only call."""
+    r = np.random.default_rng(8820)
+    kinds = set()
+    for case in range(40):
+        abits, wbits = int(r.integers(1, 5)), int(r.integers(1, 5))
+        ea = int(r.choice([UNSIGNED, TWOS]))
+        ew = BIPOLAR if wbits == 1 and r.random() < 0.5 else int(r.choice([UNSIGNED, TWOS]))
+        k = int(r.choice([1, 1, 2, 3, 3, 5]))
+        stride, pad = int(r.choice([1, 1, 2])), int(r.choice([0, 1, k // 2]))
+        Ci = int(r.choice([3, 16, 32, 33, 64, 100, 256]))
+        Co = int(r.choice([1, 8, 32, 40, 64, 130]))
+        H, W_ = int(r.choice([5, 40, 130, 130])), int(r.choice([7, 128, 128]))
+        N = int(r.choice([1, 5, 5]))
+        Ho, Wo = (H + 2 * pad - k) // stride + 1, (W_ + 2 * pad - k) // stride + 1
+        if Ho <= 0 or Wo <= 0:
+            continue
+        if N * Ho * Wo * Co * k * k * Ci > 2.5e9:
+            N, Ci = 1, min(Ci, 33)
+        qbits = int(r.integers(1, 5))
+        kinds.add(dlrt.dlrt_query_plan(N * Ho * Wo, Co, k * k * ((Ci + 31) // 32) * 32, abits, wbits)["kernel"])
+        x = inputs.uniform_values((N, H, W_, Ci), abits, ea, 61000 + case)
+        w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 62000 + case)
+        fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits)
+        fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, packed_only=True)
+    assert kinds == {"rows", "wave", "block"}
+
+
 def test_conv_fused_large_batch_takes_the_block_kernel(dlrt, oracle):
     """Batch 16 of the 56 x 56 x 64 layer: 784 block tiles, so the throughput kernel runs the fused epilogue."""
     x = inputs.uniform_values((16, 56, 56, 64), 2, UNSIGNED, 888)
