@@ -9,9 +9,10 @@
 // the reduction.  Bipolar 1-bit weights use 2*popcount(A[j] & W) - popcount(A[j]).
 //
 // Tiling (wave64, 256 threads = 16 x 16 lanes): a lane owns TM x TN outputs, rows ty + 16*r and
-// columns tx + 16*s, so a block owns (16*TM) x (16*TN) outputs.  TM*abits and TN*wbits are kept
-// near 8, which keeps the accumulator count near 64 per lane and the LDS traffic per VALU
-// instruction constant over bit widths.  Packed A / W tiles are staged through LDS in chunks of
+// columns tx + 16*s, so a block owns (16*TM) x (16*TN) outputs.  For 2 to 4 bits TM*abits and TN*wbits
+// are kept near 8, which keeps the accumulator count near 64 per lane and the LDS traffic per VALU
+// instruction constant; 1-bit operands get 4 rows / columns per lane (8 measured 2-9 % slower: 128-wide
+// tiles leave too few blocks and half-empty tiles on narrow problems).  Packed A / W tiles are staged through LDS in chunks of
 // 16 words (512 reduction elements), double buffered, laid out [k4][plane][row] in 16-byte
 // units so that the inner loop reads whole uint4 with compile-time offsets and neighbouring
 // lanes read neighbouring 16-byte units.
@@ -397,7 +398,7 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     else write_tile(std::false_type{});
 }
 
-template <int B> struct LaneTile { static constexpr int value = B == 1 ? 8 : B == 2 ? 4 : 2; };
+template <int B> struct LaneTile { static constexpr int value = B <= 2 ? 4 : 2; };
 
 template <int WB, int VEC, bool BIPOLAR, bool CONV>
 dlrt_status launch(const ContractArgs &g, const FusedOut &o, hipStream_t stream)

@@ -51,8 +51,8 @@ dlrt_status wave_by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, 
 }
 
 // ---- tile planning -----------------------------------------------------------------------------
-// Block kernel (contract.hip): lane tile {8,4,2,2}[bits] on 16 x 16 lanes.
-int block_tile(int bits) { return 16 * (bits == 1 ? 8 : bits == 2 ? 4 : 2); }
+// Block kernel (contract.hip): lane tile {4,4,2,2}[bits] on 16 x 16 lanes.
+int block_tile(int bits) { return 16 * (bits <= 2 ? 4 : 2); }
 
 // The block kernel needs enough 256-thread blocks to occupy 256 compute units twice over; below
 // that the per-wave kernel spreads the same work over more, smaller waves.  It also needs its tiles

@@ -146,9 +146,9 @@ def query(lib, M, N, K, a, w):
 
 
 def test_planner_choices_for_the_benchmark_workloads(lib):
-    # the 4096^3 sweep takes the throughput kernel with tiles of 16 * {8,4,2,2}[bits]
+    # the 4096^3 sweep takes the throughput kernel with tiles of 16 * {4,4,2,2}[bits]
     assert query(lib, 4096, 4096, 4096, 2, 2) == (1, 64, 64, 1)
-    assert query(lib, 4096, 4096, 4096, 1, 1) == (1, 128, 128, 1)
+    assert query(lib, 4096, 4096, 4096, 1, 1) == (1, 64, 64, 1)
     assert query(lib, 4096, 4096, 4096, 2, 4) == (1, 64, 32, 1)
     # batch-1 conv layers take the per-wave kernel; deep reductions are split across waves
     assert query(lib, 64, 64, 576, 2, 2)[0] == 0
@@ -163,8 +163,8 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     assert query(lib, 1 << 20, 128, 64, 2, 2) == (2, 64, 128, 1)  # enough row blocks: a wave keeps all columns of its rows
     assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # too few rows
     assert query(lib, 409600, 64, 288, 2, 1)[0] == 2              # a 3x3 conv over 32 channels: nine words
-    assert query(lib, 409600, 64, 576, 2, 1)[0] == 0              # eighteen words; 64 columns are half a 128-column block tile
-    assert query(lib, 409600, 128, 576, 2, 1)[0] == 1
+    assert query(lib, 409600, 32, 576, 2, 1)[0] == 0              # eighteen words; 32 columns are half a 64-column block tile
+    assert query(lib, 409600, 64, 576, 2, 1)[0] == 1
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
 
@@ -183,7 +183,7 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
             assert Kw <= 9 and N * Kw <= 576 and M >= (16384 if Kw <= 2 else 65536)
             assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= -(-N // 32) * 32
         elif blk:
-            assert (rows, cols, ks) == (16 * [8, 4, 2, 2][a - 1], 16 * [8, 4, 2, 2][w - 1], 1)
+            assert (rows, cols, ks) == (16 * [4, 4, 2, 2][a - 1], 16 * [4, 4, 2, 2][w - 1], 1)
             assert -(-M // rows) * -(-N // cols) >= 512 and 2 * N > cols
         else:
             tm = rows // (2 * tn)
