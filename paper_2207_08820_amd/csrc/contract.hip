@@ -400,16 +400,28 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
 
 template <int B> struct LaneTile { static constexpr int value = B <= 2 ? 4 : 2; };
 
-template <int WB, int VEC, bool BIPOLAR, bool CONV>
-dlrt_status launch(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
+template <int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
+dlrt_status launch_tile(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
 {
     constexpr int AB = DLRT_ABITS;
-    constexpr int TM = LaneTile<AB>::value, TN = LaneTile<WB>::value;
+    constexpr int TN = LaneTile<WB>::value;
     const int64_t tilesM = (g.M + 16 * TM - 1) / (16 * TM), tilesN = (g.N + 16 * TN - 1) / (16 * TN);
     if (tilesM * tilesN > 0x7fffffffLL) return DLRT_ERR_SHAPE;
     hipLaunchKernelGGL((contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>), dim3((unsigned)(tilesM * tilesN)),
                        dim3(kThreads), 0, stream, g, o);
     return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+}
+
+// Activations of 1 or 2 bits have two tile heights: 4 rows per lane (64-row tiles), and 2 rows per lane
+// (32-row tiles, twice as many blocks) for problems with few tiles; the launcher's plan says which.
+template <int WB, int VEC, bool BIPOLAR, bool CONV>
+dlrt_status launch(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
+{
+    constexpr int TM = LaneTile<DLRT_ABITS>::value;
+    if constexpr (TM > 2) {
+        if (g.half_rows) return launch_tile<WB, TM / 2, VEC, BIPOLAR, CONV>(g, o, stream);
+    }
+    return launch_tile<WB, TM, VEC, BIPOLAR, CONV>(g, o, stream);
 }
 
 template <int WB, bool BIPOLAR, bool CONV>

@@ -16,6 +16,8 @@
 // A wave covers 64 rows x `ncols` columns (a multiple of 32, so that waves own whole output words);
 // the grid is rows/64 x N/ncols.  int32 / float / uint8 outputs are written one element per lane with
 // a row stride between lanes: correct, but only the packed output is a fast path.
+//
+// Compiled once per activation bit width (-DDLRT_ABITS=1..4), like contract.hip.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,6 +26,10 @@
 #include "contract_common.h"
 #include "dlrt.h"
 #include "launch.h"
+
+#ifndef DLRT_ABITS
+#error "compile with -DDLRT_ABITS=1..4"
+#endif
 
 namespace {
 
@@ -262,16 +268,13 @@ dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool
 
 namespace dlrt {
 
-dlrt_status launch_rows(const ContractArgs &g, const FusedOut &o, int abits, int wbits, bool bipolar, bool conv,
-                        int ncols, hipStream_t stream)
+#define DLRT_CAT2(a, b) a##b
+#define DLRT_CAT(a, b) DLRT_CAT2(a, b)
+
+dlrt_status DLRT_CAT(launch_rows_a, DLRT_ABITS)(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar,
+                                                 bool conv, int ncols, hipStream_t stream)
 {
-    switch (abits) {
-    case 1: return pick_wbits<1>(g, o, wbits, bipolar, conv, ncols, stream);
-    case 2: return pick_wbits<2>(g, o, wbits, bipolar, conv, ncols, stream);
-    case 3: return pick_wbits<3>(g, o, wbits, bipolar, conv, ncols, stream);
-    case 4: return pick_wbits<4>(g, o, wbits, bipolar, conv, ncols, stream);
-    }
-    return DLRT_ERR_BITS;
+    return pick_wbits<DLRT_ABITS>(g, o, wbits, bipolar, conv, ncols, stream);
 }
 
 }  // namespace dlrt

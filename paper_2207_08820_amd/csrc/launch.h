@@ -25,6 +25,7 @@ struct ContractArgs {
     int M, N, Kw;       // Kw: reduction words per plane (conv: KH*KW*Cw)
     int a_msb_neg, w_msb_neg;
     int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
+    int half_rows;      // block kernel, 1- and 2-bit activations: 32-row tiles instead of 64-row tiles
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
@@ -59,8 +60,10 @@ dlrt_status launch_wave_a4(const ContractArgs *g, const FusedOut *o, int count, 
 // Row kernel (contract_rows.hip): one output row per lane, for reductions of at most 16 words; GEMM or any
 // convolution (a conv's words are those of its im2col row).  ncols: output columns per wave, a multiple of 32.
 constexpr int kRowKernelMaxWords = 16;
-dlrt_status launch_rows(const ContractArgs &g, const FusedOut &o, int abits, int wbits, bool bipolar, bool conv,
-                        int ncols, hipStream_t stream);
+dlrt_status launch_rows_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 
 // Conv geometry handed from the C ABI to the launcher.
 struct ConvShape {

@@ -164,7 +164,8 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # too few rows
     assert query(lib, 409600, 64, 288, 2, 1)[0] == 2              # a 3x3 conv over 32 channels: nine words
     assert query(lib, 409600, 32, 576, 2, 1)[0] == 0              # eighteen words; 32 columns are half a 64-column block tile
-    assert query(lib, 409600, 64, 576, 2, 1)[0] == 1
+    assert query(lib, 409600, 64, 576, 2, 1) == (1, 64, 64, 1)
+    assert query(lib, 50176, 128, 1152, 2, 2) == (1, 32, 64, 1)   # 1568 tiles of 64 rows: the half-height tile
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
 
@@ -183,8 +184,10 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
             assert Kw <= 9 and N * Kw <= 576 and M >= (16384 if Kw <= 2 else 65536)
             assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= -(-N // 32) * 32
         elif blk:
-            assert (rows, cols, ks) == (16 * [4, 4, 2, 2][a - 1], 16 * [4, 4, 2, 2][w - 1], 1)
-            assert -(-M // rows) * -(-N // cols) >= 512 and 2 * N > cols
+            full = 16 * [4, 4, 2, 2][a - 1]   # 1- and 2-bit activations take half-height tiles below 4096 full tiles
+            assert (cols, ks) == (16 * [4, 4, 2, 2][w - 1], 1) and rows in (full, full // 2)
+            tiles = -(-M // full) * -(-N // cols)
+            assert tiles >= 512 and 2 * N > cols and (rows == full // 2) == (a <= 2 and tiles < 4096)
         else:
             tm = rows // (2 * tn)
             assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)
