@@ -66,10 +66,14 @@ dlrt_status wave_by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, 
 // Block kernel (contract.hip): lane tile {4,4,2,2}[bits] on 16 x 16 lanes.
 int block_tile(int bits) { return 16 * (bits <= 2 ? 4 : 2); }
 
-// The block kernel needs enough 256-thread blocks to occupy 256 compute units twice over; below
-// that the per-wave kernel spreads the same work over more, smaller waves.  It also needs its tiles
-// filled: with N at most half a tile wide (64 of the 128 columns of a 1-bit-weight tile, say) the
-// per-wave kernel with its 32-column tiles measured 1.5 to 2.5 times faster at any number of rows.
+// The block kernel needs enough 256-thread blocks to give every compute unit one; below that the per-wave
+// kernel spreads the same work over more, smaller waves.  Measured crossover on conv layers of 1568 .. 12544
+// rows: about 100 tiles of 64 rows (200 blocks of the 32-row tile) for 1- and 2-bit activations; wider
+// activations keep the earlier, untuned limit of 512 of their 32-row tiles.  The block kernel also needs its
+// tiles filled: with N at most half a tile wide the per-wave kernel with its 32-column tiles measured 1.5 to
+// 2.5 times faster at any number of rows.
+int64_t wave_below(int abits) { return abits <= 2 ? 128 : 512; }
+
 int64_t block_tiles(int M, int N, int abits, int wbits)
 {
     return (int64_t)((M + block_tile(abits) - 1) / block_tile(abits)) * ((N + block_tile(wbits) - 1) / block_tile(wbits));
@@ -78,12 +82,12 @@ int64_t block_tiles(int M, int N, int abits, int wbits)
 // Block kernel, 1- and 2-bit activations: below 4096 tiles of 64 rows the 32-row tile is 8 to 14 % faster on
 // every conv-shaped problem measured (twice as many blocks fill the last round of resident blocks better and
 // a tile's fixed cost is hidden behind more neighbours); from 4096 tiles on the 64-row tile is as fast or up to
-// 3 % faster (more reuse of each weight word read from LDS).
+// 3 % faster (more reuse of each weight word read from LDS).  A quarter-height tile measured slower than both.
 bool prefer_half_rows(int M, int N, int abits, int wbits) { return abits <= 2 && block_tiles(M, N, abits, wbits) < 4096; }
 
 bool prefer_wave_kernel(int M, int N, int abits, int wbits)
 {
-    return block_tiles(M, N, abits, wbits) < 512 || 2 * N <= block_tile(wbits);
+    return block_tiles(M, N, abits, wbits) < wave_below(abits) || 2 * N <= block_tile(wbits);
 }
 
 struct WavePlan {
@@ -229,7 +233,7 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     for (int i = 0; i < 2; ++i) {
         const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
         const int Kw = c[i].KH * c[i].KW * c[i].Cw;
-        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < 512 && !prefer_rows_kernel(M, c[i].Co, Kw);
+        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw);
     }
     if (!pairable) {
         for (int i = 0; i < 2; ++i) {

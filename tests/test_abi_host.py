@@ -187,7 +187,7 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
             full = 16 * [4, 4, 2, 2][a - 1]   # 1- and 2-bit activations take half-height tiles below 4096 full tiles
             assert (cols, ks) == (16 * [4, 4, 2, 2][w - 1], 1) and rows in (full, full // 2)
             tiles = -(-M // full) * -(-N // cols)
-            assert tiles >= 512 and 2 * N > cols and (rows == full // 2) == (a <= 2 and tiles < 4096)
+            assert tiles >= (128 if a <= 2 else 512) and 2 * N > cols and (rows == full // 2) == (a <= 2 and tiles < 4096)
         else:
             tm = rows // (2 * tn)
             assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)
