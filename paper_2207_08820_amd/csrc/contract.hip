@@ -415,15 +415,13 @@ dlrt_status launch_tile(const ContractArgs &g, const FusedOut &o, hipStream_t st
     return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
 }
 
-// Activations of 1 or 2 bits have two tile heights: 4 rows per lane (64-row tiles), and 2 rows per lane
-// (32-row tiles, twice as many blocks) for problems with few tiles; the launcher's plan says which.
+// Two tile heights per activation width: TM rows per lane (64-row tiles for 1 and 2 bits, 32-row tiles for 3 and
+// 4), and half of that (twice as many blocks) for problems with few tiles; the launcher's plan says which.
 template <int WB, int VEC, bool BIPOLAR, bool CONV>
 dlrt_status launch(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
 {
     constexpr int TM = LaneTile<DLRT_ABITS>::value;
-    if constexpr (TM > 2) {
-        if (g.half_rows) return launch_tile<WB, TM / 2, VEC, BIPOLAR, CONV>(g, o, stream);
-    }
+    if (g.half_rows) return launch_tile<WB, TM / 2, VEC, BIPOLAR, CONV>(g, o, stream);
     return launch_tile<WB, TM, VEC, BIPOLAR, CONV>(g, o, stream);
 }
 

@@ -79,11 +79,17 @@ int64_t block_tiles(int M, int N, int abits, int wbits)
     return (int64_t)((M + block_tile(abits) - 1) / block_tile(abits)) * ((N + block_tile(wbits) - 1) / block_tile(wbits));
 }
 
-// Block kernel, 1- and 2-bit activations: below 4096 tiles of 64 rows the 32-row tile is 8 to 14 % faster on
-// every conv-shaped problem measured (twice as many blocks fill the last round of resident blocks better and
-// a tile's fixed cost is hidden behind more neighbours); from 4096 tiles on the 64-row tile is as fast or up to
-// 3 % faster (more reuse of each weight word read from LDS).  A quarter-height tile measured slower than both.
-bool prefer_half_rows(int M, int N, int abits, int wbits) { return abits <= 2 && block_tiles(M, N, abits, wbits) < 4096; }
+// Block kernel: every activation width has a full tile (64 rows for 1 and 2 bits, 32 rows for 3 and 4) and one
+// of half that height.  With few tiles the half-height tile is 3 to 14 % faster on every conv-shaped problem
+// measured (twice as many blocks fill the last round of resident blocks better and a tile's fixed cost is
+// hidden behind more neighbours); with many tiles the full tile is as fast or up to 6 % faster (more reuse
+// of each weight word read from LDS).  Measured crossovers, in full tiles: about 4096 for A2W2 and A2W1,
+// between 1568 and 3136 for A3W3, none up to 12544 for A4W4.  A quarter-height tile measured slower than both.
+bool prefer_half_rows(int M, int N, int abits, int wbits)
+{
+    const int64_t limit = abits <= 2 ? 4096 : abits == 3 ? 2048 : 16384;
+    return block_tiles(M, N, abits, wbits) < limit;
+}
 
 bool prefer_wave_kernel(int M, int N, int abits, int wbits)
 {

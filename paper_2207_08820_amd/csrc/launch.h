@@ -25,7 +25,7 @@ struct ContractArgs {
     int M, N, Kw;       // Kw: reduction words per plane (conv: KH*KW*Cw)
     int a_msb_neg, w_msb_neg;
     int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
-    int half_rows;      // block kernel, 1- and 2-bit activations: 32-row tiles instead of 64-row tiles
+    int half_rows;      // block kernel: tiles of half the usual height (32 instead of 64 rows, 16 instead of 32)
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1

@@ -150,6 +150,8 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     assert query(lib, 4096, 4096, 4096, 2, 2) == (1, 64, 64, 1)
     assert query(lib, 4096, 4096, 4096, 1, 1) == (1, 64, 64, 1)
     assert query(lib, 4096, 4096, 4096, 2, 4) == (1, 64, 32, 1)
+    assert query(lib, 4096, 4096, 4096, 3, 3) == (1, 32, 32, 1)
+    assert query(lib, 2048, 2048, 4096, 4, 4) == (1, 16, 32, 1)   # 4096 full tiles of 32 x 32: half-height for 4-bit activations
     # batch-1 conv layers take the per-wave kernel; deep reductions are split across waves
     assert query(lib, 64, 64, 576, 2, 2)[0] == 0
     blk, rows, cols, ks = query(lib, 3136, 64, 576, 2, 2)
@@ -184,10 +186,11 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
             assert Kw <= 9 and N * Kw <= 576 and M >= (16384 if Kw <= 2 else 65536)
             assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= -(-N // 32) * 32
         elif blk:
-            full = 16 * [4, 4, 2, 2][a - 1]   # 1- and 2-bit activations take half-height tiles below 4096 full tiles
+            full = 16 * [4, 4, 2, 2][a - 1]   # problems with few full tiles take the half-height tile
             assert (cols, ks) == (16 * [4, 4, 2, 2][w - 1], 1) and rows in (full, full // 2)
             tiles = -(-M // full) * -(-N // cols)
-            assert tiles >= (128 if a <= 2 else 512) and 2 * N > cols and (rows == full // 2) == (a <= 2 and tiles < 4096)
+            assert tiles >= (128 if a <= 2 else 512) and 2 * N > cols
+            assert (rows == full // 2) == (tiles < [4096, 4096, 2048, 16384][a - 1])
         else:
             tm = rows // (2 * tn)
             assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)
