@@ -50,8 +50,9 @@ struct WavePair {
     uint32_t magicTilesN[2];  // for tile / ceil(N / 32); same convention as ContractArgs::magicHW
 };
 
-// Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n); g / o point at `count` (1 or 2) problems.: tm = rows per lane (1, 2, 4), ksplit = waves
-// per block that split the reduction (1, 2, 4, 8); both as planned by plan_wave().
+// Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n); g / o point at `count` (1 or 2) problems.
+// tm = rows per lane (1, 2, 4), ksplit = waves per block that split the reduction (1, 2, 4, 8); both as
+// planned by plan_wave().
 dlrt_status launch_wave_a1(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 dlrt_status launch_wave_a2(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 dlrt_status launch_wave_a3(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);

@@ -712,7 +712,126 @@ def test_gemm_very_tall_output_indexing_beyond_2_31_bytes(dlrt, oracle):
     rows = np.concatenate([rng(5).choice(M, size=64, replace=False), [0, M - 1, (1 << 23) + 1]])
     assert np.array_equal(C[torch.as_tensor(rows, device=DEV)].cpu().numpy(), oracle.gemm_i32(a[rows], w))
     colsum = C.sum(dim=0, dtype=torch.int64).cpu().numpy()
-    assert np.array_equal(colsum, w.astype(np.int64) @ a.astype(np.int64).sum(axis=0))
+    assert np.array_equal(colsum, w.astype(np.int64) @ a.sum(axis=0, dtype=np.int64))
+
+
+def every_output_agrees(acc, y, q, packed, scale, bias, qbits, chunk=1 << 16):
+    """Whole-tensor consistency of the four fused outputs, evaluated on the GPU with torch in row chunks:
+    y against float64 acc * scale + bias rounded to fp32 (at most 1 ulp off a fused multiply-add), q against
+    clamp(rint(y)), packed against the bits of q.  The absolute values are pinned by the sampled rows."""
+    M, N = acc.shape
+    sc, bs = dev(scale).double(), dev(bias).double()
+    shifts = torch.arange(32, device=DEV, dtype=torch.int64)
+    for r0 in range(0, M, chunk):
+        a, yy, qq = acc[r0:r0 + chunk], y[r0:r0 + chunk], q[r0:r0 + chunk]
+        want = (a.double() * sc + bs).float()
+        ulp = torch.maximum(want.abs(), torch.tensor(1e-30, device=DEV)) * 2.0 ** -23
+        assert bool(((yy - want).abs() <= ulp).all()), r0
+        assert torch.equal(qq, torch.clamp(torch.round(yy), 0, (1 << qbits) - 1).to(torch.uint8)), r0
+        pad = (-N) % 32
+        bits = torch.nn.functional.pad(qq, (0, pad)).to(torch.int64).reshape(qq.shape[0], -1, 32)
+        for p in range(qbits):
+            word = (((bits >> p) & 1) << shifts).sum(dim=2)
+            got = packed[r0:r0 + chunk, p].to(torch.int64) & 0xFFFFFFFF
+            assert torch.equal(got, word), (r0, p)
+
+
+@pytest.mark.parametrize("kernel,M,N,K,abits,wbits,ew", [
+    ("block", 1040013, 2080, 40, 2, 2, TWOS),          # 2.16e9 outputs, ragged in M, N and K
+    ("rows", (1 << 25) + 21, 65, 32, 2, 1, BIPOLAR)])  # 2.18e9 outputs, one word per row
+def test_gemm_more_than_2_31_outputs(dlrt, oracle, kernel, M, N, K, abits, wbits, ew):
+    """Element indices of every output pass 2^31 (an int32 result of 8.7 GB): sampled rows of all four fused
+    outputs against the oracle (first, last, the rows either side of element 2^31, random ones), the
+    column-sum identity over all accumulators, and the other outputs against the accumulators everywhere."""
+    assert M * N > 1 << 31 and dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"] == kernel
+    qbits = 2
+    a = inputs.uniform_values((M, K), abits, UNSIGNED, 54000 + N)
+    w = inputs.uniform_values((N, K), wbits, ew, 54001 + N)
+    edge = (1 << 31) // N
+    rows = np.concatenate([rng(N).choice(M, size=256, replace=False), [0, M - 1, edge - 1, edge, edge + 1]])
+    ref = oracle.gemm_i32(a[rows], w)
+    scale, bias = calibrate(ref)
+    y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=qbits)
+    A = dlrt.dlrt_pack_bitplanes(dev(a.astype(np.uint8)), abits, UNSIGNED)
+    W = dlrt.dlrt_pack_bitplanes(src_tensor(w, ew), wbits, ew)
+    acc = torch.full((M, N), -7, dtype=torch.int32, device=DEV)
+    y = torch.full((M, N), -7.0, dtype=torch.float32, device=DEV)
+    q = torch.full((M, N), 99, dtype=torch.uint8, device=DEV)
+    packed = torch.full((M, qbits, (N + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_gemm_fused(A, W, dev(scale), dev(bias), M, N, K, abits, wbits, UNSIGNED, ew, qbits=qbits,
+                                   out_acc=acc, out_f32=y, out_q=q, out_packed=packed)
+    torch.cuda.synchronize()
+    pick = torch.as_tensor(rows, device=DEV)
+    assert np.array_equal(acc[pick].cpu().numpy(), ref)
+    assert np.array_equal(y[pick].cpu().numpy(), y_ref)
+    assert np.array_equal(q[pick].cpu().numpy(), q_ref)
+    assert np.array_equal(words(packed[pick]), oracle.pack_bitplanes(q_ref.astype(np.int8), qbits, UNSIGNED))
+    colsum = acc.sum(dim=0, dtype=torch.int64).cpu().numpy()
+    assert np.array_equal(colsum, w.astype(np.int64) @ a.sum(axis=0, dtype=np.int64))
+    every_output_agrees(acc, y, q, packed, scale, bias, qbits)
+    # the plain call writes the same accumulators
+    plain = dlrt.dlrt_bitserial_gemm(A, W, M, N, K, abits, wbits, UNSIGNED, ew)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, acc)
+
+
+@pytest.mark.parametrize("kernel,Co,k,hint", [("rows", 32, 3, 0), ("block", 96, 3, 0), ("wave", 24, 1, 8)])
+def test_conv_image_too_large_for_multiply_high_division(dlrt, oracle, kernel, Co, k, hint):
+    """2048 x 2048 output pixels: pixels * width passes 2^32, so output row -> (image, row, column) uses the
+    hardware's division instead of the multiply-high shortcut, in each of the three kernels."""
+    H = W = 2048
+    if not hint:
+        assert dlrt.dlrt_query_plan(H * W, Co, k * k * 32, 2, 2)["kernel"] == kernel
+    x = inputs.uniform_values((1, H, W, 32), 2, UNSIGNED, 55000 + Co)
+    w = inputs.uniform_values((Co, k, k, 32), 2, TWOS, 55001 + Co)
+    ref = oracle.conv2d_i32(x, w, (1, 1), (k // 2, k // 2))
+    X = dlrt.dlrt_pack_bitplanes(src_tensor(x, UNSIGNED), 2, UNSIGNED)
+    Wp = dlrt.dlrt_pack_conv_weights(dev(w), 2, TWOS)
+    acc = torch.full((1, H, W, Co), -7, dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_conv2d_fused(X, Wp, None, None, 1, H, W, 32, Co, k, k, (1, 1), (k // 2, k // 2), 2, 2, UNSIGNED,
+                                     TWOS, out_acc=acc, tile_rows=hint)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), ref)
+
+
+def test_pack_and_epilogue_more_than_2_31_elements(dlrt, oracle):
+    """The two streaming kernels past 2^31 elements.  Pack: 70001 x 32040 uint8 (2.24e9 values, ragged last
+    word, rows of 1002 words), sampled rows against the oracle and every plane's popcount against a count of
+    the values that have the bit.  Epilogue: 1100003 x 2000 accumulators (8.8 GB) drawn on the GPU, sampled
+    rows against the oracle and requantized output against the fp32 output everywhere."""
+    rows, K = 70001, 32040
+    q = inputs.uniform_values((rows, K), 2, UNSIGNED, 56000).astype(np.uint8)
+    packed = dlrt.dlrt_pack_bitplanes(dev(q), 2, UNSIGNED)
+    torch.cuda.synchronize()
+    edge = (1 << 31) // K
+    pick = np.concatenate([rng(56).choice(rows, size=128, replace=False), [0, rows - 1, edge - 1, edge, edge + 1]])
+    assert np.array_equal(words(packed[torch.as_tensor(pick, device=DEV)]), oracle.pack_bitplanes(q[pick].astype(np.int8), 2, UNSIGNED))
+    ones = torch.zeros(2, dtype=torch.int64, device=DEV)
+    table = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=DEV)
+    for r0 in range(0, rows, 4096):  # popcount per plane by bytes through a 256-entry table
+        part = packed[r0:r0 + 4096].contiguous().view(torch.uint8).reshape(-1, 2, 4 * packed.shape[2])
+        ones += table[part.long()].sum(dim=(0, 2))
+    assert ones.tolist() == [int(np.count_nonzero(q & 1)), int(np.count_nonzero(q & 2))]
+    del packed, q
+
+    M, C = 1100003, 2000
+    gen = torch.Generator(device=DEV).manual_seed(56001)
+    acc = torch.randint(-40000, 40000, (M, C), dtype=torch.int32, device=DEV, generator=gen)
+    scale = inputs.uniform_scale(C, 56002, 2e-5, 6e-5)
+    bias = inputs.uniform_scale(C, 56003, 1.0, 2.0)
+    y, qq = dlrt.dlrt_epilogue_f32(acc, dev(scale), dev(bias), qbits=2)
+    torch.cuda.synchronize()
+    edge = (1 << 31) // C
+    pick = torch.as_tensor(np.concatenate([rng(57).choice(M, size=128, replace=False), [0, M - 1, edge - 1, edge, edge + 1]]), device=DEV)
+    y_ref, q_ref = oracle.epilogue_f32(acc[pick].cpu().numpy(), scale, bias, qbits=2)
+    assert np.array_equal(y[pick].cpu().numpy(), y_ref) and np.array_equal(qq[pick].cpu().numpy(), q_ref)
+    assert len(np.unique(q_ref)) == 4
+    sc, bs = dev(scale).double(), dev(bias).double()
+    for r0 in range(0, M, 1 << 16):
+        want = (acc[r0:r0 + (1 << 16)].double() * sc + bs).float()
+        got = y[r0:r0 + (1 << 16)]
+        assert bool(((got - want).abs() <= want.abs() * 2.0 ** -23).all()), r0
+        assert torch.equal(qq[r0:r0 + (1 << 16)], torch.clamp(torch.round(got), 0, 3).to(torch.uint8)), r0
 
 
 def test_gemm_very_long_reduction(dlrt, oracle):
