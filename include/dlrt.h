@@ -141,7 +141,7 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  * wbits <= 2; 4, 8 or 16 for wbits >= 3) and ksplit (1, 2, 4, 8) the number of waves that split the
  * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
  * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  tile_rows = 64 asks for the row kernel (one output
- * pixel per lane; convolutions with KH*KW*ceil(Ci/32) <= 16, DLRT_ERR_SHAPE otherwise);
+ * pixel per lane; convolutions with KH*KW*ceil(Ci/32) <= 16 or = 18, DLRT_ERR_SHAPE otherwise);
  * ksplit then is the number of 32-column groups a wave covers (0: planned).  The result does not depend on
  * the hints.
  */

@@ -136,26 +136,31 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
     return best;
 }
 
-// The row kernel (one output row per lane, whole reduction in registers) wins where the tiled kernels are
-// mostly padding: a reduction of a few words, few output columns, and enough rows to fill the chip with one
-// lane per row.  Measured on 1x1 convs of 32 .. 512 channels and 3x3 convs of up to 32 channels at batch
-// 1 .. 64: up to 9 words and N * Kw <= 576 it is 1.2 to 6 times faster than the better of the other two,
-// from 16 K rows on for one or two words and from 64 K rows on for more; with longer reductions or more
-// columns the tiled kernels catch up.
-bool prefer_rows_kernel(int64_t M, int N, int Kw)
+// The row kernel (one output row per lane, whole reduction in registers, weights through scalar loads) has no
+// per-tile set-up, LDS traffic or barrier, so on short reductions it beats the tiled kernels as soon as
+// there are enough waves of 64 rows x 32 columns to fill the chip; how many depends on how well the
+// reduction fits the tiled kernels' 4- and 16-word steps.  Measured on convolutions of 3136 .. 200704 output
+// pixels x 32 .. 512 channels at A1W1, A2W1, A2W2, A3W2 and A4W4: from the wave counts below on it is as fast
+// or (mostly) 1.1 to 4 times faster than the better of the other two, below them slower.  An 18-word
+// reduction (3x3 taps over 64 channels) needs 18 x wbits scalar registers of weights per column, which only
+// pays for 1- and 2-bit weights (A4W4 measured half the block kernel's speed).
+int64_t row_kernel_waves(int64_t M, int N) { return ((M + 63) / 64) * ((N + 31) / 32); }
+
+bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits)
 {
-    if (Kw > 9 || (int64_t)N * Kw > 576) return false;
-    return M >= (Kw <= 2 ? 16384 : 65536);
+    if (!dlrt::row_kernel_has(Kw) || (Kw > 16 && wbits > 2)) return false;
+    if (M < 2048 || (N + 31) / 32 > 65535) return false;  // lanes idle on few rows (none measured below 3136); grid limit
+    const int64_t from = Kw == 1 ? 256 : Kw == 2 ? 384 : Kw <= 4 ? 1024 : Kw <= 8 ? 3072 : Kw == 9 ? 1536 : Kw <= 16 ? 12288 : 4096;
+    return row_kernel_waves(M, N) >= from;
 }
 
-// Row kernel: a wave covers 64 rows x ncols columns.  One column group per row block amortises the row's
-// load and set-up best; the columns are split further (down to 32) while there are fewer waves than would
-// fill the chip twice.
-int plan_rows(int M, int N)
+// Row kernel: a wave covers 64 rows x ncols columns.  32 columns (one output word per row) measured fastest
+// or within 3 % of it at every size: more, shorter waves balance better over the SIMDs than the saved
+// activation loads are worth.  Only from about 32 K waves on do wider waves gain those few per cent.
+int plan_rows(int64_t M, int N)
 {
-    const int64_t row_blocks = ((int64_t)M + 63) / 64;
-    int ncols = (N + 31) / 32 * 32;
-    while (ncols > 32 && row_blocks * ((N + ncols - 1) / ncols) < 2048) ncols = (ncols / 2 + 31) / 32 * 32;
+    int ncols = 32;
+    while (ncols < 128 && ncols < N && ((M + 63) / 64) * ((N + ncols - 1) / ncols) > 32768) ncols *= 2;
     return ncols;
 }
 
@@ -167,7 +172,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
 {
     const bool wave = prefer_wave_kernel(M, N, abits, wbits);
     int rows = block_tile(abits), cols = block_tile(wbits), ks = 1;
-    if (prefer_rows_kernel(M, N, Kw)) {
+    if (prefer_rows_kernel(M, N, Kw, wbits)) {
         if (block_kernel) *block_kernel = 2;
         if (tile_rows) *tile_rows = 64;
         if (tile_cols) *tile_cols = plan_rows(M, N);
@@ -195,7 +200,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
-    if (prefer_rows_kernel(M, N, Kw)) return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N), stream);
+    if (prefer_rows_kernel(M, N, Kw, wbits)) return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N), stream);
     if (prefer_wave_kernel(M, N, abits, wbits)) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
         return wave_by_abits(g, o, abits, wbits, bipolar, false, p.tm, p.ksplit, stream);
@@ -239,7 +244,7 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     for (int i = 0; i < 2; ++i) {
         const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
         const int Kw = c[i].KH * c[i].KW * c[i].Cw;
-        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw);
+        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw, wbits);
     }
     if (!pairable) {
         for (int i = 0; i < 2; ++i) {
@@ -262,12 +267,12 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
                         hipStream_t stream)
 {
     const ContractArgs g = conv_args(X, Wp, c, a_msb_neg, w_msb_neg);
-    const bool rows_fit = g.Kw <= kRowKernelMaxWords;
+    const bool rows_fit = row_kernel_has(g.Kw);
     if (tile_rows == 64) {  // hint: the row kernel, ksplit groups of 32 columns per wave
         if (!rows_fit || ksplit < 0 || ksplit > 2048) return DLRT_ERR_SHAPE;
         return launch_rows(g, o, abits, wbits, bipolar, true, ksplit > 0 ? 32 * ksplit : plan_rows(g.M, g.N), stream);
     }
-    if (tile_rows == 0 && ksplit == 0 && rows_fit && prefer_rows_kernel(g.M, g.N, g.Kw))
+    if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits))
         return launch_rows(g, o, abits, wbits, bipolar, true, plan_rows(g.M, g.N), stream);
     if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
         const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);

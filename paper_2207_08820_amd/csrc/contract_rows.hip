@@ -1,5 +1,5 @@
-// Bit-serial contraction for SHORT reductions (at most 16 packed words): GEMMs over up to 512 elements,
-// 1x1 convolutions over few channels, 3x3 convolutions over up to 32 channels (9 words), where the tiled
+// Bit-serial contraction for SHORT reductions (at most 16 packed words, or 18): GEMMs over up to 512 elements,
+// 1x1 convolutions over few channels, 3x3 convolutions over up to 64 channels (9 or 18 words), where the tiled
 // kernels are mostly padding (their reduction step is 4 words, their tiles 32 or more columns wide, and
 // their per-tile set-up outweighs the work).
 //
@@ -45,6 +45,31 @@ __device__ __forceinline__ uint32_t dot4(uint32_t a, uint32_t b, uint32_t c)
 #else
     (void)a; (void)b;
     return c;  // host pass of the single-source compile: never executed
+#endif
+}
+
+// Marks `acc` as opaque between two steps of a popcount chain: the accumulation then stays a chain of
+// accumulating v_bcnt_u32_b32 (one instruction per word) instead of being re-associated into separate counts
+// joined by three-input adds.  Emits no instruction.
+__device__ __forceinline__ void keep_chain(int &acc)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(acc));
+#else
+    (void)acc;
+#endif
+}
+
+// a * b + c on 24-bit operands, b uniform over the wave: one full-rate instruction (a general 32-bit
+// multiply runs at a quarter of that rate).
+__device__ __forceinline__ int mad24(int a, int b, int c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    int d;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(b), "v"(c));
+    return d;
+#else
+    return a * b + c;
 #endif
 }
 
@@ -142,11 +167,13 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             for (int i = 0; i < WB; ++i) {
                 int acc = 0;
 #pragma unroll
-                for (int k = 0; k < KW; ++k)  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
+                for (int k = 0; k < KW; ++k) {  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
                     acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
-                part += __mul24(acc, BIPOLAR ? 2 : wcoef[i]);
+                    keep_chain(acc);
+                }
+                part = BIPOLAR ? part + 2 * acc : mad24(acc, wcoef[i], part);
             }
-            total += __mul24(part, acoef[j]);
+            total = mad24(part, acoef[j], total);
         }
         return total;
     };
@@ -164,12 +191,11 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             }
         }
     };
-    // bias may be absent: read a valid address anyway and select, so that the column loop has no branch
+    // bias may be absent: read a valid address anyway and mask the bits (all uniform, so on the scalar unit),
+    // so that the column loop has neither a branch nor a per-lane select
     const float *const bias_or_scale = bias ? bias : scale;
-    auto bias_of = [&](int n) {
-        const float b = bias_or_scale[n];
-        return bias ? b : 0.0f;
-    };
+    const uint32_t bias_mask = bias ? 0xffffffffu : 0u;
+    auto bias_of = [&](int n) { return __uint_as_float(__float_as_uint(bias_or_scale[n]) & bias_mask); };
     auto quantized = [&](int total, int n) {
         const float y = __fmaf_rn((float)total, scale[n], bias_of(n));
         return (uint32_t)clamp0(rintf(y), qmax);
@@ -247,6 +273,7 @@ dlrt_status pick_kw(const ContractArgs &g, const FusedOut &o, bool conv, int nco
     if (g.Kw <= 8) return launch_conv_or_gemm<AB, WB, 8, BIPOLAR>(g, o, conv, ncols, stream);
     if (g.Kw == 9) return launch_conv_or_gemm<AB, WB, 9, BIPOLAR>(g, o, conv, ncols, stream);  // 3x3 taps of one word
     if (g.Kw <= 16) return launch_conv_or_gemm<AB, WB, 16, BIPOLAR>(g, o, conv, ncols, stream);
+    if (g.Kw == 18) return launch_conv_or_gemm<AB, WB, 18, BIPOLAR>(g, o, conv, ncols, stream);  // 3x3 taps of two words
     return DLRT_ERR_SHAPE;  // never planned: the reduction is too long for a lane's registers
 }
 

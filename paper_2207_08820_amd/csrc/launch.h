@@ -58,9 +58,10 @@ dlrt_status launch_wave_a2(const ContractArgs *g, const FusedOut *o, int count, 
 dlrt_status launch_wave_a3(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 dlrt_status launch_wave_a4(const ContractArgs *g, const FusedOut *o, int count, int wbits, bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream);
 
-// Row kernel (contract_rows.hip): one output row per lane, for reductions of at most 16 words; GEMM or any
-// convolution (a conv's words are those of its im2col row).  ncols: output columns per wave, a multiple of 32.
-constexpr int kRowKernelMaxWords = 16;
+// Row kernel (contract_rows.hip): one output row per lane, for reductions of at most 16 words, or of 18 (3x3
+// taps of two words); GEMM or any convolution (a conv's words are those of its im2col row).  ncols: output
+// columns per wave, a multiple of 32.
+inline bool row_kernel_has(int Kw) { return Kw <= 16 || Kw == 18; }
 dlrt_status launch_rows_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);

@@ -159,14 +159,24 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     blk, rows, cols, ks = query(lib, 49, 512, 4608, 2, 2)
     assert (blk, rows, cols) == (0, 8, 32) and ks >= 4
     assert query(lib, 784, 128, 64, 2, 2) == (0, 8, 32, 1)  # two steps of reduction: nothing to split
-    # many rows, few columns, a reduction of a word or two: one output row per lane
+    # short reductions and enough 64-row x 32-column waves: one output row per lane, 32 columns per wave
     assert query(lib, 409600, 32, 32, 2, 1) == (2, 64, 32, 1)
-    assert query(lib, 50176, 128, 64, 2, 2) == (2, 64, 32, 1)    # 784 row blocks: the columns are split to get more waves
-    assert query(lib, 1 << 20, 128, 64, 2, 2) == (2, 64, 128, 1)  # enough row blocks: a wave keeps all columns of its rows
-    assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # too few rows
+    assert query(lib, 50176, 128, 64, 2, 2) == (2, 64, 32, 1)
+    assert query(lib, 1 << 20, 128, 64, 2, 2) == (2, 64, 64, 1)   # 65536 waves of 32 columns: wider waves
+    assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # 200 waves: too few for two words
+    assert query(lib, 6400, 64, 32, 2, 1)[0] == 0                 # ... and for one
+    assert query(lib, 12544, 64, 32, 2, 1)[0] == 2                # 392 waves of one word
     assert query(lib, 409600, 64, 288, 2, 1)[0] == 2              # a 3x3 conv over 32 channels: nine words
-    assert query(lib, 409600, 32, 576, 2, 1)[0] == 0              # eighteen words; 32 columns are half a 64-column block tile
-    assert query(lib, 409600, 64, 576, 2, 1) == (1, 64, 64, 1)
+    assert query(lib, 25600, 64, 288, 2, 1)[0] == 1               # the same at batch 1: 800 waves are too few
+    assert query(lib, 25600, 32, 64, 2, 1)[0] == 2                # two words: 400 waves are enough
+    assert query(lib, 12544, 64, 288, 2, 2)[0] == 1               # 392 waves of nine words: the block kernel
+    assert query(lib, 200704, 64, 576, 2, 2) == (2, 64, 32, 1)    # eighteen words (3x3 over 64 channels), 6272 waves
+    assert query(lib, 50176, 64, 576, 2, 2)[0] == 1               # 1568 waves of eighteen words: the block kernel
+    assert query(lib, 200704, 64, 576, 4, 4)[0] == 1              # eighteen words of 3- or 4-bit weights never
+    assert query(lib, 200704, 64, 512, 2, 2)[0] == 1              # sixteen words fill the block kernel's chunk: 6272 waves are not enough
+    assert query(lib, 200704, 128, 512, 2, 2)[0] == 2             # 12544 are
+    assert query(lib, 200704, 64, 544, 2, 2)[0] == 1              # seventeen words: the row kernel has no such instance
+    assert query(lib, 1000, 4096, 32, 2, 2)[0] != 2               # few rows: lanes would idle
     assert query(lib, 50176, 128, 1152, 2, 2) == (1, 32, 64, 1)   # 1568 tiles of 64 rows: the half-height tile
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
@@ -177,14 +187,17 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
     r = random.Random(3)
     for _ in range(2000):
         a, w = r.randint(1, 4), r.randint(1, 4)
-        M, N = r.choice([1, 7, 49, 196, 784, 3136, 25600, 100000]), r.choice([1, 16, 32, 64, 100, 512, 4096])
-        K = r.choice([1, 32, 64, 288, 576, 1152, 4608, 40000])
+        M, N = r.choice([1, 7, 49, 196, 784, 3136, 25600, 100000, 3000000]), r.choice([1, 16, 32, 64, 100, 512, 4096])
+        K = r.choice([1, 32, 64, 100, 288, 500, 544, 576, 1152, 4608, 40000])
         blk, rows, cols, ks = query(lib, M, N, K, a, w)
         tn = 4 if w <= 2 else 2
         if blk == 2:  # the row kernel: the reduction fits a lane's registers, whole output words per wave
             Kw = -(-K // 32)
-            assert Kw <= 9 and N * Kw <= 576 and M >= (16384 if Kw <= 2 else 65536)
-            assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= -(-N // 32) * 32
+            waves = -(-M // 64) * -(-N // 32)
+            assert (Kw <= 16 or (Kw == 18 and w <= 2)) and M >= 2048
+            assert waves >= (256 if Kw == 1 else 384 if Kw == 2 else 1024 if Kw <= 4 else 3072 if Kw <= 8 else 1536 if Kw == 9
+                             else 12288 if Kw <= 16 else 4096)
+            assert rows == 64 and ks == 1 and cols in (32, 64, 128) and (cols == 32 or -(-M // 64) * -(-N // (cols // 2)) > 32768)
         elif blk:
             full = 16 * [4, 4, 2, 2][a - 1]   # problems with few full tiles take the half-height tile
             assert (cols, ks) == (16 * [4, 4, 2, 2][w - 1], 1) and rows in (full, full // 2)

@@ -423,7 +423,7 @@ def test_conv_fused_edge_shapes_all_encodings(dlrt, oracle, shape):
 
 
 ROW_KERNEL_SHAPES = [
-    # N, H, W, Ci, Co, k, stride, pad: convs whose im2col row fits a lane's registers (<= 16 words)
+    # N, H, W, Ci, Co, k, stride, pad: convs whose im2col row fits a lane's registers (<= 16 words, or 18)
     (1, 9, 7, 32, 32, 1, 1, 0),      # one word, one output word
     (2, 10, 10, 33, 20, 1, 2, 0),    # ragged channels (2 words, the second nearly empty), stride 2, batch 2
     (1, 12, 12, 64, 70, 1, 1, 0),    # ragged output columns: three column words, the last partly filled
@@ -438,6 +438,8 @@ ROW_KERNEL_SHAPES = [
     (1, 8, 8, 40, 24, 2, 2, 0),      # 2x2 taps of two words: eight words
     (1, 7, 6, 8, 10, 4, 1, 2),       # 4x4 taps: sixteen words, padding wider than one pixel
     (1, 6, 6, 500, 12, 1, 1, 1),     # sixteen words of channels, 1x1 with padding (border outputs are the bias)
+    (2, 9, 10, 64, 40, 3, 1, 1),     # 3x3 over two words of channels: eighteen words, batch 2
+    (1, 11, 8, 48, 70, 3, 2, 1),     # the same with ragged channels, stride 2 and a ragged third output word
 ]
 
 
@@ -468,7 +470,8 @@ def test_conv_fused_row_kernel_rejects_what_it_cannot_hold(dlrt):
                                                                     dtype=torch.uint8, device=DEV), tile_rows=64)
     call(64, 1, 0)  # two words: fits
     call(32, 3, 1)  # nine words: fits
-    for Ci, k, pad in ((64, 3, 1), (544, 1, 0)):  # eighteen and seventeen words
+    call(64, 3, 1)  # eighteen words (3x3 taps of two words): fits
+    for Ci, k, pad in ((96, 3, 1), (544, 1, 0)):  # twenty-seven and seventeen words
         with pytest.raises(dlrt.DlrtError):
             call(Ci, k, pad)
     torch.cuda.synchronize()
@@ -539,9 +542,10 @@ def test_conv_fused_rejects_hints_the_kernels_do_not_have(dlrt):
 
 # ---- fused epilogue on the throughput (block) kernel: problems large enough to leave the per-wave kernel ----
 @pytest.mark.parametrize("abits,wbits,ea,ew,qbits,M,N,K", [
-    (2, 2, UNSIGNED, TWOS, 2, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 1, 2900, 2950, 96),
+    (2, 2, UNSIGNED, TWOS, 2, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 1, 2900, 2950, 608),
     (4, 4, UNSIGNED, TWOS, 4, 730, 750, 50), (3, 3, TWOS, TWOS, 3, 760, 710, 330), (2, 4, UNSIGNED, TWOS, 2, 1500, 700, 64)])
 def test_gemm_fused_large_shapes(dlrt, oracle, abits, wbits, ea, ew, qbits, M, N, K):
+    assert dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"] == "block"
     a = inputs.uniform_values((M, K), abits, ea, 41000 + M)
     w = inputs.uniform_values((N, K), wbits, ew, 42000 + N)
     ref = (a.astype(np.int64) @ w.astype(np.int64).T).astype(np.int32)
@@ -586,11 +590,12 @@ def test_gemm_fused_small_shape_takes_the_per_wave_kernel(dlrt, oracle):
 
 
 @pytest.mark.parametrize("abits,wbits,ea,ew,qbits,M,N,K", [
-    (2, 2, UNSIGNED, TWOS, 2, 20000, 40, 50), (2, 1, UNSIGNED, BIPOLAR, 2, 70000, 33, 200),
-    (4, 4, TWOS, TWOS, 4, 65536, 7, 256), (1, 3, UNSIGNED, UNSIGNED, 1, 70001, 64, 31), (3, 2, TWOS, UNSIGNED, 3, 33000, 128, 64)])
+    (2, 2, UNSIGNED, TWOS, 2, 20000, 40, 50), (2, 1, UNSIGNED, BIPOLAR, 2, 100000, 33, 200),
+    (4, 4, TWOS, TWOS, 4, 200000, 7, 256), (1, 3, UNSIGNED, UNSIGNED, 1, 70001, 64, 31), (3, 2, TWOS, UNSIGNED, 3, 33000, 128, 64),
+    (2, 2, UNSIGNED, TWOS, 2, 10000, 300, 288), (2, 2, UNSIGNED, TWOS, 2, 60000, 130, 576), (1, 1, UNSIGNED, BIPOLAR, 2, 100100, 256, 500)])
 def test_gemm_tall_skinny_takes_the_row_kernel(dlrt, oracle, abits, wbits, ea, ew, qbits, M, N, K):
-    """Many rows, few columns and a reduction of at most 8 words: the planner picks the kernel with one
-    output row per lane, for the plain GEMM and for every output of the fused one."""
+    """A reduction of at most 16 words (or 18) and enough waves of 64 rows x 32 columns: the planner picks the
+    kernel with one output row per lane, for the plain GEMM and for every output of the fused one."""
     assert dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"] == "rows"
     a = inputs.uniform_values((M, K), abits, ea, 41000 + M % 97)
     w = inputs.uniform_values((N, K), wbits, ew, 42000 + N)
@@ -629,9 +634,9 @@ def test_random_gemms_across_the_kernel_choice_boundaries(dlrt, oracle):
         abits, wbits = int(r.integers(1, 5)), int(r.integers(1, 5))
         ea = int(r.choice([UNSIGNED, TWOS]))
         ew = BIPOLAR if wbits == 1 and r.random() < 0.5 else int(r.choice([UNSIGNED, TWOS]))
-        M = int(r.choice([1, 63, 64, 65, 1000, 16383, 16384, 16385, 40000, 65535, 65536, 70000]))
+        M = int(r.choice([1, 63, 64, 65, 1000, 2047, 2048, 2049, 16384, 16385, 40000, 65535, 65536, 70000]))
         N = int(r.choice([1, 31, 32, 33, 64, 65, 96, 128, 200, 288]))
-        K = int(r.choice([1, 31, 32, 33, 64, 65, 128, 256, 257, 288, 289, 512, 513, 600]))
+        K = int(r.choice([1, 31, 32, 33, 64, 65, 128, 256, 257, 288, 289, 512, 513, 544, 570, 576, 600]))
         if M * N * K > 3e9:   # keep the oracle's share of the test short
             M = 16385
         qbits = int(r.integers(1, 5))
@@ -737,7 +742,7 @@ def every_output_agrees(acc, y, q, packed, scale, bias, qbits, chunk=1 << 16):
 
 
 @pytest.mark.parametrize("kernel,M,N,K,abits,wbits,ew", [
-    ("block", 1040013, 2080, 40, 2, 2, TWOS),          # 2.16e9 outputs, ragged in M, N and K
+    ("block", 1040013, 2080, 680, 2, 2, TWOS),         # 2.16e9 outputs, ragged in M, N and K (22 words)
     ("rows", (1 << 25) + 21, 65, 32, 2, 1, BIPOLAR)])  # 2.18e9 outputs, one word per row
 def test_gemm_more_than_2_31_outputs(dlrt, oracle, kernel, M, N, K, abits, wbits, ew):
     """Element indices of every output pass 2^31 (an int32 result of 8.7 GB): sampled rows of all four fused
@@ -775,20 +780,20 @@ def test_gemm_more_than_2_31_outputs(dlrt, oracle, kernel, M, N, K, abits, wbits
     assert torch.equal(plain, acc)
 
 
-@pytest.mark.parametrize("kernel,Co,k,hint", [("rows", 32, 3, 0), ("block", 96, 3, 0), ("wave", 24, 1, 8)])
-def test_conv_image_too_large_for_multiply_high_division(dlrt, oracle, kernel, Co, k, hint):
+@pytest.mark.parametrize("kernel,Ci,Co,k,hint", [("rows", 32, 32, 3, 0), ("block", 96, 40, 3, 0), ("wave", 32, 24, 1, 8)])
+def test_conv_image_too_large_for_multiply_high_division(dlrt, oracle, kernel, Ci, Co, k, hint):
     """2048 x 2048 output pixels: pixels * width passes 2^32, so output row -> (image, row, column) uses the
     hardware's division instead of the multiply-high shortcut, in each of the three kernels."""
     H = W = 2048
     if not hint:
-        assert dlrt.dlrt_query_plan(H * W, Co, k * k * 32, 2, 2)["kernel"] == kernel
-    x = inputs.uniform_values((1, H, W, 32), 2, UNSIGNED, 55000 + Co)
-    w = inputs.uniform_values((Co, k, k, 32), 2, TWOS, 55001 + Co)
+        assert dlrt.dlrt_query_plan(H * W, Co, k * k * (Ci // 32) * 32, 2, 2)["kernel"] == kernel
+    x = inputs.uniform_values((1, H, W, Ci), 2, UNSIGNED, 55000 + Co)
+    w = inputs.uniform_values((Co, k, k, Ci), 2, TWOS, 55001 + Co)
     ref = oracle.conv2d_i32(x, w, (1, 1), (k // 2, k // 2))
     X = dlrt.dlrt_pack_bitplanes(src_tensor(x, UNSIGNED), 2, UNSIGNED)
     Wp = dlrt.dlrt_pack_conv_weights(dev(w), 2, TWOS)
     acc = torch.full((1, H, W, Co), -7, dtype=torch.int32, device=DEV)
-    dlrt.dlrt_bitserial_conv2d_fused(X, Wp, None, None, 1, H, W, 32, Co, k, k, (1, 1), (k // 2, k // 2), 2, 2, UNSIGNED,
+    dlrt.dlrt_bitserial_conv2d_fused(X, Wp, None, None, 1, H, W, Ci, Co, k, k, (1, 1), (k // 2, k // 2), 2, 2, UNSIGNED,
                                      TWOS, out_acc=acc, tile_rows=hint)
     torch.cuda.synchronize()
     assert np.array_equal(acc.cpu().numpy(), ref)
@@ -853,9 +858,10 @@ def test_conv_large_image_single_channel_word(dlrt, oracle):
 
 # ---- GEMM through both kernels: large shapes take the block kernel, small ones the per-wave kernel ----
 def test_gemm_ragged_large_shape_block_kernel(dlrt, oracle):
-    for abits, wbits, ea, ew, M, N, K in [(2, 2, UNSIGNED, TWOS, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 2900, 2950, 96),
+    for abits, wbits, ea, ew, M, N, K in [(2, 2, UNSIGNED, TWOS, 1500, 1400, 200), (1, 1, UNSIGNED, BIPOLAR, 2900, 2950, 608),
                                           (4, 4, UNSIGNED, TWOS, 730, 750, 50), (3, 3, TWOS, TWOS, 760, 710, 330),
-                                          (1, 1, UNSIGNED, TWOS, 3000, 2900, 70)]:
+                                          (1, 1, UNSIGNED, TWOS, 3000, 2900, 530)]:
+        assert dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"] == "block"
         a = inputs.uniform_values((M, K), abits, ea, 31000 + M)
         w = inputs.uniform_values((N, K), wbits, ew, 32000 + N)
         got = gpu_gemm(dlrt, a, w, abits, wbits, ea, ew)
