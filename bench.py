@@ -123,7 +123,7 @@ def layer_floors(L, abits, wbits, qbits, batch=1):
     return abits * wbits * batch * L.macs / 16.0 / VALU_PEAK_LANE_OPS * 1e6, nbytes / HBM_PEAK_BYTES * 1e6
 
 
-def stack_ms(dlrt, dev, which, iters=50, batch=1):
+def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0):
     """Whole conv chain of a model-shaped stack ("resnet18": 19 convs A2W2; "yolo": 16 convs A2 / bipolar
     W1).  Scale and bias come from the closed-form mean / deviation of a uniform-input layer; timing
     does not depend on the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
@@ -149,6 +149,14 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1):
 
     stack = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=True, keep_outputs=False,
                       batch=batch)
+    if launches_only:  # counter-collection runs: every layer's fused kernel a few times, eagerly, nothing timed
+        stack.run(x0)
+        for i in range(len(stack.layers)):
+            xin = stack.layer_input(i)
+            for _ in range(launches_only):
+                stack.run_layer_fused(i, xin)
+        torch.cuda.synchronize()
+        return {}, [{"layer": pl.spec.name, "M": batch * pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K} for pl in stack.layers]
     stack.capture(x0)
     for _ in range(5):
         stack.replay()
@@ -219,6 +227,9 @@ def main():
     ap.add_argument("--gemm-only", action="store_true",
                     help="time only the GEMM step (for counter-collection runs, which serialise every launch)")
     ap.add_argument("--sweep", action="store_true", help="also time the other bit-width pairs of the 4096^3 sweep")
+    ap.add_argument("--conv-launches", type=int, default=0, metavar="R",
+                    help="instead of timing the conv stacks, launch every layer of the batch-64 ResNet-18 and batch-16 "
+                         "YOLO-style chains R times (for rocprofv3 --pmc runs: counters per layer kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (a kernel of known HBM traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -284,6 +295,10 @@ def main():
     torch.cuda.synchronize()
     extra["unfused_step_ms"] = round(time_events(unfused, 20), 5)
     if args.gemm_only:
+        return emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t)
+    if args.conv_launches:
+        for which, b in (("resnet18", 64), ("yolo", 16)):
+            extra[f"{which}_batch{b}_layers_launched"] = stack_ms(dlrt, dev, which, batch=b, launches_only=args.conv_launches)[1]
         return emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t)
     r18, per_layer = stack_ms(dlrt, dev, "resnet18")
     extra["resnet18_a2w2_conv_stack_ms"] = round(r18["graph_fused_ms"], 5)
