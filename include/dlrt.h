@@ -188,8 +188,8 @@ dlrt_status dlrt_bitserial_conv2d_fused_pair(const dlrt_conv_problem *first, con
  *   *block_kernel = 1: the throughput kernel (one 256-thread block per tile_rows x tile_cols tile, ksplit 1)
  *   *block_kernel = 0: the latency kernel (one wave per tile_rows x 32 tile, ksplit waves split K)
  *   *block_kernel = 2: the row kernel (one output row per lane: a wave covers 64 rows x tile_cols columns);
- *                      taken when the reduction is at most 16 packed words and there are many rows and few
- *                      columns.
+ *                      taken when the reduction is at most 16 packed words (or 18) and the problem has
+ *                      enough 64-row x 32-column waves for that reduction length.
  * Any output pointer may be NULL.
  */
 dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbits, int *block_kernel,
