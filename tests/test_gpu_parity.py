@@ -703,6 +703,43 @@ def test_conv_fused_large_batch_takes_the_block_kernel(dlrt, oracle):
     fused_case(dlrt, oracle, xb, wb, 2, 1, 2, 1, UNSIGNED, BIPOLAR, 2)
 
 
+# ---- streams: every call enqueues on the stream it is given and never synchronises -------------------------
+def test_calls_follow_the_current_stream_and_two_streams_do_not_mix(dlrt, oracle):
+    """Two independent pack -> GEMM -> epilogue chains, each enqueued on a stream of its own (the binding hands
+    torch's current stream to the C ABI), interleaved call by call; results are read only after each stream's
+    own synchronisation."""
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    cases = [(300, 200, 1000, 2, 2, TWOS), (257, 129, 4100, 4, 1, BIPOLAR)]
+    host, state = [], [{}, {}]
+    for i, (M, N, K, abits, wbits, ew) in enumerate(cases):
+        a = inputs.uniform_values((M, K), abits, UNSIGNED, 57000 + i)
+        w = inputs.uniform_values((N, K), wbits, ew, 57010 + i)
+        host.append((a, w, inputs.uniform_scale(N, 57020 + i)))
+    steps = ["upload", "pack_a", "pack_w", "gemm", "epilogue"]
+    for step in steps:  # interleave the two chains step by step
+        for i, (M, N, K, abits, wbits, ew) in enumerate(cases):
+            st, (a, w, scale) = state[i], host[i]
+            with torch.cuda.stream(streams[i]):
+                if step == "upload":
+                    st["a"], st["w"], st["s"] = src_tensor(a, UNSIGNED), src_tensor(w, ew), dev(scale)
+                elif step == "pack_a":
+                    st["A"] = dlrt.dlrt_pack_bitplanes(st["a"], abits, UNSIGNED)
+                elif step == "pack_w":
+                    st["W"] = dlrt.dlrt_pack_bitplanes(st["w"], wbits, ew)
+                elif step == "gemm":
+                    st["C"] = dlrt.dlrt_bitserial_gemm(st["A"], st["W"], M, N, K, abits, wbits, UNSIGNED, ew)
+                else:
+                    st["y"], st["q"] = dlrt.dlrt_epilogue_f32(st["C"], st["s"], qbits=2)
+    for i, (M, N, K, abits, wbits, ew) in enumerate(cases):
+        streams[i].synchronize()
+        a, w, scale = host[i]
+        ref = oracle.gemm_i32(a, w)
+        y_ref, q_ref = oracle.epilogue_f32(ref, scale, qbits=2)
+        assert np.array_equal(state[i]["C"].cpu().numpy(), ref), i
+        assert np.array_equal(state[i]["y"].cpu().numpy(), y_ref) and np.array_equal(state[i]["q"].cpu().numpy(), q_ref), i
+    torch.cuda.synchronize()
+
+
 # ---- sizes at the far ends -------------------------------------------------------------------------------
 def test_gemm_very_tall_output_indexing_beyond_2_31_bytes(dlrt, oracle):
     """M = 2^24 + 5 rows of 40 outputs: the int32 result is 2.7 GB, so byte offsets pass 2^31; sampled rows
