@@ -375,6 +375,15 @@ def test_config3_stack_as_hip_graph_every_replay_bit_exact(dlrt, oracle):
     run_stack_against_oracle(dlrt, oracle, 3, inputs.resnet18_stack(), 2, TWOS, fused=True, graph=True)
 
 
+def test_config4_stack_batched_as_hip_graph_every_replay_bit_exact(dlrt, oracle):
+    """The YOLO-style chain at batch 2 in one captured graph: row, block and per-wave kernels and the paired
+    launches all sit in the same graph; three replays with eager work between them, each checked."""
+    layers = inputs.yolo_style_stack()
+    kinds = {dlrt.dlrt_query_plan(2 * L.M, L.Co, L.k * L.k * ((L.Ci + 31) // 32) * 32, 2, 1)["kernel"] for L in layers}
+    assert kinds == {"rows", "block", "wave"}
+    run_stack_against_oracle(dlrt, oracle, 4, layers, 1, BIPOLAR, fused=True, graph=True, batch=2)
+
+
 # ---- fused convolution: conv + scale/bias + requant + bitplanes of the result in one launch -------------
 def fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=0, ksplit=0, seed=0,
                packed_only=False):
