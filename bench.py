@@ -372,6 +372,21 @@ def main():
                               "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
                               "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
                 log(sweep[-1])
+            if (ab, wb) == (1, 1):  # the extra row: the same sizes with bipolar (+1 / -1) weights
+                w_bip = torch.as_tensor(inputs.uniform_values((cs.N, cs.K), 1, inputs.BIPOLAR, inputs.seed_for(5, 1) + 7), device=dev)
+                dlrt.dlrt_pack_bitplanes(w_bip, 1, inputs.BIPOLAR, out=ts["W"])
+
+                def bipolar_gemm(ts=ts, cs=cs):
+                    dlrt.dlrt_bitserial_gemm(ts["A"], ts["W"], cs.M, cs.N, cs.K, 1, 1, cs.enc_a, inputs.BIPOLAR, out=ts["C"])
+
+                for _ in range(3):
+                    bipolar_gemm()
+                torch.cuda.synchronize()
+                ms = time_events(bipolar_gemm, 20)
+                sweep.append({"abits": 1, "wbits": 1, "enc_w": "bipolar", "gemm_ms": round(ms, 5),
+                              "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
+                              "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
+                log(sweep[-1])
             del ts
         extra["sweep_4096"] = sweep
 

@@ -205,10 +205,20 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
                 stageW[t] = load4_tail<VEC>(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
         }
     };
+    // Bipolar weights need popcount(A[j]) of every row (Section V's sum with weight bits 0 read as -1:
+    // 2 * popcount(A & W) - popcount(A)).  It is counted where each activation word passes through a register
+    // exactly once, in the thread that stages it: a partial count per staging slot (row, plane, 4-word column
+    // of the chunk), summed over the four slots of a row and plane after the reduction.
+    int stagepc[MapA::kPerThread];
+#pragma unroll
+    for (int t = 0; t < MapA::kPerThread; ++t) stagepc[t] = 0;
     auto commit = [&](int buf) {
 #pragma unroll
         for (int t = 0; t < MapA::kPerThread; ++t)
-            if (dstA[t] >= 0) ldsA[buf * kTileA + dstA[t]] = stageA[t];
+            if (dstA[t] >= 0) {
+                ldsA[buf * kTileA + dstA[t]] = stageA[t];
+                if (BIPOLAR) stagepc[t] += __popc(stageA[t].x) + __popc(stageA[t].y) + __popc(stageA[t].z) + __popc(stageA[t].w);
+            }
 #pragma unroll
         for (int t = 0; t < MapW::kPerThread; ++t)
             if (dstW[t] >= 0) ldsW[buf * kTileW + dstW[t]] = stageW[t];
@@ -217,15 +227,12 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     // acc[r][j][s * WB + i]: row r of the lane tile, activation plane j, column s, weight plane i
     constexpr int NG = TN * WB;
     int acc[TM][AB][NG];
-    int rowpc[TM][AB];
 #pragma unroll
     for (int r = 0; r < TM; ++r)
 #pragma unroll
-        for (int j = 0; j < AB; ++j) {
-            rowpc[r][j] = 0;
+        for (int j = 0; j < AB; ++j)
 #pragma unroll
             for (int n = 0; n < NG; ++n) acc[r][j][n] = 0;
-        }
 
     fetch(0);
     commit(0);
@@ -275,7 +282,6 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
                     for (int j = 0; j < AB; ++j) {
                         const uint4 &q = av[b][r][j];
                         const uint32_t a = e == 0 ? q.x : e == 1 ? q.y : e == 2 ? q.z : q.w;
-                        if (BIPOLAR) popc_acc(rowpc[r][j], a);
                         and_popc_group<NG>(acc[r][j], a, w);
                     }
             }
@@ -302,6 +308,24 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
 
         if (chunk + 1 < nchunks) commit(buf ^ 1);
         __syncthreads();
+    }
+
+    int rowpc[TM][AB];
+    if (BIPOLAR) {
+        __shared__ int pcbuf[BIPOLAR ? kK4 * AB * BM : 1];  // [k4][plane][row], as the staging slots are numbered
+#pragma unroll
+        for (int t = 0; t < MapA::kPerThread; ++t)
+            if (dstA[t] >= 0) pcbuf[dstA[t]] = stagepc[t];
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < TM; ++r)
+#pragma unroll
+            for (int j = 0; j < AB; ++j) {
+                int n = 0;
+#pragma unroll
+                for (int k4 = 0; k4 < kK4; ++k4) n += pcbuf[(k4 * AB + j) * BM + ty + 16 * r];
+                rowpc[r][j] = n;
+            }
     }
 
     // ---- combine the plane pairs (signs and shifts of Section V's double sum), then the optional fused
