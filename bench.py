@@ -211,10 +211,34 @@ def cpu_baseline(t, budget_s=12.0):
         acc = oracle.gemm_i32(a[:rows], w)
         oracle.epilogue_f32(acc, scale)
     dt = (time.perf_counter() - t0) / reps
-    return {"value": round(2.0 * rows * c.N * c.K / dt / 1e12, 6), "unit": "effective TOPS",
-            "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"first {rows} of {c.M} activation rows against all {c.N} weight rows, K={c.K} "
-                      f"(pack + int32 GEMM + scale epilogue), {reps} run(s) of {dt:.2f} s"}
+    out = {"value": round(2.0 * rows * c.N * c.K / dt / 1e12, 6), "unit": "effective TOPS",
+           "cores": oracle.num_threads(), "kind": "oracle",
+           "sample": f"first {rows} of {c.M} activation rows against all {c.N} weight rows, K={c.K} "
+                     f"(pack + int32 GEMM + scale epilogue), {reps} run(s) of {dt:.2f} s"}
+
+    # the two small configurations (64 x 64 x 576 GEMM, 56 x 56 x 64 -> 64 3x3 conv) on one thread and on all
+    from paper_2207_08820_amd import inputs
+
+    def best_us(fn, runs=5):
+        fn()
+        best = 1e30
+        for _ in range(runs):
+            t0 = time.perf_counter()
+            fn()
+            best = min(best, time.perf_counter() - t0)
+        return round(best * 1e6, 1)
+
+    _, a1, w1 = inputs.config1()
+    _, x2, w2, _ = inputs.config2()
+    threads = oracle.num_threads()
+    small = {}
+    for label, n in (("1_thread", 1), (f"{threads}_threads", threads)):
+        oracle.set_threads(n)
+        small[label] = {"config1_gemm_us": best_us(lambda: oracle.gemm_i32(a1, w1)),
+                        "config2_conv_us": best_us(lambda: oracle.conv2d_i32(x2, w2, (1, 1), (1, 1)))}
+    oracle.set_threads(threads)
+    out["small_configs"] = small
+    return out
 
 
 def main():
