@@ -21,10 +21,10 @@ import numpy as np
 # plain 32-bit VALU rate of the chip: 256 compute units x 64 lanes per clock x 2.4 GHz
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
 # HBM bytes per launch of the 4096^3 A2W2 GEMM kernel, from the committed rocprofv3 --pmc runs
-# (profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md): FETCH_SIZE 18700 KiB x 2.000 (calibration
+# (profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md): FETCH_SIZE 12616 KiB x 2.000 (calibration
 # against a plain 256 MiB copy) + WRITE_SIZE 65536 KiB.  Counters cannot be read from inside this
 # script, so the figure is only reported for the exact workload it was measured on.
-GEMM_4096_A2W2_TRAFFIC_BYTES = int((18700 * 2.0 + 65536) * 1024)
+GEMM_4096_A2W2_TRAFFIC_BYTES = int((12616 * 2.0 + 65536) * 1024)
 
 
 def log(*a):

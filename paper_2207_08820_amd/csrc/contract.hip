@@ -104,7 +104,22 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int tilesN = (g.N + BN - 1) / BN;
-    const int tileM = blockIdx.x / tilesN, tileN = blockIdx.x - tileM * tilesN;
+    int tileM, tileN;
+    if (g.xcd_split) {
+        // Consecutive blocks go to the chip's 8 dies (XCDs) in turn, each with an L2 of its own.  Block b is
+        // therefore given a tile of die (b mod 8)'s own 1/2 x 1/4 part of the tile grid, so that a die's L2
+        // fetches half of A's rows and a quarter of W's instead of all of one of them: 24 MiB instead of 36
+        // from HBM for the 8 MiB of operands of a 4096^3 A2W2 GEMM.  Any mapping is correct (it is a
+        // bijection); the launcher sets the flag only when the grid divides evenly.
+        const int tilesM = (g.M + BM - 1) / BM, subN = tilesN >> 2;
+        const int die = blockIdx.x & 7, local = blockIdx.x >> 3;
+        const int lm = local / subN, ln = local - lm * subN;
+        tileM = (die >> 2) * (tilesM >> 1) + lm;
+        tileN = (die & 3) * subN + ln;
+    } else {
+        tileM = blockIdx.x / tilesN;
+        tileN = blockIdx.x - tileM * tilesN;
+    }
     const int m0 = tileM * BM, n0 = tileN * BN;
 
     // ---- staging slots, resolved once.  Rows beyond the matrix are clamped to its last row:
@@ -434,8 +449,10 @@ dlrt_status launch_tile(const ContractArgs &g, const FusedOut &o, hipStream_t st
     constexpr int TN = LaneTile<WB>::value;
     const int64_t tilesM = (g.M + 16 * TM - 1) / (16 * TM), tilesN = (g.N + 16 * TN - 1) / (16 * TN);
     if (tilesM * tilesN > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    ContractArgs ga = g;
+    ga.xcd_split = tilesM % 2 == 0 && tilesN % 4 == 0;
     hipLaunchKernelGGL((contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>), dim3((unsigned)(tilesM * tilesN)),
-                       dim3(kThreads), 0, stream, g, o);
+                       dim3(kThreads), 0, stream, ga, o);
     return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
 }
 
