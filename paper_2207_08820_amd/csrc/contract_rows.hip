@@ -14,8 +14,8 @@
 // the packed output needs no ballot or shuffle either.
 //
 // A wave covers 64 rows x `ncols` columns (a multiple of 32, so that waves own whole output words);
-// the grid is rows/64 x N/ncols.  int32 / float / uint8 outputs are written one element per lane with
-// a row stride between lanes: correct, but only the packed output is a fast path.
+// the grid is one one-wave block per (64 rows, ncols columns).  int32 / float / uint8 outputs are written one
+// element per lane with a row stride between lanes: correct, but only the packed output is a fast path.
 //
 // Measured and dropped: software-pipelining the scalar loads (the next group's weights requested while this
 // group is computed, both groups in scalar registers) was 0 to 7 % slower on 14 layer shapes; with seven waves
@@ -98,9 +98,18 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
 {
     // Wp / scale / bias repeat g.W / o.scale / o.bias as parameters of their own: only a read-only
     // pointer that provably aliases none of the stores is loaded through the scalar unit.
-    const int m = blockIdx.x * kRowsPerBlock + threadIdx.x;
+    // Block -> (row block, column group).  Consecutive blocks go to the chip's 8 dies in turn, each with an
+    // L2 of its own, so the column groups of one row block are numbered 8 apart (plus the die): they land on
+    // the same die, one after the other, and the row's activations come from HBM once however the grid divides.
+    // The grid is padded to a multiple of 8 row blocks; the surplus blocks leave here.
+    const int col_groups = (g.N + ncols - 1) / ncols;
+    const int die = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int row_group = local / col_groups, col_group = local - row_group * col_groups;
+    const int row_block = row_group * 8 + die;
+    if (row_block * kRowsPerBlock >= g.M) return;
+    const int m = row_block * kRowsPerBlock + threadIdx.x;
     const int mc = min(m, g.M - 1);  // rows beyond the matrix are computed on the last row, never stored
-    const int n0 = blockIdx.y * ncols, n1 = min(n0 + ncols, g.N);
+    const int n0 = col_group * ncols, n1 = min(n0 + ncols, g.N);
 
     // ---- this lane's activation row: abits planes of Kw words, zero beyond Kw.  For a convolution the
     // row is the im2col row of the lane's output pixel: word k is channel word c of tap (kh, kw), zero where
@@ -263,8 +272,9 @@ template <int AB, int WB, int KW, bool BIPOLAR>
 dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
 {
     const int64_t bx = ((int64_t)g.M + kRowsPerBlock - 1) / kRowsPerBlock, by = (g.N + ncols - 1) / ncols;
-    if (bx > 0x7fffffffLL || by > 65535) return DLRT_ERR_SHAPE;
-    const dim3 grid((unsigned)bx, (unsigned)by), block(kRowsPerBlock);
+    const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies, see the kernel
+    if (blocks > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(kRowsPerBlock);
     if (conv) hipLaunchKernelGGL((contract_rows_kernel<AB, WB, KW, BIPOLAR, true>), grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
     else hipLaunchKernelGGL((contract_rows_kernel<AB, WB, KW, BIPOLAR, false>), grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
     return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
