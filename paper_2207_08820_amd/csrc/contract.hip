@@ -107,15 +107,17 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     int tileM, tileN;
     if (g.xcd_split) {
         // Consecutive blocks go to the chip's 8 dies (XCDs) in turn, each with an L2 of its own.  Block b is
-        // therefore given a tile of die (b mod 8)'s own 1/2 x 1/4 part of the tile grid, so that a die's L2
-        // fetches half of A's rows and a quarter of W's instead of all of one of them: 24 MiB instead of 36
-        // from HBM for the 8 MiB of operands of a 4096^3 A2W2 GEMM.  Any mapping is correct (it is a
-        // bijection); the launcher sets the flag only when the grid divides evenly.
-        const int tilesM = (g.M + BM - 1) / BM, subN = tilesN >> 2;
+        // therefore given a tile of die (b mod 8)'s own part of the tile grid, an r x c split of it with
+        // r * c = 8 (c = 2^(xcd_split - 1), chosen by the launcher): every row band of A is then fetched from
+        // HBM by c dies and every column band of W by r, instead of all of A by all eight.  4096^3 A2W2 with
+        // 2 x 4: 24 MiB instead of 36 for the 8 MiB of operands.  Any mapping is correct (it is a bijection);
+        // the launcher picks a split only among those that divide the grid evenly.
+        const int lc = g.xcd_split - 1;
+        const int tilesM = (g.M + BM - 1) / BM, subN = tilesN >> lc, subM = tilesM >> (3 - lc);
         const int die = blockIdx.x & 7, local = blockIdx.x >> 3;
         const int lm = local / subN, ln = local - lm * subN;
-        tileM = (die >> 2) * (tilesM >> 1) + lm;
-        tileN = (die & 3) * subN + ln;
+        tileM = (die >> lc) * subM + lm;
+        tileN = (die & ((1 << lc) - 1)) * subN + ln;
     } else {
         tileM = blockIdx.x / tilesN;
         tileN = blockIdx.x - tileM * tilesN;
@@ -449,8 +451,16 @@ dlrt_status launch_tile(const ContractArgs &g, const FusedOut &o, hipStream_t st
     constexpr int TN = LaneTile<WB>::value;
     const int64_t tilesM = (g.M + 16 * TM - 1) / (16 * TM), tilesN = (g.N + 16 * TN - 1) / (16 * TN);
     if (tilesM * tilesN > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    // split of the tile grid over the 8 dies: r x c with the least HBM fetch, c * (bytes of A) + r * (bytes of W)
     ContractArgs ga = g;
-    ga.xcd_split = tilesM % 2 == 0 && tilesN % 4 == 0;
+    ga.xcd_split = 0;
+    double best = 0;
+    for (int lc = 0; lc <= 3; ++lc) {
+        const int c = 1 << lc, r = 8 >> lc;
+        if (tilesM % r != 0 || tilesN % c != 0) continue;
+        const double fetch = (double)c * g.M * AB + (double)r * g.N * WB;  // per reduction word
+        if (!ga.xcd_split || fetch < best) { best = fetch; ga.xcd_split = lc + 1; }
+    }
     hipLaunchKernelGGL((contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>), dim3((unsigned)(tilesM * tilesN)),
                        dim3(kThreads), 0, stream, ga, o);
     return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;

@@ -26,7 +26,7 @@ struct ContractArgs {
     int a_msb_neg, w_msb_neg;
     int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
     int half_rows;      // block kernel: tiles of half the usual height (32 instead of 64 rows, 16 instead of 32)
-    int xcd_split;      // block kernel: block index -> tile through a 2 x 4 split of the tile grid over the 8 dies
+    int xcd_split;      // block kernel: 0, or 1 + log2(c) of the r x c split (r * c = 8) of the tile grid over the 8 dies
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
