@@ -66,8 +66,10 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     const ContractArgs g = pair.g[which];
     const FusedOut o = pair.o[which];
     const int steps_base = pair.steps_base[which], steps_rem = pair.steps_rem[which], tiles = pair.tiles[which];
-    const uint32_t magicTilesN = pair.magicTilesN[which];
-    asm volatile("" ::"s"(tiles), "s"(magicTilesN), "s"(g.A), "s"(g.W), "s"(g.M), "s"(g.N), "s"(g.Kw), "s"(g.a_msb_neg), "s"(g.w_msb_neg), "s"(g.H),
+    const uint32_t magicSubN = pair.magicSubN[which];
+    const int subN = pair.subN[which], subM = pair.subM[which], die_bits = pair.die_bits[which], lc = pair.lc[which];
+    asm volatile("" ::"s"(subN), "s"(subM), "s"(die_bits), "s"(lc));
+    asm volatile("" ::"s"(tiles), "s"(magicSubN), "s"(g.A), "s"(g.W), "s"(g.M), "s"(g.N), "s"(g.Kw), "s"(g.a_msb_neg), "s"(g.w_msb_neg), "s"(g.H),
                  "s"(g.Wd), "s"(g.Cw), "s"(g.KW), "s"(g.Ho), "s"(g.Wo), "s"(g.sh), "s"(g.sw), "s"(g.ph), "s"(g.pw),
                  "s"(g.magicCw), "s"(g.magicKW), "s"(g.magicHW), "s"(g.magicWo), "s"(o.acc), "s"(o.y), "s"(o.q),
                  "s"(o.packed), "s"(o.scale), "s"(o.bias), "s"(o.qbits), "s"(steps_base), "s"(steps_rem));
@@ -87,8 +89,14 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     uint4 *const la = lds + ks * (UA + UW);
     uint4 *const lw = la + UA;
     const int lx = lane % LX, ly = lane / LX;
-    const int tilesN = (g.N + 31) / 32;
-    const int tileM = checked_div(tile, tilesN, magicTilesN), tileN = tile - tileM * tilesN;
+    // tile index -> (tileM, tileN).  Consecutive blocks go to the chip's 8 dies in turn, each with an L2 of its
+    // own; where the tile grid divides, the low die_bits (3) bits of the index pick one of r x c parts of
+    // the grid (c = 2^lc, r * c = 8) and the rest a tile inside it, so that a die fetches 1/c of the weights
+    // and 1/r of the activations of the layer instead of all of both.  Without a split die_bits and lc are 0
+    // and subN is the whole width: the same arithmetic gives the row-major order.
+    const int die = tile & ((1 << die_bits) - 1), local = tile >> die_bits;
+    const int lm = checked_div(local, subN, magicSubN), ln = local - lm * subN;
+    const int tileM = (die >> lc) * subM + lm, tileN = (die & ((1 << lc) - 1)) * subN + ln;
     const int m0 = tileM * ROWS, n0 = tileN * 32;
 
     // ---- staging slots: lane + 64 t; four consecutive lanes fetch the 64 contiguous bytes of one
@@ -404,8 +412,22 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
             const int64_t t = (int64_t)((g[i].M + ROWS - 1) / ROWS) * ((g[i].N + 31) / 32);
             if (t > 0x7fffffffLL) return DLRT_ERR_SHAPE;
             pair.tiles[i] = (int)t;
-            const int64_t tn = (g[i].N + 31) / 32;  // tile index < t is divided by tn
-            pair.magicTilesN[i] = t * tn >= (1LL << 32) ? 1u : tn == 1 ? 0u : (uint32_t)(((1ULL << 32) + tn - 1) / tn);
+            // split of the tile grid over the 8 dies: r x c = 8 with the least fetch among those that divide it
+            const int64_t tm = (g[i].M + ROWS - 1) / ROWS, tn = (g[i].N + 31) / 32;
+            int lc = -1;
+            double best = 0;
+            for (int l = 0; l <= 3; ++l) {
+                const int c = 1 << l, r = 8 >> l;
+                if (tm % r != 0 || tn % c != 0) continue;
+                const double fetch = (double)c * g[i].M * AB + (double)r * g[i].N * WB;
+                if (lc < 0 || fetch < best) { best = fetch; lc = l; }
+            }
+            pair.die_bits[i] = lc < 0 ? 0 : 3;
+            pair.lc[i] = lc < 0 ? 0 : lc;
+            const int64_t sn = lc < 0 ? tn : tn >> lc;  // a local index < t is divided by sn
+            pair.subN[i] = (int)sn;
+            pair.subM[i] = lc < 0 ? 0 : (int)(tm >> (3 - lc));
+            pair.magicSubN[i] = t * sn >= (1LL << 32) ? 1u : sn == 1 ? 0u : (uint32_t)(((1ULL << 32) + sn - 1) / sn);
             if (t > tiles) tiles = t;
         }
         const size_t lds_bytes = (size_t)ksplit * units * 16;

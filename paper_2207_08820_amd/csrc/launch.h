@@ -48,7 +48,10 @@ struct WavePair {
     FusedOut o[2];
     int steps_base[2], steps_rem[2];  // 4-word steps per wave: base, and one more for the first `rem` waves
     int tiles[2];
-    uint32_t magicTilesN[2];  // for tile / ceil(N / 32); same convention as ContractArgs::magicHW
+    // tile index -> tile: the low die_bits bits pick one of r x c parts of the tile grid (c = 2^lc), the rest a
+    // tile inside it, row-major over subN columns (die_bits = lc = 0, subN = ceil(N / 32): plain row-major order)
+    int die_bits[2], lc[2], subN[2], subM[2];
+    uint32_t magicSubN[2];  // for (tile >> die_bits) / subN; same convention as ContractArgs::magicHW
 };
 
 // Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n); g / o point at `count` (1 or 2) problems.
