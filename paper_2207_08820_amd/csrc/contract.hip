@@ -47,6 +47,9 @@
 // The two waves that share a SIMD start together, take the same time and so run prologue, loop and epilogue
 // in lockstep; DLRT_PRIO_RAMP raises a wave's priority along its K loop to pull them apart.  Measured: no
 // change at any K (the pair falls back into step within a tile), so it is off.
+// Starting the blocks of the first round a third of a tile apart (each waits by its wave slot, so that the
+// blocks sharing a SIMD are out of step from the start) changed nothing either (+-0.7 % on 15 GEMMs): the fixed
+// cost per tile is not an artefact of the blocks running in step.
 // A half-width variant of the reduction's last step (2 instead of 4 words when the tail is that short, as
 // with the 18 words of a 3x3 conv over 64 channels) made everything slower, 4096^3 by 13 %: the second code
 // path in the unrolled step loop upsets the register allocation of the whole loop.
