@@ -19,7 +19,9 @@
  *     Element k of a row occupies bit (k % 32) of word (k / 32) of each plane; plane p holds bit p
  *     of the element's pattern (plane 0 = least significant).  Bits beyond K are zero.
  *     Packed buffers must be 16-byte aligned (DLRT_ERR_ALIGN otherwise).
- *   - Overflow is a precondition, not checked: K_total * (2^abits - 1) * 2^(wbits-1) < 2^31.
+ *   - Overflow is a precondition, not checked: K_total * max|a| * max|w| < 2^31, where the largest
+ *     magnitude of a b-bit operand is 2^b - 1 (unsigned), 2^(b-1) (two's complement) or 1 (bipolar),
+ *     and K_total is the reduction length (KH * KW * Ci for a convolution).
  */
 #ifndef DLRT_H
 #define DLRT_H
@@ -65,7 +67,9 @@ const char *dlrt_status_string(dlrt_status status);
  * Bitplane split (Section V) with the optional forward quantizer of Section IV in front.
  *   src    rows x K elements of type `st`, element (r, k) at src[r * ld + k]; ld >= K.
  *   scale  NULL, or for DLRT_SRC_F32 (required there): one float (scale_per_row == 0) or `rows`
- *          floats.  q = rint(min(max(x / s, lo), hi)), ties to even, [lo, hi] the range of `enc`.
+ *          floats, all positive.  q = rint(min(max(x / s, lo), hi)), ties to even, [lo, hi] the range of
+ *          `enc`.  DLRT_BIPOLAR has no zero level: there q is the sign of x / s with zero counted as +1
+ *          (bit = x / s >= 0), the quantizer of binary networks.
  *          Integer sources are taken as already quantized: the low `bits` bits of the two's
  *          complement pattern are packed (bipolar: bit = value > 0); `scale` is ignored.
  *   dst    [rows][bits][ceil(K/32)] words, fully written.
@@ -84,6 +88,15 @@ dlrt_status dlrt_pack_bitplanes(const void *src, dlrt_src st, int64_t rows, int6
 dlrt_status dlrt_pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci,
                                    int bits, dlrt_encoding enc, const float *scale, uint32_t *dst,
                                    void *stream);
+
+/*
+ * The same with Section IV's scale s taken per OUTPUT CHANNEL: scale holds Co floats and element
+ * (co, kh, kw, ci) is quantized with scale[co] (F32 source; ignored for integer sources, may then be NULL).
+ * Everything else as dlrt_pack_conv_weights.
+ */
+dlrt_status dlrt_pack_conv_weights_per_channel(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW,
+                                               int Ci, int bits, dlrt_encoding enc, const float *scale,
+                                               uint32_t *dst, void *stream);
 
 /*
  * Bit-serial GEMM (Section V, multi-bit equation applied to every (m, n) pair):

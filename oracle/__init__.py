@@ -45,11 +45,12 @@ def _load():
         lib.oracle_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64]
         lib.oracle_conv2d_i32.argtypes = [vp, vp, vp] + [i32] * 11
         lib.oracle_quantize.argtypes = [vp, vp, i32, i64, i64, ctypes.c_float, ctypes.c_float, vp]
+        lib.oracle_quantize_bipolar.argtypes = [vp, vp, i32, i64, i64, vp]
         lib.oracle_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32]
         lib.oracle_pack_bitplanes.argtypes = [vp, i64, i64, i32, i32, vp]
         lib.oracle_pack_conv_weights.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp]
         for name in ("oracle_set_threads", "oracle_gemm_i32", "oracle_conv2d_i32", "oracle_quantize",
-                     "oracle_epilogue_f32", "oracle_pack_bitplanes", "oracle_pack_conv_weights"):
+                     "oracle_quantize_bipolar", "oracle_epilogue_f32", "oracle_pack_bitplanes", "oracle_pack_conv_weights"):
             getattr(lib, name).restype = None
         _lib = lib
     return _lib
@@ -117,7 +118,8 @@ def value_range(bits: int, enc: int):
 
 
 def quantize(x, scale, bits: int, enc: int) -> np.ndarray:
-    """round(clip(x / s, lo, hi)), ties to even, fp32 (Section IV).  scale: scalar or one per row."""
+    """round(clip(x / s, lo, hi)), ties to even, fp32 (Section IV).  scale: scalar or one per row.
+    Bipolar (+1 / -1, no zero level): the sign of x / s, zero counted as +1."""
     x = np.ascontiguousarray(np.asarray(x, dtype=np.float32))
     x2 = x.reshape(-1, x.shape[-1])
     scale = np.ascontiguousarray(np.asarray(scale, dtype=np.float32).reshape(-1))
@@ -126,6 +128,9 @@ def quantize(x, scale, bits: int, enc: int) -> np.ndarray:
         raise ValueError("scale must have one value or one per row")
     lo, hi = value_range(bits, enc)
     q = np.empty(x2.shape, dtype=np.int8)
+    if enc == BIPOLAR:
+        _load().oracle_quantize_bipolar(_p(x2), _p(scale), per_row, x2.shape[0], x2.shape[1], _p(q))
+        return q.reshape(x.shape)
     _load().oracle_quantize(_p(x2), _p(scale), per_row, x2.shape[0], x2.shape[1], float(lo), float(hi), _p(q))
     return q.reshape(x.shape)
 

@@ -59,10 +59,10 @@ void oracle_gemm_i32(const int8_t *a, const int8_t *w, int32_t *c,
     }
 }
 
-/* Section V: "the convolution is performed using bitserial computation ... to
- * calculate the dot products" -> a direct convolution whose dot products are
- * the integer ones above.  x: NHWC, w: OHWI, y: NHWC int32.  Taps that fall
- * outside the image are skipped, which is zero padding. */
+/* Section V applies the bit-serial dot product to convolution: a direct
+ * convolution whose dot products are the integer ones above.  x: NHWC, w: OHWI,
+ * y: NHWC int32.  Taps that fall outside the image are skipped, which is zero
+ * padding. */
 void oracle_conv2d_i32(const int8_t *x, const int8_t *w, int32_t *y,
                        int N, int H, int W, int Ci, int Co, int KH, int KW,
                        int stride_h, int stride_w, int pad_h, int pad_w)
@@ -112,6 +112,20 @@ void oracle_quantize(const float *x, const float *scale, int per_row,
     }
 }
 
+/* Quantizer for bipolar (+1 / -1) one-bit weights.  Section IV with b = 1 gives
+ * the range {-1, 0}, which has no +1; the bipolar encoding has no 0.  Its
+ * quantizer is therefore read as the sign of t / s, zero counted as +1 (the
+ * usual convention of binary networks). */
+void oracle_quantize_bipolar(const float *x, const float *scale, int per_row,
+                             int64_t rows, int64_t K, int8_t *q)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        const float s = scale[per_row ? r : 0];
+        for (int64_t k = 0; k < K; ++k)
+            q[r * K + k] = (x[r * K + k] / s >= 0.0f) ? 1 : -1;
+    }
+}
+
 /* Section IV dequantisation t_hat = t_bar * s, taken per output channel, with an
  * optional bias, as one fused multiply-add on the exactly converted integer;
  * then the quantizer of the same section (scale 1, unsigned range) for the
@@ -132,8 +146,8 @@ void oracle_epilogue_f32(const int32_t *acc, const float *scale, const float *bi
     }
 }
 
-/* Section V "splitting the weights and activations into separate bitplanes":
- * the packed format the GPU packer must emit, written out bit by bit.
+/* Section V's bitplane split of weights and activations: the packed format the
+ * GPU packer must emit, written out bit by bit.
  * q: rows x K values.  enc 0 = unsigned, 1 = two's complement (plane p holds bit p
  * of the b-bit pattern), 2 = bipolar (bits == 1; +1 -> bit 1, -1 -> bit 0).
  * dst: [rows][bits][ceil(K/32)] words, element k -> bit (k % 32) of word k / 32,

@@ -54,6 +54,8 @@ def load():
     lib.dlrt_pack_bitplanes.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, i32, vp, vp]
     lib.dlrt_pack_conv_weights.restype = i32
     lib.dlrt_pack_conv_weights.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.dlrt_pack_conv_weights_per_channel.restype = i32
+    lib.dlrt_pack_conv_weights_per_channel.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.dlrt_bitserial_gemm.restype = i32
     lib.dlrt_bitserial_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, i32, i32, vp]
     lib.dlrt_bitserial_gemm_fused.restype = i32
@@ -87,6 +89,31 @@ def _ptr(t):
     return t.data_ptr()
 
 
+def _expect(t, dtype, numel: int, name: str):
+    """The C ABI sees pointers only; a buffer of the wrong type or size would become an out-of-bounds access
+    on the device, so every tensor is checked here against the elements the call reads or writes."""
+    if t is None:
+        return
+    dtypes = dtype if isinstance(dtype, tuple) else (dtype,)
+    if t.dtype not in dtypes:
+        raise ValueError(f"{name}: expected dtype {' or '.join(str(d) for d in dtypes)}, got {t.dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: the call touches {numel} elements, the tensor has {t.numel()}")
+
+
+def _cw(n: int) -> int:
+    return (n + 31) // 32
+
+
+def _expect_fused(M: int, N: int, qbits: int, scale, bias, out_acc, out_f32, out_q, out_packed):
+    _expect(scale, torch.float32, N, "scale")
+    _expect(bias, torch.float32, N, "bias")
+    _expect(out_acc, torch.int32, M * N, "out_acc")
+    _expect(out_f32, torch.float32, M * N, "out_f32")
+    _expect(out_q, torch.uint8, M * N, "out_q")
+    _expect(out_packed, torch.int32, M * qbits * _cw(N), "out_packed")
+
+
 def _check(code: int, where: str):
     if code != OK:
         raise DlrtError(code, where)
@@ -108,9 +135,13 @@ def dlrt_pack_bitplanes(src: torch.Tensor, bits: int, enc: int, scale: torch.Ten
     K = ld if K is None else K
     rows = src.numel() // ld
     Kw = (K + 31) // 32
+    if src.dtype not in _SRC_OF:
+        raise ValueError(f"src: expected uint8, int8 or float32, got {src.dtype}")
     if out is None:
         out = torch.empty((rows, bits, Kw), dtype=torch.int32, device=src.device)
     per_row = int(scale is not None and scale.numel() != 1)
+    _expect(scale, torch.float32, rows if per_row else 1, "scale")
+    _expect(out, torch.int32, rows * bits * Kw, "out")
     _check(lib.dlrt_pack_bitplanes(_ptr(src), _SRC_OF[src.dtype], rows, K, ld, bits, enc, _ptr(scale), per_row,
                                    _ptr(out), _stream()), "dlrt_pack_bitplanes")
     return out
@@ -121,10 +152,31 @@ def dlrt_pack_conv_weights(w_ohwi: torch.Tensor, bits: int, enc: int, scale: tor
     """w [Co, KH, KW, Ci] -> int32 words [Co, bits, KH*KW*ceil(Ci/32)]."""
     lib = load()
     Co, KH, KW, Ci = w_ohwi.shape
+    if w_ohwi.dtype not in _SRC_OF:
+        raise ValueError(f"w_ohwi: expected uint8, int8 or float32, got {w_ohwi.dtype}")
     if out is None:
         out = torch.empty((Co, bits, KH * KW * ((Ci + 31) // 32)), dtype=torch.int32, device=w_ohwi.device)
+    _expect(scale, torch.float32, 1, "scale")
+    _expect(out, torch.int32, Co * bits * KH * KW * _cw(Ci), "out")
     _check(lib.dlrt_pack_conv_weights(_ptr(w_ohwi), _SRC_OF[w_ohwi.dtype], Co, KH, KW, Ci, bits, enc, _ptr(scale),
                                       _ptr(out), _stream()), "dlrt_pack_conv_weights")
+    return out
+
+
+def dlrt_pack_conv_weights_per_channel(w_ohwi: torch.Tensor, bits: int, enc: int, scale: torch.Tensor | None = None,
+                                       out: torch.Tensor | None = None) -> torch.Tensor:
+    """As dlrt_pack_conv_weights with one quantizer scale per output channel (scale [Co], float32 source)."""
+    lib = load()
+    Co, KH, KW, Ci = w_ohwi.shape
+    if scale is not None:
+        _expect(scale, torch.float32, Co, "scale")
+    if w_ohwi.dtype not in _SRC_OF:
+        raise ValueError(f"w_ohwi: expected uint8, int8 or float32, got {w_ohwi.dtype}")
+    if out is None:
+        out = torch.empty((Co, bits, KH * KW * ((Ci + 31) // 32)), dtype=torch.int32, device=w_ohwi.device)
+    _expect(out, torch.int32, Co * bits * KH * KW * _cw(Ci), "out")
+    _check(lib.dlrt_pack_conv_weights_per_channel(_ptr(w_ohwi), _SRC_OF[w_ohwi.dtype], Co, KH, KW, Ci, bits, enc,
+                                                  _ptr(scale), _ptr(out), _stream()), "dlrt_pack_conv_weights_per_channel")
     return out
 
 
@@ -134,6 +186,9 @@ def dlrt_bitserial_gemm(A: torch.Tensor, W: torch.Tensor, M: int, N: int, K: int
     lib = load()
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _expect(A, torch.int32, M * abits * _cw(K), "A")
+    _expect(W, torch.int32, N * wbits * _cw(K), "W")
+    _expect(out, torch.int32, M * N, "out")
     _check(lib.dlrt_bitserial_gemm(_ptr(A), _ptr(W), _ptr(out), M, N, K, abits, wbits, enc_a, enc_w, _stream()),
            "dlrt_bitserial_gemm")
     return out
@@ -144,6 +199,9 @@ def dlrt_bitserial_gemm_fused(A: torch.Tensor, W: torch.Tensor, scale: torch.Ten
                               out_acc: torch.Tensor | None = None, out_f32: torch.Tensor | None = None,
                               out_q: torch.Tensor | None = None, out_packed: torch.Tensor | None = None):
     """One launch: GEMM -> scale/bias -> requant -> bitplanes.  Only the outputs whose buffers are passed are written."""
+    _expect(A, torch.int32, M * abits * _cw(K), "A")
+    _expect(W, torch.int32, N * wbits * _cw(K), "W")
+    _expect_fused(M, N, qbits, scale, bias, out_acc, out_f32, out_q, out_packed)
     _check(load().dlrt_bitserial_gemm_fused(_ptr(A), _ptr(W), _ptr(scale), _ptr(bias), M, N, K, abits, wbits, enc_a, enc_w,
                                             _ptr(out_acc), _ptr(out_f32), _ptr(out_q), _ptr(out_packed), qbits, _stream()),
            "dlrt_bitserial_gemm_fused")
@@ -160,6 +218,9 @@ def dlrt_bitserial_conv2d(X: torch.Tensor, Wp: torch.Tensor, N: int, H: int, W: 
     Wo = (W + 2 * pw - KW) // sw + 1
     if out is None:
         out = torch.empty((N, max(Ho, 0), max(Wo, 0), Co), dtype=torch.int32, device=X.device)
+    _expect(X, torch.int32, N * H * W * abits * _cw(Ci), "X")
+    _expect(Wp, torch.int32, Co * wbits * KH * KW * _cw(Ci), "Wp")
+    _expect(out, torch.int32, N * max(Ho, 0) * max(Wo, 0) * Co, "out")
     _check(lib.dlrt_bitserial_conv2d(_ptr(X), _ptr(Wp), _ptr(out), N, H, W, Ci, Co, KH, KW, sh, sw, ph, pw,
                                      abits, wbits, enc_a, enc_w, _stream()), "dlrt_bitserial_conv2d")
     return out
@@ -176,15 +237,24 @@ def dlrt_bitserial_conv2d_fused(X: torch.Tensor, Wp: torch.Tensor, scale: torch.
     lib = load()
     sh, sw = stride
     ph, pw = pad
+    Mo = N * max((H + 2 * ph - KH) // sh + 1, 0) * max((W + 2 * pw - KW) // sw + 1, 0)
+    _expect(X, torch.int32, N * H * W * abits * _cw(Ci), "X")
+    _expect(Wp, torch.int32, Co * wbits * KH * KW * _cw(Ci), "Wp")
+    _expect_fused(Mo, Co, qbits, scale, bias, out_acc, out_f32, out_q, out_packed)
     _check(lib.dlrt_bitserial_conv2d_fused(_ptr(X), _ptr(Wp), _ptr(scale), _ptr(bias), N, H, W, Ci, Co, KH, KW,
                                            sh, sw, ph, pw, abits, wbits, enc_a, enc_w, _ptr(out_acc), _ptr(out_f32),
                                            _ptr(out_q), _ptr(out_packed), qbits, tile_rows, ksplit, _stream()),
            "dlrt_bitserial_conv2d_fused")
 
 
-def conv_problem(X, Wp, scale, bias, N, H, W, Ci, Co, KH, KW, stride, pad, qbits=2, out_acc=None, out_f32=None,
-                 out_q=None, out_packed=None) -> ConvProblem:
-    """Fill a dlrt_conv_problem from tensors (None = NULL)."""
+def conv_problem(X, Wp, scale, bias, N, H, W, Ci, Co, KH, KW, stride, pad, abits, wbits, qbits=2, out_acc=None,
+                 out_f32=None, out_q=None, out_packed=None) -> ConvProblem:
+    """Fill a dlrt_conv_problem from tensors (None = NULL); abits / wbits are those the pair call will be
+    given, needed here to check the operand sizes."""
+    Mo = N * max((H + 2 * pad[0] - KH) // stride[0] + 1, 0) * max((W + 2 * pad[1] - KW) // stride[1] + 1, 0)
+    _expect(X, torch.int32, N * H * W * abits * _cw(Ci), "X")
+    _expect(Wp, torch.int32, Co * wbits * KH * KW * _cw(Ci), "Wp")
+    _expect_fused(Mo, Co, qbits, scale, bias, out_acc, out_f32, out_q, out_packed)
     return ConvProblem(_ptr(X), _ptr(Wp), _ptr(scale), _ptr(bias), N, H, W, Ci, Co, KH, KW, stride[0], stride[1], pad[0],
                        pad[1], _ptr(out_acc), _ptr(out_f32), _ptr(out_q), _ptr(out_packed), qbits)
 
@@ -212,6 +282,11 @@ def dlrt_unpacked_gemm_i8(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor | 
     N = W.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _expect(A, (torch.int8, torch.uint8), M * K, "A")
+    _expect(W, (torch.int8, torch.uint8), N * K, "W")
+    if W.shape[1] != K:
+        raise ValueError(f"W: reduction length {W.shape[1]} differs from A's {K}")
+    _expect(out, torch.int32, M * N, "out")
     _check(lib.dlrt_unpacked_gemm_i8(_ptr(A), _ptr(W), _ptr(out), M, N, K, _stream()), "dlrt_unpacked_gemm_i8")
     return out
 
@@ -227,6 +302,11 @@ def dlrt_epilogue_f32(acc: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor
         out_f32 = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
     if qbits is not None and out_q is None:
         out_q = torch.empty(acc.shape, dtype=torch.uint8, device=acc.device)
+    _expect(acc, torch.int32, rows * C, "acc")
+    _expect(scale, torch.float32, C, "scale")
+    _expect(bias, torch.float32, C, "bias")
+    _expect(out_f32, torch.float32, rows * C, "out_f32")
+    _expect(out_q, torch.uint8, rows * C, "out_q")
     _check(lib.dlrt_epilogue_f32(_ptr(acc), _ptr(scale), _ptr(bias), rows, C, _ptr(out_f32), _ptr(out_q),
                                  int(qbits or 0), _stream()), "dlrt_epilogue_f32")
     return out_f32, out_q

@@ -101,8 +101,10 @@ dlrt_status dlrt_pack_bitplanes(const void *src, dlrt_src st, int64_t rows, int6
     return dlrt::launch_pack(p, as_stream(stream));
 }
 
-dlrt_status dlrt_pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci, int bits,
-                                   dlrt_encoding enc, const float *scale, uint32_t *dst, void *stream)
+namespace {
+
+dlrt_status pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci, int bits,
+                              dlrt_encoding enc, const float *scale, int scale_per_channel, uint32_t *dst, void *stream)
 {
     if (dlrt_status s = check_pack(w_ohwi, st, bits, enc, scale, dst)) return s;
     if (Co <= 0 || KH <= 0 || KW <= 0 || Ci <= 0) return DLRT_ERR_SHAPE;
@@ -110,9 +112,24 @@ dlrt_status dlrt_pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int 
     if ((int64_t)Co * taps > 0x7fffffffLL * 32 / Cw) return DLRT_ERR_SHAPE;
     dlrt::PackArgs p{};
     p.src = w_ohwi; p.src_type = st; p.rows = (int64_t)Co * taps; p.K = Ci; p.ld = Ci; p.bits = bits; p.enc = enc;
-    p.scale = scale; p.scale_per_row = 0; p.dst = dst;
+    p.scale = scale; p.scale_per_row = scale_per_channel ? 2 : 0; p.dst = dst;
     p.taps = taps; p.outer_stride = bits * taps * Cw; p.plane_stride = taps * Cw; p.tap_stride = Cw;
     return dlrt::launch_pack(p, as_stream(stream));
+}
+
+}  // namespace
+
+dlrt_status dlrt_pack_conv_weights(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci, int bits,
+                                   dlrt_encoding enc, const float *scale, uint32_t *dst, void *stream)
+{
+    return pack_conv_weights(w_ohwi, st, Co, KH, KW, Ci, bits, enc, scale, 0, dst, stream);
+}
+
+dlrt_status dlrt_pack_conv_weights_per_channel(const void *w_ohwi, dlrt_src st, int Co, int KH, int KW, int Ci, int bits,
+                                               dlrt_encoding enc, const float *scale, uint32_t *dst, void *stream)
+{
+    if (st == DLRT_SRC_F32 && !scale) return DLRT_ERR_NULL;
+    return pack_conv_weights(w_ohwi, st, Co, KH, KW, Ci, bits, enc, scale, 1, dst, stream);
 }
 
 dlrt_status dlrt_bitserial_gemm(const uint32_t *A, const uint32_t *W, int32_t *C, int64_t M, int64_t N, int64_t K,

@@ -31,37 +31,9 @@
 #ifndef DLRT_ABITS
 #error "compile with -DDLRT_ABITS=1..4"
 #endif
-// Tuning knobs of the block kernel.  Measured at 4096^3, fraction of the VALU roofline for the pairs
-// (1,1) (2,2) (3,3) (4,4) (2,4), 20 back-to-back launches each:
-//   2 waves/SIMD, operands read one 16-byte step ahead (register double buffer): .78 .88 .92 .95 .93
-//   2 waves/SIMD, operands read at the top of each step (the default):           .80 .90 .96 .96 .93
-//   3 waves/SIMD (168 registers), no double buffer (spills at 2 x 2 bits):       .74 .85 .96 .94 .89
-//   3 waves/SIMD with the double buffer (spills everywhere):                     .52 .63 .85 .73 .69
-// With two waves per SIMD the other wave covers the LDS latency, and the smaller live range lets the
-// register allocator keep everything else in registers.
-// Also measured and dropped: persistent blocks (512 resident blocks walking the 4096 tiles with a fixed
-// stride, with and without fetching the next tile's first chunk during the current tile's last one):
-// .74 .82 .83 .87 .85 either way.  One block per tile lets the hardware hand tiles to whichever compute
-// unit frees up first, which is worth more than the saved set-up.  Half-height lane tiles (twice as many,
-// shorter blocks): .77 .86 .91 .95 .91, no better.
-// The two waves that share a SIMD start together, take the same time and so run prologue, loop and epilogue
-// in lockstep; DLRT_PRIO_RAMP raises a wave's priority along its K loop to pull them apart.  Measured: no
-// change at any K (the pair falls back into step within a tile), so it is off.
-// Starting the blocks of the first round a third of a tile apart (each waits by its wave slot, so that the
-// blocks sharing a SIMD are out of step from the start) changed nothing either (+-0.7 % on 15 GEMMs): the fixed
-// cost per tile is not an artefact of the blocks running in step.
-// A half-width variant of the reduction's last step (2 instead of 4 words when the tail is that short, as
-// with the 18 words of a 3x3 conv over 64 channels) made everything slower, 4096^3 by 13 %: the second code
-// path in the unrolled step loop upsets the register allocation of the whole loop.
-#ifndef DLRT_WAVES_PER_EU
+// Two waves per SIMD: the other wave covers the LDS latency of a step, and the short live ranges let the
+// register allocator keep everything else in registers (three waves per SIMD measured slower or spilled).
 #define DLRT_WAVES_PER_EU 2
-#endif
-#ifndef DLRT_PRIO_RAMP
-#define DLRT_PRIO_RAMP 0
-#endif
-#ifndef DLRT_REG_DOUBLE_BUFFER
-#define DLRT_REG_DOUBLE_BUFFER 0
-#endif
 
 namespace {
 
@@ -260,21 +232,14 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
 
     for (int chunk = 0; chunk < nchunks; ++chunk) {
         const int buf = chunk & 1;
-#if DLRT_PRIO_RAMP
-        // the wave that is further along its tile gets the issue slots first
-        if (4 * chunk >= 3 * nchunks) __builtin_amdgcn_s_setprio(3);
-        else if (2 * chunk >= nchunks) __builtin_amdgcn_s_setprio(2);
-        else if (4 * chunk >= nchunks) __builtin_amdgcn_s_setprio(1);
-#endif
         if (chunk + 1 < nchunks) fetch(chunk + 1);
 
         const uint4 *la = ldsA + buf * kTileA + ty;
         const uint4 *lw = ldsW + buf * kTileW + tx;
-        // Four 16-byte steps per chunk.  The scheduling barrier after each step keeps the compiler
-        // from hoisting every LDS read of the chunk to the top, which would need four times the
-        // operand registers (and spills).  Optionally the reads of step k4 + 1 are issued before
-        // the AND/BCNT block of step k4 (register double buffer).
-        uint4 av[2][TM][AB], wv[2][TN][WB];
+        // Four 16-byte steps per chunk, each reading its operands at its top.  The scheduling barrier
+        // after each step keeps the compiler from hoisting every LDS read of the chunk to the top,
+        // which would need four times the operand registers (and spills).
+        uint4 av[1][TM][AB], wv[1][TN][WB];
         auto lds_load = [&](int b, int k4) {
 #pragma unroll
             for (int r = 0; r < TM; ++r)
@@ -306,15 +271,6 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
                     }
             }
         };
-#if DLRT_REG_DOUBLE_BUFFER
-        lds_load(0, 0);
-#pragma unroll
-        for (int k4 = 0; k4 < kK4; ++k4) {
-            if (k4 + 1 < kK4) lds_load((k4 + 1) & 1, k4 + 1);
-            mac(k4 & 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#else
         const int nsteps = chunk + 1 < nchunks ? kK4 : last_steps;  // block-uniform
 #pragma unroll
         for (int k4 = 0; k4 < kK4; ++k4) {
@@ -324,7 +280,6 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-#endif
 
         if (chunk + 1 < nchunks) commit(buf ^ 1);
         __syncthreads();
@@ -464,9 +419,8 @@ dlrt_status launch_tile(const ContractArgs &g, const FusedOut &o, hipStream_t st
         const double fetch = (double)c * g.M * AB + (double)r * g.N * WB;  // per reduction word
         if (!ga.xcd_split || fetch < best) { best = fetch; ga.xcd_split = lc + 1; }
     }
-    hipLaunchKernelGGL((contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>), dim3((unsigned)(tilesM * tilesN)),
-                       dim3(kThreads), 0, stream, ga, o);
-    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+    return dlrt::enqueue(contract_kernel<AB, WB, TM, TN, VEC, BIPOLAR, CONV>, dim3((unsigned)(tilesM * tilesN)),
+                         dim3(kThreads), 0, stream, ga, o);
 }
 
 // Two tile heights per activation width: TM rows per lane (64-row tiles for 1 and 2 bits, 32-row tiles for 3 and

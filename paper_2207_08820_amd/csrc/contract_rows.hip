@@ -275,9 +275,8 @@ dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool c
     const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies, see the kernel
     if (blocks > 0x7fffffffLL) return DLRT_ERR_SHAPE;
     const dim3 grid((unsigned)blocks), block(kRowsPerBlock);
-    if (conv) hipLaunchKernelGGL((contract_rows_kernel<AB, WB, KW, BIPOLAR, true>), grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
-    else hipLaunchKernelGGL((contract_rows_kernel<AB, WB, KW, BIPOLAR, false>), grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
-    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+    if (conv) return dlrt::enqueue(contract_rows_kernel<AB, WB, KW, BIPOLAR, true>, grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
+    return dlrt::enqueue(contract_rows_kernel<AB, WB, KW, BIPOLAR, false>, grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
 }
 
 template <int AB, int WB, bool BIPOLAR>

@@ -431,9 +431,8 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
             if (t > tiles) tiles = t;
         }
         const size_t lds_bytes = (size_t)ksplit * units * 16;
-        hipLaunchKernelGGL((contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>), dim3((unsigned)tiles, (unsigned)count),
-                           dim3(64 * ksplit), lds_bytes, stream, pair, ksplit);
-        return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+        return dlrt::enqueue(contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>, dim3((unsigned)tiles, (unsigned)count),
+                             dim3(64 * ksplit), lds_bytes, stream, pair, ksplit);
     }
 }
 

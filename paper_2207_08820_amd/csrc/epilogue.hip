@@ -69,14 +69,12 @@ dlrt_status launch_epilogue(const int32_t *acc, const float *scale, const float 
     if (blocks > 256 * 32) blocks = 256 * 32;
     if (blocks < 1) blocks = 1;
     if (vec)
-        hipLaunchKernelGGL(epilogue_vec4, dim3((unsigned)blocks), dim3(kThreads), 0, stream,
-                           reinterpret_cast<const int4 *>(acc), reinterpret_cast<const float4 *>(scale),
-                           reinterpret_cast<const float4 *>(bias), work, C / 4, reinterpret_cast<float4 *>(out_f32),
-                           reinterpret_cast<uint32_t *>(out_q), qmax);
-    else
-        hipLaunchKernelGGL(epilogue_scalar, dim3((unsigned)blocks), dim3(kThreads), 0, stream, acc, scale, bias, n, C,
-                           out_f32, out_q, qmax);
-    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+        return enqueue(epilogue_vec4, dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                       reinterpret_cast<const int4 *>(acc), reinterpret_cast<const float4 *>(scale),
+                       reinterpret_cast<const float4 *>(bias), work, C / 4, reinterpret_cast<float4 *>(out_f32),
+                       reinterpret_cast<uint32_t *>(out_q), qmax);
+    return enqueue(epilogue_scalar, dim3((unsigned)blocks), dim3(kThreads), 0, stream, acc, scale, bias, n, C, out_f32,
+                   out_q, qmax);
 }
 
 }  // namespace dlrt

@@ -8,6 +8,20 @@
 
 namespace dlrt {
 
+template <typename T> struct NonDeduced { using type = T; };
+
+// Launches `kernel` and reports the status of THIS launch: hipLaunchKernel returns its own result, whereas
+// hipGetLastError() after a <<<>>> launch would also pick up (and wrongly blame this call for) an error that an
+// earlier, unrelated call of the process left behind.
+template <typename... P>
+dlrt_status enqueue(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                    typename NonDeduced<P>::type... args)
+{
+    void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds_bytes, stream);
+    return e == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+}
+
 // Optional outputs of the fused epilogue of both contraction kernels; any pointer may be null.
 struct FusedOut {
     int32_t *acc;      // [M][N] accumulators
@@ -102,7 +116,7 @@ struct PackArgs {
     int64_t rows, K, ld;
     int bits, enc;         // dlrt_encoding
     const float *scale;
-    int scale_per_row;
+    int scale_per_row;     // 0: one value; 1: one per row; 2: one per outer index (group of `taps` rows)
     uint32_t *dst;
     // destination addressing, in words
     int64_t taps;          // rows are grouped as [outer][taps]; 1 for plain tensors

@@ -73,7 +73,8 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const dlrt::PackArgs p, 
     uint32_t x[8];
     if (SRC == DLRT_SRC_F32) {
         const float *s = static_cast<const float *>(p.src) + r * p.ld + k0;
-        const float sc = p.scale[p.scale_per_row ? r : 0];
+        // one scale for the tensor, one per row, or one per group of `taps` rows (an output channel's taps)
+        const float sc = p.scale[p.scale_per_row == 0 ? 0 : p.scale_per_row == 1 ? r : r / p.taps];
 #pragma unroll
         for (int d = 0; d < 8; ++d) {
             float v[4] = {0.f, 0.f, 0.f, 0.f};
@@ -88,9 +89,11 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const dlrt::PackArgs p, 
             uint32_t w = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                // Section IV: round(clip(t / s, lo, hi)); IEEE division, ties to even
-                const int qi = (int)rintf(fminf(fmaxf(v[e] / sc, q.lo), q.hi));
-                const uint32_t pat = q.bipolar ? (qi > 0 ? 1u : 0u) : ((uint32_t)qi & 0xffu);
+                // Section IV: round(clip(t / s, lo, hi)); IEEE division, ties to even.  Bipolar has no zero
+                // level, so its quantizer is the sign of t / s with zero counted as +1.
+                const float ts = v[e] / sc;
+                const int qi = (int)rintf(fminf(fmaxf(ts, q.lo), q.hi));
+                const uint32_t pat = q.bipolar ? (ts >= 0.0f ? 1u : 0u) : ((uint32_t)qi & 0xffu);
                 w |= (4 * d + e < valid ? pat : 0u) << (8 * e);
             }
             x[d] = w;
@@ -130,13 +133,12 @@ dlrt_status launch_bits(const dlrt::PackArgs &p, const Quant &q, int64_t Kw, int
                         unsigned blocks, hipStream_t stream)
 {
     switch (p.bits) {
-    case 1: hipLaunchKernelGGL((pack_kernel<SRC, 1>), dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned); break;
-    case 2: hipLaunchKernelGGL((pack_kernel<SRC, 2>), dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned); break;
-    case 3: hipLaunchKernelGGL((pack_kernel<SRC, 3>), dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned); break;
-    case 4: hipLaunchKernelGGL((pack_kernel<SRC, 4>), dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned); break;
-    default: return DLRT_ERR_BITS;
+    case 1: return dlrt::enqueue(pack_kernel<SRC, 1>, dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned);
+    case 2: return dlrt::enqueue(pack_kernel<SRC, 2>, dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned);
+    case 3: return dlrt::enqueue(pack_kernel<SRC, 3>, dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned);
+    case 4: return dlrt::enqueue(pack_kernel<SRC, 4>, dim3(blocks), dim3(kThreads), 0, stream, p, q, Kw, total, aligned);
     }
-    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+    return DLRT_ERR_BITS;
 }
 
 }  // namespace

@@ -64,7 +64,9 @@ __global__ __launch_bounds__(kThreads) void gemm_i8_mfma_kernel(const int8_t *A,
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const bool ok = k0 + unitk[t] < K;  // K is a multiple of 16: a unit is inside or outside as a whole
-            const int kk = ok ? k0 : 0;
+            // a unit outside the reduction reads the first 16 bytes of its own row instead (always inside the
+            // buffer, since K >= 16) and is discarded; srcA / srcW already point at this thread's unit
+            const int kk = ok ? k0 : -unitk[t];
             const uint4 a = *reinterpret_cast<const uint4 *>(srcA[t] + kk);
             const uint4 w = *reinterpret_cast<const uint4 *>(srcW[t] + kk);
             stA[t] = ok ? a : make_uint4(0u, 0u, 0u, 0u);
@@ -137,8 +139,7 @@ dlrt_status launch_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C
 {
     const int64_t tiles = (int64_t)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     if (tiles > 0x7fffffffLL) return DLRT_ERR_SHAPE;
-    hipLaunchKernelGGL(gemm_i8_mfma_kernel, dim3((unsigned)tiles), dim3(kThreads), 0, stream, A, W, C, M, N, K);
-    return hipGetLastError() == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+    return enqueue(gemm_i8_mfma_kernel, dim3((unsigned)tiles), dim3(kThreads), 0, stream, A, W, C, M, N, K);
 }
 
 }  // namespace dlrt

@@ -135,7 +135,7 @@ class ConvStack:
         pl = self.layers[i]
         L = pl.spec
         return binding.conv_problem(self.layer_input(i), pl.wp, pl.scale, pl.bias, self.batch, L.H, L.W, L.Ci, L.Co, L.k, L.k,
-                                    (L.stride, L.stride), (L.pad, L.pad), qbits=self.qbits[i],
+                                    (L.stride, L.stride), (L.pad, L.pad), self.abits[i], self.wbits[i], qbits=self.qbits[i],
                                     out_acc=pl.acc if self.keep else None, out_q=pl.q if self.keep else None,
                                     out_packed=pl.out_packed)
 

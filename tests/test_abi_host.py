@@ -44,7 +44,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_conv2d_fused_pair", "dlrt_bitserial_gemm", "dlrt_bitserial_gemm_fused", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
-                     "dlrt_pack_conv_weights", "dlrt_packed_words", "dlrt_query_plan", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
+                     "dlrt_pack_conv_weights", "dlrt_pack_conv_weights_per_channel", "dlrt_packed_words", "dlrt_query_plan", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -130,6 +130,11 @@ def test_pack_and_epilogue_reject_bad_arguments_before_launch(lib):
     w = lib.dlrt_pack_conv_weights
     assert w(FAKE, 1, 0, 3, 3, 8, 2, TWOS, NULL, FAKE, NULL) == ERR_SHAPE
     assert w(FAKE, 1, 4, 3, 3, 8, 1, 5, NULL, FAKE, NULL) == ERR_ENCODING
+    lib.dlrt_pack_conv_weights_per_channel.argtypes = lib.dlrt_pack_conv_weights.argtypes
+    wc = lib.dlrt_pack_conv_weights_per_channel
+    assert wc(FAKE, 2, 4, 3, 3, 8, 2, TWOS, NULL, FAKE, NULL) == ERR_NULL  # float source without scales
+    assert wc(FAKE, 1, 4, 3, 0, 8, 2, TWOS, NULL, FAKE, NULL) == ERR_SHAPE
+    assert wc(FAKE, 1, 4, 3, 3, 8, 2, BIPOLAR, NULL, FAKE, NULL) == ERR_ENCODING
     e = lib.dlrt_epilogue_f32
     assert e(FAKE, FAKE, NULL, 4, 4, NULL, NULL, 2, NULL) == ERR_NULL  # no output at all
     assert e(FAKE, NULL, NULL, 4, 4, FAKE, NULL, 2, NULL) == ERR_NULL
@@ -217,3 +222,52 @@ def test_binding_exposes_the_same_names():
     for n in declared_functions():
         if n != "dlrt_status_string":
             assert callable(getattr(binding, n))
+
+
+def test_binding_rejects_wrong_sized_or_typed_tensors_before_calling_the_library():
+    """The ctypes layer knows the tensors' sizes, the C ABI does not: a buffer that is too small or of the
+    wrong type must be refused on the host (on CPU tensors the size check comes before the device check)."""
+    import torch
+    from paper_2207_08820_amd import binding
+
+    i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32)
+    f32 = lambda *shape: torch.zeros(shape, dtype=torch.float32)
+    A, W = i32(8, 2, 2), i32(4, 2, 2)   # M = 8, N = 4, K = 64, two planes each
+    with pytest.raises(ValueError, match="out"):
+        binding.dlrt_bitserial_gemm(A, W, 8, 4, 64, 2, 2, UNSIGNED, TWOS, out=i32(8, 3))
+    with pytest.raises(ValueError, match="A"):
+        binding.dlrt_bitserial_gemm(A, W, 8, 4, 64, 4, 2, UNSIGNED, TWOS, out=i32(8, 4))      # A packed for 2 bits
+    with pytest.raises(ValueError, match="W"):
+        binding.dlrt_bitserial_gemm(A, W.to(torch.int64), 8, 4, 64, 2, 2, UNSIGNED, TWOS, out=i32(8, 4))
+    with pytest.raises(ValueError, match="out_packed"):
+        binding.dlrt_bitserial_gemm_fused(A, W, f32(4), None, 8, 4, 64, 2, 2, UNSIGNED, TWOS, qbits=4, out_packed=i32(8, 2, 1))
+    with pytest.raises(ValueError, match="scale"):
+        binding.dlrt_bitserial_gemm_fused(A, W, f32(3), None, 8, 4, 64, 2, 2, UNSIGNED, TWOS, out_f32=f32(8, 4))
+    with pytest.raises(ValueError, match="out_q"):
+        binding.dlrt_bitserial_gemm_fused(A, W, f32(4), None, 8, 4, 64, 2, 2, UNSIGNED, TWOS, out_q=i32(8, 4))
+    X, Wp = i32(1 * 6 * 6, 2, 1), i32(16, 2, 9)   # 6 x 6 x 32 image, 16 filters of 3 x 3 x 32
+    geom = (1, 6, 6, 32, 16, 3, 3, (1, 1), (1, 1))
+    with pytest.raises(ValueError, match="out"):
+        binding.dlrt_bitserial_conv2d(X, Wp, *geom, 2, 2, UNSIGNED, TWOS, out=i32(1, 6, 6, 8))
+    with pytest.raises(ValueError, match="Wp"):
+        binding.dlrt_bitserial_conv2d(X, i32(16, 2, 8), *geom, 2, 2, UNSIGNED, TWOS, out=i32(1, 6, 6, 16))
+    with pytest.raises(ValueError, match="out_packed"):
+        binding.dlrt_bitserial_conv2d_fused(X, Wp, f32(16), f32(16), *geom, 2, 2, UNSIGNED, TWOS, qbits=2, out_packed=i32(35, 2, 1))
+    with pytest.raises(ValueError, match="bias"):
+        binding.dlrt_bitserial_conv2d_fused(X, Wp, f32(16), f32(15), *geom, 2, 2, UNSIGNED, TWOS, qbits=2, out_packed=i32(36, 2, 1))
+    with pytest.raises(ValueError, match="X"):
+        binding.conv_problem(i32(35, 2, 1), Wp, f32(16), None, *geom, 2, 2, out_packed=i32(36, 2, 1))
+    with pytest.raises(ValueError, match="out"):
+        binding.dlrt_pack_bitplanes(torch.zeros((4, 70), dtype=torch.uint8), 2, UNSIGNED, out=i32(4, 2, 2))  # needs 3 words
+    with pytest.raises(ValueError, match="scale"):
+        binding.dlrt_pack_bitplanes(f32(4, 64), 2, TWOS, scale=f32(3), out=i32(4, 2, 2))
+    with pytest.raises(ValueError, match="src"):
+        binding.dlrt_pack_bitplanes(torch.zeros((4, 64), dtype=torch.int16), 2, UNSIGNED)
+    with pytest.raises(ValueError, match="scale"):
+        binding.dlrt_pack_conv_weights_per_channel(f32(16, 3, 3, 32), 2, TWOS, scale=f32(15))
+    with pytest.raises(ValueError, match="out"):
+        binding.dlrt_unpacked_gemm_i8(torch.zeros((4, 32), dtype=torch.int8), torch.zeros((6, 32), dtype=torch.int8), out=i32(4, 5))
+    with pytest.raises(ValueError, match="scale"):
+        binding.dlrt_epilogue_f32(i32(5, 8), f32(7))
+    with pytest.raises(ValueError, match="out_q"):
+        binding.dlrt_epilogue_f32(i32(5, 8), f32(8), want_f32=False, qbits=2, out_q=torch.zeros((5, 7), dtype=torch.uint8))

@@ -91,11 +91,28 @@ def test_pack_float_source_quantizes_like_the_oracle(dlrt, oracle, bits, enc):
     for scale in (np.array([0.37], np.float32), r.uniform(0.1, 1.0, rows).astype(np.float32)):
         if scale.size == 1:
             x[0, :8] *= scale[0]
-        q = oracle.quantize(x, scale, bits, enc)
         if enc == BIPOLAR:
-            q = np.where(q > 0, 1, -1).astype(np.int8)
+            x[1, :4] = [0.0, -0.0, 0.2 * scale[0], -0.2 * scale[0]]  # no zero level: the sign decides, zero is +1
+        q = oracle.quantize(x, scale, bits, enc)
         got = dlrt.dlrt_pack_bitplanes(dev(x), bits, enc, scale=dev(scale))
         assert np.array_equal(words(got), oracle.pack_bitplanes(q, bits, enc))
+
+
+@pytest.mark.parametrize("Co,k,Ci", [(3, 3, 40), (16, 1, 32), (5, 5, 7), (7, 3, 100), (8, 1, 256)])
+def test_pack_conv_weights_float_source_quantizes_like_the_oracle(dlrt, oracle, Co, k, Ci):
+    """Section IV's quantizer in front of the conv-weight packer: ragged channel counts (a tap's last word is
+    partly padding), ties, saturation at both ends, every encoding, one scale for the tensor."""
+    r = rng(4100 + Co * 7 + Ci)
+    for bits, enc in [(2, TWOS), (1, BIPOLAR), (4, TWOS), (3, UNSIGNED), (1, TWOS)]:
+        s = np.float32(r.uniform(0.05, 0.9))
+        x = r.normal(0, 2.0 * s, size=(Co, k, k, Ci)).astype(np.float32)
+        flat = x.reshape(-1)
+        flat[:10] = np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 1e9, -1e9, 0.0, -0.0], np.float32) * s
+        flat[-1] = np.float32(-1e9)  # the last element of the last tap saturates too
+        q = oracle.quantize(x.reshape(Co * k * k, Ci), np.array([s], np.float32), bits, enc).reshape(x.shape)
+        got = dlrt.dlrt_pack_conv_weights(dev(x), bits, enc, scale=dev(np.array([s], np.float32)))
+        assert got.shape == (Co, bits, k * k * ((Ci + 31) // 32))
+        assert np.array_equal(words(got), oracle.pack_conv_weights(q, bits, enc)), (bits, enc)
 
 
 @pytest.mark.parametrize("Co,k,Ci", [(3, 3, 40), (64, 3, 64), (16, 1, 32), (5, 5, 7), (8, 1, 256)])
@@ -527,7 +544,7 @@ def test_conv_fused_pair_two_problems_in_one_launch(dlrt, oracle):
             packed = torch.full((Mo, 2, (Co + 31) // 32), -1, dtype=torch.int32, device=DEV)
             sc, bs = dev(scale), dev(bias)
             probs.append(dlrt.conv_problem(X, Wp, sc, bs, xs[0], xs[1], xs[2], xs[3], Co, ws[1], ws[2], (st, st), (pd, pd),
-                                           qbits=2, out_acc=acc, out_f32=y, out_packed=packed))
+                                           abits, wbits, qbits=2, out_acc=acc, out_f32=y, out_packed=packed))
             refs.append((ref, y_ref, oracle.pack_bitplanes(q_ref.reshape(Mo, Co).astype(np.int8), 2, UNSIGNED)))
             keep.append((X, Wp, sc, bs, acc, y, packed))
         dlrt.dlrt_bitserial_conv2d_fused_pair(probs[0], probs[1], abits, wbits, UNSIGNED, ew)

@@ -45,9 +45,12 @@ MUTANTS = [
     ("epilogue_bias_dropped", "bias ? bias[c] : 0.0f", "0.0f"),
     ("epilogue_scale_indexed_by_row", "scale[c], bias", "scale[r % C], bias"),
     ("quantize_truncates", "(int8_t)nearbyintf(v)", "(int8_t)v"),
-    ("quantize_multiplies_by_scale", "x[r * K + k] / s", "x[r * K + k] * s"),
+    ("quantize_multiplies_by_scale", "float v = x[r * K + k] / s", "float v = x[r * K + k] * s"),
     ("quantize_no_upper_clip", "fminf(fmaxf(v, lo), hi)", "fmaxf(v, lo)"),
-    ("quantize_scale_of_row_0", "scale[per_row ? r : 0]", "scale[0]"),
+    ("quantize_scale_of_row_0", "scale[per_row ? r : 0];\n        for (int64_t k = 0; k < K; ++k) {", "scale[0];\n        for (int64_t k = 0; k < K; ++k) {"),
+    ("quantize_bipolar_zero_is_minus_one", "/ s >= 0.0f) ? 1 : -1", "/ s > 0.0f) ? 1 : -1"),
+    ("quantize_bipolar_sign_flipped", "/ s >= 0.0f) ? 1 : -1", "/ s >= 0.0f) ? -1 : 1"),
+    ("quantize_bipolar_rounds_small_values_to_minus_one", "/ s >= 0.0f) ? 1 : -1", "/ s > 0.5f) ? 1 : -1"),
     ("pack_msb_first", "|= 1u << (k % 32);", "|= 1u << (31 - k % 32);"),
     ("pack_bipolar_inverted", PACK_PATTERN.format(one=1, zero=0), PACK_PATTERN.format(one=0, zero=1)),
     ("pack_planes_reversed", "dst[(r * bits + p) * Kw + k / 32]", "dst[(r * bits + (bits - 1 - p)) * Kw + k / 32]"),

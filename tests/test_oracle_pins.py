@@ -342,6 +342,25 @@ def test_quantizer_ranges_grid_points_saturation_and_error_bound(oracle):
     assert oracle.quantize(xr, np.array([1.0, 0.5], np.float32), 4, UNSIGNED).tolist() == [[1, 2], [2, 4]]
 
 
+def test_bipolar_quantizer_is_the_sign_with_zero_counted_as_plus_one(oracle):
+    """Bipolar weights have no zero level: the quantizer is the sign of x / s (binary-network convention,
+    sign(0) = +1).  Pinned by what a sign is: only +-1 comes out, q * x is never negative, |q * x| = |x|,
+    a positive scale changes nothing, zero (of either sign) gives +1, and per-row scales are per row."""
+    r = rng(52)
+    x = r.normal(0, 1.0, size=(6, 97)).astype(np.float32)
+    x[0, :4] = [0.0, -0.0, 0.2, -0.2]  # below half a step either side: still +-1, never 0
+    for s in (np.float32(0.37), np.float32(5.0), r.uniform(0.1, 2.0, 6).astype(np.float32)):
+        q = oracle.quantize(x, s, 1, BIPOLAR)
+        assert q.dtype == np.int8 and set(np.unique(q).tolist()) == {-1, 1}
+        assert np.all(q.astype(np.float64) * x >= 0)
+        assert np.array_equal(np.abs(q.astype(np.float64) * x), np.abs(x.astype(np.float64)))
+        assert q[0, :4].tolist() == [1, 1, 1, -1]
+        assert np.array_equal(q, np.where(np.signbit(x) & (x != 0), -1, 1))
+    # the bit the packer emits for it: +1 -> 1, -1 -> 0
+    words = oracle.pack_bitplanes(oracle.quantize(np.array([[3.0, -3.0, 0.0, -1e-3]], np.float32), 1.0, 1, BIPOLAR), 1, BIPOLAR)
+    assert words.tolist() == [[[0b0101]]]
+
+
 # ---- workload tables (host logic) -----------------------------------------------------------------
 def test_workload_tables_match_the_stated_shapes():
     r18 = inputs.resnet18_stack()
