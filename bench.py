@@ -1,6 +1,6 @@
 """Benchmark of the bit-serial hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-sweep] [--no-probes]
 
 A step is one pass of the whole path over one batch of synthetic input that is already resident
 in HBM: bitplane-pack the uint8 activations and the int8 weights, bit-serial GEMM accumulating in int32, and
@@ -20,11 +20,33 @@ import numpy as np
 
 # plain 32-bit VALU rate of the chip: 256 compute units x 64 lanes per clock x 2.4 GHz
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
-# HBM bytes per launch of the 4096^3 A2W2 GEMM kernel, from the committed rocprofv3 --pmc runs
-# (profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md): FETCH_SIZE 12616 KiB x 2.000 (calibration
-# against a plain 256 MiB copy) + WRITE_SIZE 65536 KiB.  Counters cannot be read from inside this
-# script, so the figure is only reported for the exact workload it was measured on.
-GEMM_4096_A2W2_TRAFFIC_BYTES = int((12616 * 2.0 + 65536) * 1024)
+# HBM bytes per launch of the 4096^3 A2W2 GEMM kernel come from the committed rocprofv3 --pmc summary
+# (counters cannot be read from inside this script): its FETCH_SIZE / WRITE_SIZE table, KiB per dispatch,
+# each scaled by what the same counter reads for a plain copy of known size in the same file.
+TRAFFIC_SOURCE = "profiles/contract_kernel_gemm_4096x4096x4096_a2w2.md"
+
+
+def traffic_from_profile():
+    """(bytes per launch, description) of the 4096^3 A2W2 GEMM kernel, parsed from the committed counter
+    summary; (None, reason) if the file or its two table rows cannot be read."""
+    import os
+    import re
+
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), TRAFFIC_SOURCE)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, f"{TRAFFIC_SOURCE} not found"
+    num = r"\|\s*([0-9.]+)[^|]*"
+    cal = re.search(r"plain copy of (\d+) KiB[^|]*" + num + num + r"\|", text)
+    row = re.search(r"contract_kernel GEMM 4096\^3 A2W2\s*" + num + num + r"\|", text)
+    if not cal or not row:
+        return None, f"no FETCH_SIZE / WRITE_SIZE rows in {TRAFFIC_SOURCE}"
+    known = float(cal.group(1))
+    fetch_factor, write_factor = known / float(cal.group(2)), known / float(cal.group(3))
+    nbytes = int((float(row.group(1)) * fetch_factor + float(row.group(2)) * write_factor) * 1024)
+    return nbytes, (f"{TRAFFIC_SOURCE}: FETCH_SIZE {row.group(1)} KiB x {fetch_factor:.3f} + WRITE_SIZE {row.group(2)} KiB x "
+                    f"{write_factor:.3f} (factors from the plain {int(known)} KiB copy in the same file)")
 
 
 def log(*a):
@@ -63,6 +85,56 @@ def time_graph(fn, reps=20, replays=5):
     graph.replay()
     torch.cuda.synchronize()
     return time_events(graph.replay, replays) / reps
+
+
+def measure_denominators(dev):
+    """The rates the kernels are judged against, measured on this chip with the probes of csrc/probe.hip:
+    the AND + accumulating-popcount lane-op rate at 8 and at 2 waves per SIMD (8 saturates the issue slots; the
+    block kernel runs 2 to 3), the shader clock while the VALUs are busy (shader-clock cycles of the probe's
+    loop over the ticks of the constant-rate counter), a plain copy's HBM rate, and an empty kernel launched
+    back to back (eagerly, and as dependent nodes of a HIP graph, which is how the conv chains are timed)."""
+    import torch
+
+    from paper_2207_08820_amd import probe
+
+    out = {}
+    ops = probe.valu_ops_per_thread_iter()
+    khz = probe.wall_clock_khz()
+    for waves_per_simd in (8, 2):
+        blocks, iters = 256 * waves_per_simd, 12000 // waves_per_simd  # about 1 ms either way
+        clocks = torch.zeros((blocks, 2), dtype=torch.int64, device=dev)
+        sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
+        for _ in range(3):
+            probe.valu(blocks, iters, clocks, sink)
+        torch.cuda.synchronize()
+        ms = time_events(lambda: probe.valu(blocks, iters, clocks, sink), 5)
+        rate = blocks * 256.0 * iters * ops / (ms * 1e-3)
+        c = clocks.cpu().numpy().astype(np.float64)
+        key = f"valu_lane_ops_per_s_T_{waves_per_simd}_waves_per_simd"
+        out[key] = round(rate / 1e12, 3)
+        if waves_per_simd == 8:
+            out["valu_peak_measured"] = round(rate / 1e12, 3)
+            out["valu_peak_measured_frac_of_datasheet"] = round(rate / VALU_PEAK_LANE_OPS, 4)
+            if khz > 0 and np.all(c[:, 1] > 0):
+                mhz = float(np.median(c[:, 0] / c[:, 1])) * khz / 1e3
+                out["shader_clock_mhz_under_valu_load"] = round(mhz, 1)
+                out["constant_counter_khz"] = khz
+                out["valu_peak_at_measured_clock"] = round(256 * 64 * mhz * 1e6 / 1e12, 3)
+    n = 1 << 28  # 1 GiB of int32
+    src = torch.zeros(n, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        probe.copy(src, dst)
+    torch.cuda.synchronize()
+    ms = time_events(lambda: probe.copy(src, dst), 5)
+    out["copy_TBps_measured"] = round(2.0 * 4 * n / (ms * 1e-3) / 1e12, 3)
+    del src, dst
+    for _ in range(20):
+        probe.empty()
+    torch.cuda.synchronize()
+    out["launch_floor_eager_us"] = round(time_events(probe.empty, 500) * 1e3, 3)
+    out["launch_floor_us"] = round(time_graph(probe.empty, reps=50, replays=10) * 1e3, 3)
+    return out
 
 
 def gemm_workload(abits, wbits, size, dev):
@@ -123,7 +195,7 @@ def layer_floors(L, abits, wbits, qbits, batch=1):
     return abits * wbits * batch * L.macs / 16.0 / VALU_PEAK_LANE_OPS * 1e6, nbytes / HBM_PEAK_BYTES * 1e6
 
 
-def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0):
+def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_us=0.0):
     """Whole conv chain of a model-shaped stack ("resnet18": 19 convs A2W2; "yolo": 16 convs A2 / bipolar
     W1).  Scale and bias come from the closed-form mean / deviation of a uniform-input layer; timing
     does not depend on the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
@@ -170,12 +242,15 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0):
         valu_us, hbm_us = layer_floors(pl.spec, 2, wbits, stack.qbits[i], batch)
         plan = dlrt.dlrt_query_plan(batch * pl.spec.M, pl.spec.Co, pl.spec.k * pl.spec.k * (((pl.spec.Ci + 31) // 32) * 32),
                                     2, wbits)
+        bound_us = max(valu_us, hbm_us, launch_floor_us)  # the floor that binds: VALU, HBM, or a dependent launch
         per_layer.append({"layer": pl.spec.name, "M": batch * pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K,
                           "ms": round(ms, 5), "valu_floor_us": round(valu_us, 3), "hbm_floor_us": round(hbm_us, 3),
                           "valu_frac": round(valu_us / (ms * 1e3), 4),
+                          "bound_us": round(bound_us, 3), "frac_of_bound": round(bound_us / (ms * 1e3), 4),
                           "kernel": plan["kernel"],
                           "tile": [plan["tile_rows"], plan["tile_cols"]], "ksplit": plan["ksplit"]})
     out["sum_valu_floor_us"] = sum(p["valu_floor_us"] for p in per_layer)
+    out["sum_bound_us"] = round(sum(p["bound_us"] for p in per_layer), 3)
     if batch > 1:
         macs = batch * sum(L.macs for L in layers)
         out["batch"] = batch
@@ -250,7 +325,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-only", action="store_true",
                     help="time only the GEMM step (for counter-collection runs, which serialise every launch)")
-    ap.add_argument("--sweep", action="store_true", help="also time the other bit-width pairs of the 4096^3 sweep")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the other bit-width pairs of the 4096^3 sweep")
+    ap.add_argument("--no-probes", action="store_true", help="skip the measured denominators (VALU peak, copy, launch floor)")
     ap.add_argument("--conv-launches", type=int, default=0, metavar="R",
                     help="instead of timing the conv stacks, launch every layer of the batch-64 ResNet-18 and batch-16 "
                          "YOLO-style chains R times (for rocprofv3 --pmc runs: counters per layer kernel)")
@@ -302,10 +378,11 @@ def main():
     value = 2.0 * macs / (ms_per_step * 1e-3) / 1e12
     lane_ops = abits * wbits * macs / 16.0  # one AND + one BCNT per plane pair per 32 elements
     achieved = lane_ops / (gemm_ms * 1e-3)
+    traffic, traffic_source = traffic_from_profile() if args.size == 4096 else (None, "only measured at 4096^3")
     roofline = {"bound": "alu", "kernel": "contract_kernel (dlrt_bitserial_gemm_fused)",
                 "achieved": round(achieved / 1e12, 4), "peak": round(VALU_PEAK_LANE_OPS / 1e12, 4),
                 "unit": "T lane-op/s", "frac": round(achieved / VALU_PEAK_LANE_OPS, 4),
-                "traffic": GEMM_4096_A2W2_TRAFFIC_BYTES if args.size == 4096 else None,
+                "traffic": traffic, "traffic_source": traffic_source,
                 "algorithmic_bytes": 4 * c.M * c.N + (abits * c.M + wbits * c.N) * ((c.K + 31) // 32) * 4,
                 "kernel_ms": round(gemm_ms, 5),
                 "kernel_effective_tops": round(2.0 * macs / (gemm_ms * 1e-3) / 1e12, 3)}
@@ -313,6 +390,19 @@ def main():
         f"VALU roofline {roofline['frac']:.3f}")
 
     extra = {}
+    denominators = {}
+    if not args.no_probes:
+        denominators = measure_denominators(dev)
+        log("measured denominators:", denominators)
+        roofline["valu_peak_measured"] = denominators["valu_peak_measured"]
+        roofline["frac_vs_measured_peak"] = round(achieved / 1e12 / denominators["valu_peak_measured"], 4)
+        roofline["copy_TBps_measured"] = denominators["copy_TBps_measured"]
+        roofline["launch_floor_us"] = denominators["launch_floor_us"]
+        if "shader_clock_mhz_under_valu_load" in denominators:
+            roofline["shader_clock_mhz_under_valu_load"] = denominators["shader_clock_mhz_under_valu_load"]
+            roofline["frac_vs_peak_at_measured_clock"] = round(achieved / 1e12 / denominators["valu_peak_at_measured_clock"], 4)
+        extra["measured_denominators"] = denominators
+    floor_us = denominators.get("launch_floor_us", 0.0)
     unfused = make_step(dlrt, t, fused=False)
     for _ in range(3):
         unfused()
@@ -324,12 +414,12 @@ def main():
         for which, b in (("resnet18", 64), ("yolo", 16)):
             extra[f"{which}_batch{b}_layers_launched"] = stack_ms(dlrt, dev, which, batch=b, launches_only=args.conv_launches)[1]
         return emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t)
-    r18, per_layer = stack_ms(dlrt, dev, "resnet18")
+    r18, per_layer = stack_ms(dlrt, dev, "resnet18", launch_floor_us=floor_us)
     extra["resnet18_a2w2_conv_stack_ms"] = round(r18["graph_fused_ms"], 5)
     extra["resnet18_a2w2_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in r18.items()}
     extra["resnet18_per_layer"] = per_layer
     log(f"ResNet-18 A2W2 conv stack (19 convs): {r18}")
-    yolo, per_layer = stack_ms(dlrt, dev, "yolo")
+    yolo, per_layer = stack_ms(dlrt, dev, "yolo", launch_floor_us=floor_us)
     extra["yolo_style_a2w1_conv_stack_ms"] = round(yolo["graph_fused_ms"], 5)
     extra["yolo_style_a2w1_conv_stack_variants_ms"] = {k: round(v, 5) for k, v in yolo.items()}
     extra["yolo_style_per_layer"] = per_layer
@@ -337,7 +427,7 @@ def main():
 
     # throughput of the same chains with many images per pass (large enough for the block kernel)
     for name, which, b in (("resnet18_a2w2_conv_stack_batch64", "resnet18", 64), ("yolo_style_a2w1_conv_stack_batch16", "yolo", 16)):
-        res, per_layer = stack_ms(dlrt, dev, which, iters=10, batch=b)
+        res, per_layer = stack_ms(dlrt, dev, which, iters=10, batch=b, launch_floor_us=floor_us)
         extra[name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()}
         extra[name + "_per_layer"] = per_layer
         log(f"{name}: {res}")
@@ -358,8 +448,20 @@ def main():
                                       "speedup_over_bit_serial_a2w2_kernel": round(gemm_ms / mfma_ms, 2)}
     log("unpacked int8 MFMA GEMM (comparison):", extra["unpacked_i8_mfma_gemm"])
 
-    if args.sweep:
+    if not args.no_sweep:
         from paper_2207_08820_amd import inputs
+
+        measured_peak = denominators.get("valu_peak_measured")
+
+        def sweep_row(ab, wb, ms, **tags):
+            ops = ab * wb * macs / 16.0
+            row = {"abits": ab, "wbits": wb, **tags, "gemm_ms": round(ms, 5),
+                   "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
+                   "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)}
+            if measured_peak:
+                row["frac_vs_measured_peak"] = round(ops / (ms * 1e-3) / 1e12 / measured_peak, 4)
+            log(row)
+            return row
 
         sweep = []
         for ab, wb in inputs.CONFIG5_PAIRS:
@@ -374,12 +476,7 @@ def main():
             for _ in range(3):
                 only_gemm()
             torch.cuda.synchronize()
-            ms = time_events(only_gemm, 20)
-            ops = ab * wb * macs / 16.0
-            sweep.append({"abits": ab, "wbits": wb, "gemm_ms": round(ms, 5),
-                          "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
-                          "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
-            log(sweep[-1])
+            sweep.append(sweep_row(ab, wb, time_events(only_gemm, 20)))
             if (ab, wb) == (2, 2):  # the same pair with two's-complement activations (only the sign of the MSB planes differs)
                 a_twos = torch.as_tensor(inputs.uniform_values((cs.M, cs.K), ab, inputs.TWOS, inputs.seed_for(5, 0) + 3), device=dev)
                 dlrt.dlrt_pack_bitplanes(a_twos, ab, inputs.TWOS, out=ts["A"])
@@ -391,11 +488,7 @@ def main():
                 for _ in range(3):
                     twos_gemm()
                 torch.cuda.synchronize()
-                ms = time_events(twos_gemm, 20)
-                sweep.append({"abits": ab, "wbits": wb, "enc_a": "twos_complement", "gemm_ms": round(ms, 5),
-                              "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
-                              "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
-                log(sweep[-1])
+                sweep.append(sweep_row(ab, wb, time_events(twos_gemm, 20), enc_a="twos_complement"))
             if (ab, wb) == (1, 1):  # the extra row: the same sizes with bipolar (+1 / -1) weights
                 w_bip = torch.as_tensor(inputs.uniform_values((cs.N, cs.K), 1, inputs.BIPOLAR, inputs.seed_for(5, 1) + 7), device=dev)
                 dlrt.dlrt_pack_bitplanes(w_bip, 1, inputs.BIPOLAR, out=ts["W"])
@@ -406,11 +499,7 @@ def main():
                 for _ in range(3):
                     bipolar_gemm()
                 torch.cuda.synchronize()
-                ms = time_events(bipolar_gemm, 20)
-                sweep.append({"abits": 1, "wbits": 1, "enc_w": "bipolar", "gemm_ms": round(ms, 5),
-                              "effective_tops": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
-                              "valu_frac": round(ops / (ms * 1e-3) / VALU_PEAK_LANE_OPS, 4)})
-                log(sweep[-1])
+                sweep.append(sweep_row(1, 1, time_events(bipolar_gemm, 20), enc_w="bipolar"))
             del ts
         extra["sweep_4096"] = sweep
 

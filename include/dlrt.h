@@ -155,8 +155,11 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
  * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  tile_rows = 64 asks for the row kernel (one output
  * pixel per lane; convolutions with KH*KW*ceil(Ci/32) <= 16 or = 18, DLRT_ERR_SHAPE otherwise);
- * ksplit then is the number of 32-column groups a wave covers (0: planned).  The result does not depend on
- * the hints.
+ * ksplit then is the number of 32-column groups a wave covers (0: planned).  tile_rows = 128 asks for the panel
+ * kernel (one output pixel per lane, the reduction walked in panels against weights held in LDS; needs Ci a
+ * multiple of 128, abits * wbits * 8 * ksplit <= 64 and at most 2^31 bytes of activations, DLRT_ERR_SHAPE
+ * otherwise); ksplit (0 or 1, 2, 4) then is the number of 8-column groups a wave covers.  The result does not
+ * depend on the hints.
  */
 dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, const float *scale,
                                         const float *bias, int N, int H, int W, int Ci, int Co, int KH,
@@ -203,6 +206,10 @@ dlrt_status dlrt_bitserial_conv2d_fused_pair(const dlrt_conv_problem *first, con
  *   *block_kernel = 2: the row kernel (one output row per lane: a wave covers 64 rows x tile_cols columns);
  *                      taken when the reduction is at most 16 packed words (or 18) and the problem has
  *                      enough 64-row x 32-column waves for that reduction length.
+ *   *block_kernel = 3: the panel kernel (one output row per lane, 64 rows x tile_cols columns per wave, the
+ *                      reduction walked in panels against weights in LDS); taken for long reductions with
+ *                      many rows.  The answer assumes 16-byte aligned operands and, for a convolution, a
+ *                      channel count that is a multiple of 128; otherwise such a call takes the throughput kernel.
  * Any output pointer may be NULL.
  */
 dlrt_status dlrt_query_plan(int64_t M, int64_t N, int64_t K, int abits, int wbits, int *block_kernel,

@@ -270,7 +270,7 @@ def dlrt_query_plan(M: int, N: int, K: int, abits: int, wbits: int) -> dict:
     """Kernel and tile the library would use for an M x N x K contraction (host only)."""
     out = [ctypes.c_int() for _ in range(4)]
     _check(load().dlrt_query_plan(M, N, K, abits, wbits, *[ctypes.byref(o) for o in out]), "dlrt_query_plan")
-    kind = ("wave", "block", "rows")[out[0].value]
+    kind = ("wave", "block", "rows", "panels")[out[0].value]
     return dict(kernel=kind, block_kernel=kind == "block", tile_rows=out[1].value, tile_cols=out[2].value,
                 ksplit=out[3].value)
 

@@ -14,12 +14,16 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdlrt_hip.so")
+# measurement probes of bench.py (VALU peak, copy bandwidth, launch floor): a library of its own, so that the
+# product library exports nothing but include/dlrt.h
+PROBE_LIB = os.path.join(HERE, "libdlrt_probe.so")
 # (source, object name, extra defines); the contraction kernels are built once per activation bit width
 UNITS = [("api.hip", "api.o", []), ("pack.hip", "pack.o", []), ("epilogue.hip", "epilogue.o", []),
          ("contract_dispatch.hip", "contract_dispatch.o", []), ("unpacked_mfma.hip", "unpacked_mfma.o", [])] + \
         [("contract_rows.hip", f"contract_rows_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)] + \
         [("contract.hip", f"contract_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)] + \
-        [("contract_wave.hip", f"contract_wave_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)]
+        [("contract_wave.hip", f"contract_wave_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)] + \
+        [("contract_panels.hip", f"contract_panels_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # packed-fp32 instruction selection is switched off for every device compile
@@ -46,10 +50,12 @@ def _compile(unit, extra) -> str:
 
 def build_library(extra_flags=()) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(len(UNITS), os.cpu_count() or 4, 16)) as pool:
-        objs = list(pool.map(lambda u: _compile(u, list(extra_flags)), UNITS))
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs,
-                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    units = UNITS + [("probe.hip", "probe.o", [])]
+    with ThreadPoolExecutor(max_workers=min(len(units), os.cpu_count() or 4, 16)) as pool:
+        objs = list(pool.map(lambda u: _compile(u, list(extra_flags)), units))
+    link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-rpath,/opt/rocm/lib"]
+    subprocess.run([*link, "-o", LIB, *objs[:-1]], check=True)
+    subprocess.run([*link, "-o", PROBE_LIB, objs[-1]], check=True)
     return LIB
 
 

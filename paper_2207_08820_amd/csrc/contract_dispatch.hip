@@ -56,6 +56,18 @@ dlrt_status launch_rows(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, in
     return DLRT_ERR_BITS;
 }
 
+dlrt_status launch_panels(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
+                          bool conv, int ncols, hipStream_t stream)
+{
+    switch (abits) {
+    case 1: return dlrt::launch_panels_a1(g, o, wbits, bipolar, conv, ncols, stream);
+    case 2: return dlrt::launch_panels_a2(g, o, wbits, bipolar, conv, ncols, stream);
+    case 3: return dlrt::launch_panels_a3(g, o, wbits, bipolar, conv, ncols, stream);
+    case 4: return dlrt::launch_panels_a4(g, o, wbits, bipolar, conv, ncols, stream);
+    }
+    return DLRT_ERR_BITS;
+}
+
 dlrt_status wave_by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
                           bool conv, int tm, int ksplit, hipStream_t stream)
 {
@@ -93,7 +105,8 @@ bool prefer_half_rows(int M, int N, int abits, int wbits)
 
 bool prefer_wave_kernel(int M, int N, int abits, int wbits)
 {
-    return block_tiles(M, N, abits, wbits) < wave_below(abits) || 2 * N <= block_tile(wbits);
+    // (also when M fills at most half a tile's rows: the same waste in the other direction)
+    return block_tiles(M, N, abits, wbits) < wave_below(abits) || 2 * N <= block_tile(wbits) || 2 * M <= block_tile(abits);
 }
 
 struct WavePlan {
@@ -155,6 +168,21 @@ bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits)
     return row_kernel_waves(M, N) >= from;
 }
 
+// The panel kernel (one output row per lane, 64 rows x 8 columns per wave, the reduction walked in panels against
+// weights in LDS) has small units of work that the hardware deals out as earlier ones finish, where the block
+// kernel's few large tiles leave the last round of blocks partly empty.  Measured at A2W2 on 3x3 convolutions over
+// 128 / 256 / 512 channels with 3136 .. 50176 output pixels x 128 .. 512 channels (3136 .. 12544 waves): 4 to 9 %
+// faster than the block kernel on every one (392 .. 1568 of its 64 x 64 tiles); with 1-bit weights (half the
+// arithmetic per activation word fetched) the two are level, and reductions below about 1000 elements belong to
+// the row kernel or are too short to amortise a wave's own copy of the weights.  With thousands of tiles the
+// block kernel fills its rounds and is the faster one (0.95 of the VALU roof at 4096^3, where the panel kernel's
+// LDS broadcasts and per-panel address arithmetic hold it below 0.8).
+bool prefer_panel_kernel(int64_t M, int N, int Kw, int abits, int wbits)
+{
+    return abits >= 2 && abits * wbits == 4 && Kw >= 32 && M >= 2048 && ((M + 63) / 64) * ((N + 7) / 8) >= 3072 &&
+           block_tiles((int)M, N, abits, wbits) < 2048;
+}
+
 // Row kernel: a wave covers 64 rows x ncols columns.  32 columns (one output word per row) measured fastest
 // or within 3 % of it at every size: more, shorter waves balance better over the SIMDs than the saved
 // activation loads are worth.  Only from about 32 K waves on do wider waves gain those few per cent.
@@ -180,6 +208,13 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
         if (ksplit) *ksplit = 1;
         return;
     }
+    if (prefer_panel_kernel(M, N, Kw, abits, wbits) && Kw % 4 == 0) {
+        if (block_kernel) *block_kernel = 3;
+        if (tile_rows) *tile_rows = 64;
+        if (tile_cols) *tile_cols = 8;
+        if (ksplit) *ksplit = 1;
+        return;
+    }
     if (!wave && prefer_half_rows(M, N, abits, wbits)) rows /= 2;
     if (wave) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
@@ -202,6 +237,11 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
     if (prefer_rows_kernel(M, N, Kw, wbits)) return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N), stream);
+    const int64_t a_bytes = (int64_t)M * abits * Kw * 4;
+    if (prefer_panel_kernel(M, N, Kw, abits, wbits) && panel_kernel_has(g, abits, wbits, false, 8, a_bytes)) {
+        g.a_bytes = (uint32_t)a_bytes;
+        return launch_panels(g, o, abits, wbits, bipolar, false, 8, stream);
+    }
     if (prefer_wave_kernel(M, N, abits, wbits)) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
         return wave_by_abits(g, o, abits, wbits, bipolar, false, p.tm, p.ksplit, stream);
@@ -232,6 +272,13 @@ static ContractArgs conv_args(const uint32_t *X, const uint32_t *Wp, const ConvS
     return g;
 }
 
+// A 1x1 convolution with stride 1 and no padding IS a GEMM over the pixels (the im2col row of an output pixel is
+// that pixel's own packed words), so it runs on the GEMM instantiations, which decode no pixel coordinates.
+static bool pointwise(const ConvShape &c)
+{
+    return c.KH == 1 && c.KW == 1 && c.sh == 1 && c.sw == 1 && c.ph == 0 && c.pw == 0;
+}
+
 dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const Wp[2], const ConvShape c[2], int abits,
                              int wbits, bool a_msb_neg, bool w_msb_neg, bool bipolar, const FusedOut o[2],
                              hipStream_t stream)
@@ -260,7 +307,7 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
         if (!p.found) return DLRT_ERR_SHAPE;
         if (p.ksplit > ksplit) ksplit = p.ksplit;  // one block shape for both: the deeper reduction decides
     }
-    return wave_by_abits(g, o, 2, abits, wbits, bipolar, true, 1, ksplit, stream);
+    return wave_by_abits(g, o, 2, abits, wbits, bipolar, !(pointwise(c[0]) && pointwise(c[1])), 1, ksplit, stream);
 }
 
 dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &c, int abits, int wbits,
@@ -268,21 +315,36 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
                         hipStream_t stream)
 {
     const ContractArgs g = conv_args(X, Wp, c, a_msb_neg, w_msb_neg);
+    const bool conv = !pointwise(c);
     const bool rows_fit = row_kernel_has(g.Kw);
+    const int64_t x_bytes = (int64_t)c.N * c.H * c.W * abits * c.Cw * 4;
+    if (tile_rows == 128) {  // hint: the panel kernel, 8 * ksplit columns per wave
+        const int ncols = ksplit == 0 ? 8 : 8 * ksplit;
+        if (!panel_kernel_has(g, abits, wbits, conv, ncols, x_bytes)) return DLRT_ERR_SHAPE;
+        ContractArgs gp = g;
+        gp.a_bytes = (uint32_t)x_bytes;
+        return launch_panels(gp, o, abits, wbits, bipolar, conv, ncols, stream);
+    }
     if (tile_rows == 64) {  // hint: the row kernel, ksplit groups of 32 columns per wave
         if (!rows_fit || ksplit < 0 || ksplit > 2048) return DLRT_ERR_SHAPE;
-        return launch_rows(g, o, abits, wbits, bipolar, true, ksplit > 0 ? 32 * ksplit : plan_rows(g.M, g.N), stream);
+        return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 32 * ksplit : plan_rows(g.M, g.N), stream);
     }
     if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits))
-        return launch_rows(g, o, abits, wbits, bipolar, true, plan_rows(g.M, g.N), stream);
+        return launch_rows(g, o, abits, wbits, bipolar, conv, plan_rows(g.M, g.N), stream);
+    if (tile_rows == 0 && ksplit == 0 && prefer_panel_kernel(g.M, g.N, g.Kw, abits, wbits) &&
+        panel_kernel_has(g, abits, wbits, conv, 8, x_bytes)) {
+        ContractArgs gp = g;
+        gp.a_bytes = (uint32_t)x_bytes;
+        return launch_panels(gp, o, abits, wbits, bipolar, conv, 8, stream);
+    }
     if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
         const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
         if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have
-        return wave_by_abits(g, o, abits, wbits, bipolar, true, p.tm, p.ksplit, stream);
+        return wave_by_abits(g, o, abits, wbits, bipolar, conv, p.tm, p.ksplit, stream);
     }
     ContractArgs gb = g;
     gb.half_rows = prefer_half_rows(g.M, g.N, abits, wbits);
-    return by_abits(gb, o, abits, wbits, bipolar, true, stream);
+    return by_abits(gb, o, abits, wbits, bipolar, conv, stream);
 }
 
 }  // namespace dlrt

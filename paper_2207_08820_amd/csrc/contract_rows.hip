@@ -42,7 +42,12 @@ namespace {
 using dlrt::ContractArgs;
 using dlrt::FusedOut;
 
-constexpr int kRowsPerBlock = 64;
+constexpr int kRowsPerBlock = 64;   // rows of one wave's tile: one per lane
+// Waves per workgroup.  The waves of a block never synchronise or share anything; they only travel together
+// because the chip hands out one-wave workgroups too slowly: with 6272 of them a 3x3 conv over 64 channels had
+// 2.7 waves resident per SIMD on average although 6 fit, and a layer of 13 M outputs spent half of its 9 us
+// being dispatched.
+constexpr int kWavesPerBlock = 4;
 
 __device__ __forceinline__ uint32_t dot4(uint32_t a, uint32_t b, uint32_t c)
 {
@@ -89,8 +94,22 @@ __device__ __forceinline__ float clamp0(float x, float hi)
 #endif
 }
 
+// x with byte BYTE replaced by v converted to an 8-bit unsigned integer.  v_cvt_pk_u8_f32 rounds to nearest,
+// ties to even, and saturates to [0, 255] (negative values and NaN give 0) - checked on the chip with ties,
+// negatives, large values, infinities and NaN - so it is rint(), the lower clamp, the conversion and the byte
+// insertion in ONE instruction; only the upper clamp remains for the caller.
+template <int BYTE>
+__device__ __forceinline__ uint32_t byte_from_float(float v, uint32_t x)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_cvt_pk_u8_f32(v, (uint32_t)BYTE, x);
+#else
+    return x | ((uint32_t)v << (8 * BYTE));
+#endif
+}
+
 template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
+__global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
                                                                        const int ncols,
                                                                        const uint32_t *__restrict__ Wp,
                                                                        const float *__restrict__ scale,
@@ -103,11 +122,12 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
     // the same die, one after the other, and the row's activations come from HBM once however the grid divides.
     // The grid is padded to a multiple of 8 row blocks; the surplus blocks leave here.
     const int col_groups = (g.N + ncols - 1) / ncols;
-    const int die = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform, and known to be
+    const int die = blockIdx.x & 7, local = (blockIdx.x >> 3) * kWavesPerBlock + wave;
     const int row_group = local / col_groups, col_group = local - row_group * col_groups;
     const int row_block = row_group * 8 + die;
-    if (row_block * kRowsPerBlock >= g.M) return;
-    const int m = row_block * kRowsPerBlock + threadIdx.x;
+    if ((int64_t)row_block * kRowsPerBlock >= g.M) return;
+    const int m = row_block * kRowsPerBlock + (threadIdx.x & 63);
     const int mc = min(m, g.M - 1);  // rows beyond the matrix are computed on the last row, never stored
     const int n0 = col_group * ncols, n1 = min(n0 + ncols, g.N);
 
@@ -124,27 +144,81 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
         const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
         const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
         const uint32_t *image = g.A + (size_t)img * g.H * g.Wd * (AB * g.Cw);
+        // One pixel's words, [plane][Cw], are contiguous.  When a tap is CW words wide and the reduction is a whole
+        // number of taps, a tap is fetched as that one run with the widest loads its size allows, instead of a
+        // 4-byte load per word: the lanes of a wave read 64 different pixels, so what a load instruction costs
+        // the cache is its 64 separate lines, and the fewer instructions the better (measured: a 3x3 conv
+        // over 64 channels took a third of its time in these loads).
+        auto load_taps = [&](auto cw_tag) {
+            constexpr int CW = decltype(cw_tag)::value, TAPS = KW / CW, RUN = AB * CW;
 #pragma unroll
-        for (int k = 0; k < KW; ++k) {
-            const int kc = k < g.Kw ? k : 0;
-            const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
-            const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
-            const int ih = ih0 + kh, iw = iw0 + kw;
-            const bool ok = k < g.Kw && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
-            const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
-            const uint32_t *pixel = image + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
+            for (int t = 0; t < TAPS; ++t) {
+                const int kh = fast_div(t, g.magicKW), kw = t - kh * g.KW;  // uniform: the scalar unit's work
+                const int ih = ih0 + kh, iw = iw0 + kw;
+                const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
+                const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
+                const uint32_t *pixel = image + (size_t)(ihc * g.Wd + iwc) * RUN;
+                uint32_t v[RUN];
+                if constexpr (RUN % 4 == 0) {  // the image base is 16-byte aligned, so every run of 4n words is
 #pragma unroll
-            for (int j = 0; j < AB; ++j) {
-                const uint32_t v = pixel[j * g.Cw];
-                a[j][k] = ok ? v : 0u;
+                    for (int e = 0; e < RUN; e += 4) {
+                        const uint4 q = *reinterpret_cast<const uint4 *>(pixel + e);
+                        v[e] = q.x; v[e + 1] = q.y; v[e + 2] = q.z; v[e + 3] = q.w;
+                    }
+                } else if constexpr (RUN % 2 == 0) {
+#pragma unroll
+                    for (int e = 0; e < RUN; e += 2) {
+                        const uint2 q = *reinterpret_cast<const uint2 *>(pixel + e);
+                        v[e] = q.x; v[e + 1] = q.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < RUN; ++e) v[e] = pixel[e];
+                }
+#pragma unroll
+                for (int j = 0; j < AB; ++j)
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) a[j][t * CW + c] = ok ? v[j * CW + c] : 0u;
+            }
+        };
+        if (g.Kw == KW && g.Cw == 1) {
+            load_taps(std::integral_constant<int, 1>{});
+        } else if (g.Kw == KW && g.Cw == 2 && KW % 2 == 0) {
+            load_taps(std::integral_constant<int, KW % 2 == 0 ? 2 : 1>{});
+        } else if (g.Kw == KW && g.Cw == 4 && KW % 4 == 0) {
+            load_taps(std::integral_constant<int, KW % 4 == 0 ? 4 : 1>{});
+        } else if (g.Kw == KW && g.Cw == KW) {  // one tap (a strided 1x1 convolution)
+            load_taps(std::integral_constant<int, KW>{});
+        } else {
+#pragma unroll
+            for (int k = 0; k < KW; ++k) {
+                const int kc = k < g.Kw ? k : 0;
+                const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
+                const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
+                const int ih = ih0 + kh, iw = iw0 + kw;
+                const bool ok = k < g.Kw && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
+                const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
+                const uint32_t *pixel = image + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
+#pragma unroll
+                for (int j = 0; j < AB; ++j) {
+                    const uint32_t v = pixel[j * g.Cw];
+                    a[j][k] = ok ? v : 0u;
+                }
             }
         }
     } else {
         const uint32_t *arow = g.A + (size_t)mc * (AB * g.Kw);
+        if (g.Kw == KW) {  // compile-time offsets: the row's AB * KW words are fetched with wide loads
 #pragma unroll
-        for (int j = 0; j < AB; ++j)
+            for (int j = 0; j < AB; ++j)
 #pragma unroll
-            for (int k = 0; k < KW; ++k) a[j][k] = k < g.Kw ? arow[j * g.Kw + k] : 0u;
+                for (int k = 0; k < KW; ++k) a[j][k] = arow[j * KW + k];
+        } else {
+#pragma unroll
+            for (int j = 0; j < AB; ++j)
+#pragma unroll
+                for (int k = 0; k < KW; ++k) a[j][k] = k < g.Kw ? arow[j * g.Kw + k] : 0u;
+        }
     }
     if (BIPOLAR) {
 #pragma unroll
@@ -155,26 +229,56 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
 
     // Plane weights with their signs (Section V's double sum): +-2^i, +-2^j, negative for the MSB plane of a
     // two's-complement operand.  Popcount sums stay below 2^10 and partial sums below 2^14 here, so the
-    // combine is a chain of 24-bit multiply-adds (one full-rate instruction per plane pair).
+    // combine is a chain of 24-bit multiply-adds (one full-rate instruction each).
     int wcoef[WB], acoef[AB];
 #pragma unroll
     for (int i = 0; i < WB; ++i) wcoef[i] = (g.w_msb_neg && i == WB - 1) ? -(1 << i) : (1 << i);
 #pragma unroll
     for (int j = 0; j < AB; ++j) acoef[j] = (g.a_msb_neg && j == AB - 1) ? -(1 << j) : (1 << j);
+    // bipolar: sum_j 2^j (2 pc(A[j] & W) - pc(A[j])) = 2 sum_j 2^j pc(A[j] & W) - R with one constant R per row
+    int neg_row_sum = 0;
+#pragma unroll
+    for (int j = 0; j < AB; ++j) neg_row_sum -= rowpc[j] << j;
     const float qmax = (float)((1 << o.qbits) - 1);
     const int Cwo = (g.N + 31) / 32;
     const bool row_ok = m < g.M;
+    int lane_zero = 0;  // zero, but opaque to the compiler: an index with it is loaded per lane
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("v_mov_b32 %0, 0" : "=v"(lane_zero));
+#endif
     const bool packed_only = !o.acc && !o.y && !o.q;  // the chained-layer case: nothing but the packed words
 
     // One output.  n is uniform over the wave, so the weight words, scale and bias come through
     // scalar loads and the AND takes them as scalar operands.  EXACT: the reduction has exactly KW words,
     // so every weight index is a compile-time offset from n * WB * KW and the loads of neighbouring
     // columns merge into wide scalar loads.
-    auto output = [&](int n, auto exact_tag) {
-        constexpr bool EXACT = decltype(exact_tag)::value;
+    // HORNER (unsigned activations): the activation planes of one weight plane share ONE accumulator, most
+    // significant plane first, doubled between planes: the accumulating popcount then leaves
+    // sum_j 2^j popcount(A[j] & W[i]) with one shift per further plane and no separate adds.  Two's-complement
+    // activations (a negative MSB plane cannot be accumulated) take one accumulator per plane pair, on the
+    // general path below, as does any call that wants more than the packed output.
+    auto output = [&](int n, auto exact_tag, auto horner_tag) {
+        constexpr bool EXACT = decltype(exact_tag)::value, HORNER = decltype(horner_tag)::value;
         const int kw = EXACT ? KW : g.Kw;
         const uint32_t *w = Wp + (size_t)n * (WB * kw);
         int total = 0;
+        if (HORNER) {
+#pragma unroll
+            for (int i = 0; i < WB; ++i) {
+                int acc = 0;
+#pragma unroll
+                for (int j = AB - 1; j >= 0; --j) {
+                    if (j < AB - 1) acc <<= 1;
+#pragma unroll
+                    for (int k = 0; k < KW; ++k) {  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
+                        acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
+                        keep_chain(acc);
+                    }
+                }
+                total = BIPOLAR ? (acc << 1) + neg_row_sum : mad24(acc, wcoef[i], total);
+            }
+            return total;
+        }
 #pragma unroll
         for (int j = 0; j < AB; ++j) {
             int part = BIPOLAR ? -rowpc[j] : 0;
@@ -182,7 +286,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             for (int i = 0; i < WB; ++i) {
                 int acc = 0;
 #pragma unroll
-                for (int k = 0; k < KW; ++k) {  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
+                for (int k = 0; k < KW; ++k) {
                     acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
                     keep_chain(acc);
                 }
@@ -206,20 +310,24 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
             }
         }
     };
-    // bias may be absent: read a valid address anyway and mask the bits (all uniform, so on the scalar unit),
-    // so that the column loop has neither a branch nor a per-lane select
-    const float *const bias_or_scale = bias ? bias : scale;
-    const uint32_t bias_mask = bias ? 0xffffffffu : 0u;
-    auto bias_of = [&](int n) { return __uint_as_float(__float_as_uint(bias_or_scale[n]) & bias_mask); };
-    auto quantized = [&](int total, int n) {
-        const float y = __fmaf_rn((float)total, scale[n], bias_of(n));
-        return (uint32_t)clamp0(rintf(y), qmax);
+    // min(y, qmax) with y = fma(float(acc), scale, bias): the upper clamp of the requantization, applied before the
+    // rounding (the same number, qmax being an integer); byte_from_float() then rounds and clamps at zero.  With
+    // no bias the product alone rounds to the same number as the fused multiply-add with +0 (up to the sign of a
+    // zero, which the clamp removes).  A column's bias is the same for every lane but has to sit in a vector
+    // register (an instruction reads at most one scalar register, and that is the scale): it comes through a
+    // vector load of one address, which costs the VALUs nothing, instead of a register move per output.
+    auto upper_clamped = [&](int total, int n, auto bias_tag) {
+        constexpr bool HAS_BIAS = decltype(bias_tag)::value;
+        const float y = HAS_BIAS ? __fmaf_rn((float)total, scale[n], bias[n + lane_zero]) : (float)total * scale[n];
+        return fminf(y, qmax);
     };
-    auto packed_columns = [&](auto exact_tag) {
+    auto requantized = [&](int total, int n, auto bias_tag) { return clamp0(rintf(upper_clamped(total, n, bias_tag)), qmax); };
+    auto packed_columns = [&](auto exact_tag, auto horner_tag, auto bias_tag) {
         // Eight columns at a time, in groups of CB with no branch inside a group: the scalar loads of a
         // group (weights, scale, bias) are issued together and waited for once, instead of one round trip
-        // to the scalar cache per column.  The eight results are kept as bytes; one byte of each plane word
-        // is then gathered with two dot products per plane, as the packing kernel does.
+        // to the scalar cache per column.  The eight results land in the nibbles of four bytes (columns c and
+        // c + 4 share a byte); bit p of every nibble is then one byte of plane p's word, gathered by ONE dot
+        // product with the byte vector {1, 2, 4, 8}: sum_c 2^c (bit(q_c) + 16 bit(q_{c+4})).
         constexpr int CB = WB * KW <= 8 ? 4 : WB * KW <= 16 ? 2 : 1;
         int n = n0;
         for (; n + 8 <= n1; n += 8) {
@@ -227,16 +335,18 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
 #pragma unroll
             for (int c0 = 0; c0 < 8; c0 += CB) {
 #pragma unroll
-                for (int c = c0; c < c0 + CB; ++c) x[c >> 2] |= quantized(output(n + c, exact_tag), n + c) << (8 * (c & 3));
+                for (int c = c0; c < c0 + CB; ++c) {
+                    const float r = upper_clamped(output(n + c, exact_tag, horner_tag), n + c, bias_tag);
+                    x[c >> 2] = (c & 3) == 0 ? byte_from_float<0>(r, x[c >> 2]) : (c & 3) == 1 ? byte_from_float<1>(r, x[c >> 2])
+                              : (c & 3) == 2 ? byte_from_float<2>(r, x[c >> 2]) : byte_from_float<3>(r, x[c >> 2]);
+                }
                 __builtin_amdgcn_sched_barrier(0);  // keep the next group's scalar loads out of this group
             }
+            const uint32_t nib = x[0] | (x[1] << 4);
             const int shift = n & 24;  // which byte of the 32-column word these eight columns are
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if (p < o.qbits) {
-                    const uint32_t even = (x[0] >> p) & 0x01010101u, odd = (x[1] >> p) & 0x01010101u;
-                    word[p] |= dot4(odd, 0x80402010u, dot4(even, 0x08040201u, 0u)) << shift;
-                }
+                if (p < o.qbits) word[p] |= dot4((nib >> p) & 0x11111111u, 0x08040201u, 0u) << shift;
             }
             if (shift == 24 || n + 8 == n1) {
 #pragma unroll
@@ -246,19 +356,26 @@ __global__ __launch_bounds__(kRowsPerBlock) void contract_rows_kernel(const Cont
                 }
             }
         }
-        for (; n < n1; ++n) add_bits(n, quantized(output(n, exact_tag), n));  // the last columns of a ragged N
+        for (; n < n1; ++n)  // the last columns of a ragged N
+            add_bits(n, (uint32_t)requantized(output(n, exact_tag, horner_tag), n, bias_tag));
     };
-    if (packed_only) {
-        if (g.Kw == KW) packed_columns(std::true_type{});
-        else packed_columns(std::false_type{});
+    if (packed_only && !g.a_msb_neg) {
+        // uniform over the launch; each combination is a loop of its own so that none pays for the others
+        if (g.Kw == KW) {
+            if (bias) packed_columns(std::true_type{}, std::true_type{}, std::true_type{});
+            else packed_columns(std::true_type{}, std::true_type{}, std::false_type{});
+        } else {
+            if (bias) packed_columns(std::false_type{}, std::true_type{}, std::true_type{});
+            else packed_columns(std::false_type{}, std::true_type{}, std::false_type{});
+        }
     } else {
         for (int n = n0; n < n1; ++n) {
-            const int total = output(n, std::false_type{});
+            const int total = output(n, std::false_type{}, std::false_type{});
             const size_t idx = (size_t)m * g.N + n;
             uint32_t q = 0;
             if (o.acc && row_ok) o.acc[idx] = total;
             if (scale) {
-                const float y = __fmaf_rn((float)total, scale[n], bias_of(n));
+                const float y = __fmaf_rn((float)total, scale[n], bias ? bias[n] : 0.0f);
                 q = (uint32_t)clamp0(rintf(y), qmax);
                 if (o.y && row_ok) o.y[idx] = y;
                 if (o.q && row_ok) o.q[idx] = (uint8_t)q;
@@ -272,9 +389,11 @@ template <int AB, int WB, int KW, bool BIPOLAR>
 dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
 {
     const int64_t bx = ((int64_t)g.M + kRowsPerBlock - 1) / kRowsPerBlock, by = (g.N + ncols - 1) / ncols;
-    const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies, see the kernel
-    if (blocks > 0x7fffffffLL) return DLRT_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks), block(kRowsPerBlock);
+    // per die: its share of the row blocks (padded to the 8 dies) times the column groups, kWavesPerBlock to a block
+    const int64_t per_die = ((bx + 7) / 8 * by + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t blocks = 8 * per_die;
+    if (blocks * kWavesPerBlock > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(kRowsPerBlock * kWavesPerBlock);
     if (conv) return dlrt::enqueue(contract_rows_kernel<AB, WB, KW, BIPOLAR, true>, grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
     return dlrt::enqueue(contract_rows_kernel<AB, WB, KW, BIPOLAR, false>, grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
 }

@@ -41,6 +41,7 @@ struct ContractArgs {
     int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
     int half_rows;      // block kernel: tiles of half the usual height (32 instead of 64 rows, 16 instead of 32)
     int xcd_split;      // block kernel: 0, or 1 + log2(c) of the r x c split (r * c = 8) of the tile grid over the 8 dies
+    uint32_t a_bytes;   // panel kernel: size of the activation tensor in bytes (at most 2^31)
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
@@ -84,6 +85,25 @@ dlrt_status launch_rows_a1(const ContractArgs &g, const FusedOut &o, int wbits, 
 dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+
+// Panel kernel (contract_panels.hip): one output row per lane, 64 rows x ncols columns per wave, the reduction
+// walked in panels of 12 or 16 words against weights held in LDS; for long reductions with many rows.  ncols is
+// 8, 16 or 32 with ncols * abits * wbits <= 64 accumulators per lane.  Needs Kw % 4 == 0 and 16-byte aligned
+// operands (vec == 4), at most 64 KB of weights per wave, an activation tensor of at most 2^31 bytes (g.a_bytes),
+// and for a convolution Cw % 4 == 0 and fewer than 2^24 pixels per image.
+inline bool panel_kernel_has(const ContractArgs &g, int abits, int wbits, bool conv, int ncols, int64_t a_bytes)
+{
+    if (ncols != 8 && ncols != 16 && ncols != 32) return false;
+    const int p = g.Kw % 12 == 0 && g.Kw % 16 != 0 ? 12 : 16;
+    const int64_t padded = (int64_t)((g.Kw + p - 1) / p) * p;  // words per column and plane
+    if (g.Kw % 4 != 0 || g.vec != 4 || ncols * abits * wbits > 64 || ncols * wbits * padded * 4 > 65536) return false;
+    if (a_bytes > (1LL << 31)) return false;
+    return !conv || (g.Cw % 4 == 0 && (int64_t)g.H * g.Wd < (1 << 24));
+}
+dlrt_status launch_panels_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_panels_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_panels_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_panels_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 
 // Conv geometry handed from the C ABI to the launcher.
 struct ConvShape {

@@ -150,71 +150,84 @@ def query(lib, M, N, K, a, w):
     return tuple(o.value for o in out)
 
 
+WAVE, BLOCK, ROWS, PANELS = 0, 1, 2, 3
+
+
 def test_planner_choices_for_the_benchmark_workloads(lib):
-    # the 4096^3 sweep takes the throughput kernel with tiles of 16 * {4,4,2,2}[bits]
-    assert query(lib, 4096, 4096, 4096, 2, 2) == (1, 64, 64, 1)
-    assert query(lib, 4096, 4096, 4096, 1, 1) == (1, 64, 64, 1)
-    assert query(lib, 4096, 4096, 4096, 2, 4) == (1, 64, 32, 1)
-    assert query(lib, 4096, 4096, 4096, 3, 3) == (1, 32, 32, 1)
-    assert query(lib, 2048, 2048, 4096, 4, 4) == (1, 16, 32, 1)   # 4096 full tiles of 32 x 32: half-height for 4-bit activations
-    # batch-1 conv layers take the per-wave kernel; deep reductions are split across waves
-    assert query(lib, 64, 64, 576, 2, 2)[0] == 0
-    blk, rows, cols, ks = query(lib, 3136, 64, 576, 2, 2)
-    assert (blk, rows, cols) == (0, 8, 32) and ks in (1, 2)
-    blk, rows, cols, ks = query(lib, 49, 512, 4608, 2, 2)
-    assert (blk, rows, cols) == (0, 8, 32) and ks >= 4
-    assert query(lib, 784, 128, 64, 2, 2) == (0, 8, 32, 1)  # two steps of reduction: nothing to split
-    # short reductions and enough 64-row x 32-column waves: one output row per lane, 32 columns per wave
-    assert query(lib, 409600, 32, 32, 2, 1) == (2, 64, 32, 1)
-    assert query(lib, 50176, 128, 64, 2, 2) == (2, 64, 32, 1)
-    assert query(lib, 1 << 20, 128, 64, 2, 2) == (2, 64, 64, 1)   # 65536 waves of 32 columns: wider waves
-    assert query(lib, 6400, 64, 64, 2, 1)[0] == 0                 # 200 waves: too few for two words
-    assert query(lib, 6400, 64, 32, 2, 1)[0] == 0                 # ... and for one
-    assert query(lib, 12544, 64, 32, 2, 1)[0] == 2                # 392 waves of one word
-    assert query(lib, 409600, 64, 288, 2, 1)[0] == 2              # a 3x3 conv over 32 channels: nine words
-    assert query(lib, 25600, 64, 288, 2, 1)[0] == 1               # the same at batch 1: 800 waves are too few
-    assert query(lib, 25600, 32, 64, 2, 1)[0] == 2                # two words: 400 waves are enough
-    assert query(lib, 12544, 64, 288, 2, 2)[0] == 1               # 392 waves of nine words: the block kernel
-    assert query(lib, 200704, 64, 576, 2, 2) == (2, 64, 32, 1)    # eighteen words (3x3 over 64 channels), 6272 waves
-    assert query(lib, 50176, 64, 576, 2, 2)[0] == 1               # 1568 waves of eighteen words: the block kernel
-    assert query(lib, 200704, 64, 576, 4, 4)[0] == 1              # eighteen words of 3- or 4-bit weights never
-    assert query(lib, 200704, 64, 512, 2, 2)[0] == 1              # sixteen words fill the block kernel's chunk: 6272 waves are not enough
-    assert query(lib, 200704, 128, 512, 2, 2)[0] == 2             # 12544 are
-    assert query(lib, 200704, 64, 544, 2, 2)[0] == 1              # seventeen words: the row kernel has no such instance
-    assert query(lib, 1000, 4096, 32, 2, 2)[0] != 2               # few rows: lanes would idle
-    assert query(lib, 50176, 128, 1152, 2, 2) == (1, 32, 64, 1)   # 1568 tiles of 64 rows: the half-height tile
+    """Which kernel the workloads of bench.py get (a record of the plan the published numbers were measured
+    with, not of the planner's thresholds)."""
+    # the 4096^3 sweep: the throughput kernel with tiles of 16 * {4,4,2,2}[bits]
+    assert query(lib, 4096, 4096, 4096, 2, 2) == (BLOCK, 64, 64, 1)
+    assert query(lib, 4096, 4096, 4096, 1, 1) == (BLOCK, 64, 64, 1)
+    assert query(lib, 4096, 4096, 4096, 2, 4) == (BLOCK, 64, 32, 1)
+    assert query(lib, 4096, 4096, 4096, 3, 3) == (BLOCK, 32, 32, 1)
+    assert query(lib, 4096, 4096, 4096, 4, 4)[0] == BLOCK
+    # every layer of the two stacks at batch 1 except the largest YOLO-style ones: the per-wave kernel
+    assert query(lib, 64, 64, 576, 2, 2)[0] == WAVE
+    assert query(lib, 3136, 64, 576, 2, 2)[:3] == (WAVE, 8, 32)
+    assert query(lib, 49, 512, 4608, 2, 2)[0] == WAVE and query(lib, 49, 512, 4608, 2, 2)[3] >= 4  # deep reduction: split over waves
+    assert query(lib, 784, 128, 64, 2, 2) == (WAVE, 8, 32, 1)
+    # batch 16 / 64: short reductions with many rows take the row kernel, long ones with many rows the panel kernel
+    assert query(lib, 409600, 32, 32, 2, 1)[0] == ROWS
+    assert query(lib, 409600, 64, 288, 2, 1)[0] == ROWS
+    assert query(lib, 200704, 64, 576, 2, 2)[0] == ROWS
+    assert query(lib, 50176, 128, 1152, 2, 2) == (PANELS, 64, 8, 1)
+    assert query(lib, 12544, 256, 2304, 2, 2) == (PANELS, 64, 8, 1)
+    assert query(lib, 3136, 512, 4608, 2, 2) == (PANELS, 64, 8, 1)
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
 
 
 def test_planner_always_returns_a_tile_the_kernels_have(lib):
+    """Properties of any plan, whatever the thresholds are: the tile it names exists in the kernel it names and
+    fits that kernel's registers and LDS, and kernels built for many rows are never given few."""
     import random
     r = random.Random(3)
-    for _ in range(2000):
+    seen = set()
+    for _ in range(3000):
         a, w = r.randint(1, 4), r.randint(1, 4)
-        M, N = r.choice([1, 7, 49, 196, 784, 3136, 25600, 100000, 3000000]), r.choice([1, 16, 32, 64, 100, 512, 4096])
-        K = r.choice([1, 32, 64, 100, 288, 500, 544, 576, 1152, 4608, 40000])
-        blk, rows, cols, ks = query(lib, M, N, K, a, w)
+        M, N = r.choice([1, 7, 49, 196, 784, 3136, 12544, 25600, 100000, 3000000]), r.choice([1, 16, 32, 64, 100, 256, 512, 4096])
+        K = r.choice([1, 32, 64, 100, 288, 500, 544, 576, 1152, 2304, 4608, 40000])
+        kind, rows, cols, ks = query(lib, M, N, K, a, w)
+        seen.add(kind)
+        Kw = -(-K // 32)
         tn = 4 if w <= 2 else 2
-        if blk == 2:  # the row kernel: the reduction fits a lane's registers, whole output words per wave
-            Kw = -(-K // 32)
-            waves = -(-M // 64) * -(-N // 32)
-            assert (Kw <= 16 or (Kw == 18 and w <= 2)) and M >= 2048
-            assert waves >= (256 if Kw == 1 else 384 if Kw == 2 else 1024 if Kw <= 4 else 3072 if Kw <= 8 else 1536 if Kw == 9
-                             else 12288 if Kw <= 16 else 4096)
-            assert rows == 64 and ks == 1 and cols in (32, 64, 128) and (cols == 32 or -(-M // 64) * -(-N // (cols // 2)) > 32768)
-        elif blk:
-            full = 16 * [4, 4, 2, 2][a - 1]   # problems with few full tiles take the half-height tile
+        assert kind in (WAVE, BLOCK, ROWS, PANELS)
+        if kind == ROWS:    # the whole reduction in a lane's registers, whole output words per wave
+            assert Kw <= 16 or (Kw == 18 and w <= 2)
+            assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= 128
+        elif kind == PANELS:  # accumulators per lane, the wave's weights in LDS, whole 16-byte groups
+            assert rows == 64 and ks == 1 and cols in (8, 16, 32)
+            assert cols * a * w <= 64 and Kw % 4 == 0 and cols * w * (Kw + 15) // 16 * 16 * 4 <= 65536
+        elif kind == BLOCK:
+            full = 16 * [4, 4, 2, 2][a - 1]
             assert (cols, ks) == (16 * [4, 4, 2, 2][w - 1], 1) and rows in (full, full // 2)
-            tiles = -(-M // full) * -(-N // cols)
-            assert tiles >= (128 if a <= 2 else 512) and 2 * N > cols
-            assert (rows == full // 2) == (tiles < [4096, 4096, 2048, 16384][a - 1])
+            assert 2 * N > cols                                             # a tile is never mostly padding
         else:
             tm = rows // (2 * tn)
             assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)
             assert tm * tn * a * w <= 72                                     # accumulators per lane
             assert ks * (4 * a * rows + 4 * w * 32) * 16 <= 65536           # LDS of the ks staging regions
-            assert ks == 1 or ks <= -(-(-(-K // 32)) // 4)                   # no more slices than 4-word steps
+            assert ks == 1 or ks <= -(-Kw // 4)                              # no more slices than 4-word steps
+        if kind in (ROWS, PANELS):
+            assert M >= 1024                                                # one row per lane: lanes would idle
+        if M * N <= 64 * 64:
+            assert kind == WAVE                                             # a handful of tiles: the latency kernel
+    assert seen == {WAVE, BLOCK, ROWS, PANELS}
+
+
+def test_hints_override_the_plan_or_are_refused(lib):
+    """A tile hint selects that kernel whatever the planner would pick; a hint the kernels do not have is an error."""
+    f = lib.dlrt_bitserial_conv2d_fused
+    enc = [2, 2, UNSIGNED, TWOS]
+    big = [64, 28, 28, 128, 128, 3, 3, 1, 1, 1, 1]     # the planner's choice here is the panel kernel
+    small = [1, 8, 8, 32, 16, 3, 3, 1, 1, 1, 1]
+    for shape, hint, expect in ((small, (8, 1), None), (small, (64, 0), None), (small, (64, 5000), ERR_SHAPE),
+                                (small, (128, 0), ERR_SHAPE),     # 32 channels: not whole 16-byte groups per tap
+                                (big, (128, 3), ERR_SHAPE), (big, (128, 4), ERR_SHAPE), (big, (12, 1), ERR_SHAPE),
+                                (big, (64, 1), ERR_SHAPE)):       # 36 words do not fit a lane's registers
+        if expect is not None:  # refused on the host: nothing is launched, so fake pointers are safe
+            assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, hint[0], hint[1], NULL) == expect
 
 
 def test_binding_exposes_the_same_names():

@@ -485,6 +485,61 @@ def test_conv_fused_row_kernel_all_encodings(dlrt, oracle, shape):
                        packed_only=True)
 
 
+PANEL_KERNEL_SHAPES = [
+    # N, H, W, Ci, Co, k, stride, pad: convs the panel kernel holds (channels a multiple of 128, so that a tap is
+    # whole 16-byte groups), over one, several and ragged numbers of panels, rows beyond one wave, ragged columns
+    (1, 9, 7, 128, 32, 3, 1, 1),     # 36 words: three panels of 12
+    (2, 10, 10, 128, 20, 3, 2, 1),   # stride 2, batch 2, 20 columns: two full bytes and half a byte per plane
+    (1, 12, 12, 256, 70, 3, 1, 1),   # 72 words: six panels of 12; 70 columns: the last output word is partly filled
+    (1, 8, 6, 512, 64, 3, 1, 1),     # 144 words
+    (1, 6, 6, 128, 33, 1, 1, 0),     # a 1x1 conv runs as a GEMM over the pixels: four words, one ragged panel
+    (3, 7, 5, 640, 40, 1, 1, 0),     # twenty words: a panel of 16 and a ragged one
+    (1, 5, 5, 128, 129, 5, 2, 2),    # 5x5 taps: 100 words, padding wider than one pixel, 129 columns
+    (1, 11, 9, 256, 8, 3, 1, 0),     # eight columns: one wave across, no padding
+    (2, 9, 10, 384, 24, 2, 1, 1),    # 2x2 taps of twelve words: 48 words, divisible by both panel lengths
+    (1, 20, 20, 128, 16, 1, 2, 0),   # strided 1x1 (one tap): four words; 100 output rows
+]
+
+
+@pytest.mark.parametrize("shape", PANEL_KERNEL_SHAPES)
+def test_conv_fused_panel_kernel_all_encodings(dlrt, oracle, shape):
+    """tile_rows = 128 selects the kernel with one output row per lane that walks the reduction in panels against
+    weights held in LDS; ksplit then is the number of 8-column groups a wave covers (1, 2 or 4; 0: 1).  Every output
+    kind, and the packed-only call of a chained layer."""
+    N, H, W, Ci, Co, k, stride, pad = shape
+    cases = [(2, 2, UNSIGNED, TWOS, 2, (0, 1, 2)), (2, 1, UNSIGNED, BIPOLAR, 2, (1, 2, 4)), (1, 1, UNSIGNED, TWOS, 1, (1, 2, 4)),
+             (1, 1, UNSIGNED, BIPOLAR, 4, (2, 4)), (2, 2, TWOS, UNSIGNED, 3, (1, 2)), (1, 4, UNSIGNED, TWOS, 2, (1, 2)),
+             (4, 1, TWOS, TWOS, 2, (1, 2)), (1, 2, TWOS, TWOS, 2, (1, 4)), (3, 1, UNSIGNED, BIPOLAR, 2, (1, 2)),
+             (2, 4, UNSIGNED, TWOS, 2, (1,)), (3, 2, UNSIGNED, TWOS, 2, (1,))]
+    for idx, (abits, wbits, ea, ew, qbits, groups) in enumerate(cases):
+        x = inputs.uniform_values((N, H, W, Ci), abits, ea, 38000 + idx + H)
+        w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 39000 + idx + Ci)
+        for g in groups:
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128, ksplit=g)
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128, ksplit=g,
+                       packed_only=True)
+
+
+def test_conv_fused_panel_kernel_rejects_what_it_cannot_hold(dlrt):
+    def call(Ci, k, abits, wbits, ksplit=1):
+        x = torch.zeros((1, 8, 8, Ci), dtype=torch.uint8, device=DEV)
+        w = torch.zeros((16, k, k, Ci), dtype=torch.int8, device=DEV)
+        X, Wp = dlrt.dlrt_pack_bitplanes(x, abits, UNSIGNED), dlrt.dlrt_pack_conv_weights(w, wbits, TWOS)
+        s = torch.ones(16, device=DEV)
+        dlrt.dlrt_bitserial_conv2d_fused(X, Wp, s, None, 1, 8, 8, Ci, 16, k, k, (1, 1), (k // 2, k // 2), abits, wbits, UNSIGNED,
+                                         TWOS, qbits=2, out_q=torch.empty((1, 8, 8, 16), dtype=torch.uint8, device=DEV),
+                                         tile_rows=128, ksplit=ksplit)
+    call(128, 3, 2, 2)
+    call(256, 1, 1, 4)
+    for Ci, k, abits, wbits, ksplit in ((64, 3, 2, 2, 1),    # taps of two words
+                                        (128, 3, 3, 3, 1),   # nine accumulators per column
+                                        (128, 3, 2, 2, 4),   # thirty-two columns of four plane pairs
+                                        (128, 3, 2, 2, 3)):  # no such column count
+        with pytest.raises(dlrt.DlrtError):
+            call(Ci, k, abits, wbits, ksplit)
+    torch.cuda.synchronize()
+
+
 def test_conv_fused_row_kernel_rejects_what_it_cannot_hold(dlrt):
     def call(Ci, k, pad):
         x = torch.zeros((1, 8, 8, Ci), dtype=torch.uint8, device=DEV)
@@ -963,7 +1018,11 @@ def test_errors_raise_and_launch_nothing(dlrt):
     with pytest.raises(dlrt.DlrtError) as e:
         dlrt.dlrt_bitserial_gemm(a, a, 4, 4, 32, 2, 2, BIPOLAR, TWOS, out=out)
     assert e.value.code == 4
-    with pytest.raises(dlrt.DlrtError):
-        dlrt.dlrt_bitserial_gemm(a, a, 4, 4, 32, 2, 7, UNSIGNED, TWOS, out=out)
+    wide = torch.zeros((4, 7, 1), dtype=torch.int32, device=DEV)  # large enough for the binding's own size check
+    with pytest.raises(dlrt.DlrtError) as e:
+        dlrt.dlrt_bitserial_gemm(a, wide, 4, 4, 32, 2, 7, UNSIGNED, TWOS, out=out)
+    assert e.value.code == 2
+    with pytest.raises(ValueError):  # a weight buffer packed for fewer bits than the call names never reaches the library
+        dlrt.dlrt_bitserial_gemm(a, a, 4, 4, 32, 2, 4, UNSIGNED, TWOS, out=out)
     torch.cuda.synchronize()
     assert torch.all(out == 77)
