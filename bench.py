@@ -101,7 +101,7 @@ def measure_denominators(dev):
     ops = probe.valu_ops_per_thread_iter()
     khz = probe.wall_clock_khz()
     for waves_per_simd in (8, 2):
-        blocks, iters = 256 * waves_per_simd, 12000 // waves_per_simd  # about 1 ms either way
+        blocks, iters = 256 * waves_per_simd, 48000 // waves_per_simd  # about 4 ms either way
         clocks = torch.zeros((blocks, 2), dtype=torch.int64, device=dev)
         sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
         for _ in range(3):
@@ -476,7 +476,30 @@ def main():
             for _ in range(3):
                 only_gemm()
             torch.cuda.synchronize()
-            sweep.append(sweep_row(ab, wb, time_events(only_gemm, 20)))
+            row = sweep_row(ab, wb, time_events(only_gemm, 20))
+            if not args.no_probes and ab in (2, 4) and args.size % 128 == 0:
+                # the same kernel built with per-block clock sampling (probe library): the shader clock DURING this
+                # GEMM, from every block's lifetime on the shader-clock and the constant-rate counters
+                from paper_2207_08820_amd import probe
+
+                blocks = (cs.M // (64 if ab <= 2 else 32)) * (cs.N // (64 if wb <= 2 else 32))
+                clk = torch.zeros((blocks, 2), dtype=torch.int64, device=dev)
+                clocked = lambda: probe.gemm_clocks(ts["A"], ts["W"], ts["C"], cs.M, cs.N, cs.K, ab, wb, clk)
+                for _ in range(3):
+                    clocked()
+                torch.cuda.synchronize()
+                clocked_ms = time_events(clocked, 10)
+                c2 = clk.cpu().numpy().astype(np.float64)
+                khz = probe.wall_clock_khz()
+                if khz > 0 and np.all(c2[:, 1] > 0):
+                    mhz = float(np.median(c2[:, 0] / c2[:, 1])) * khz / 1e3
+                    ops = ab * wb * macs / 16.0
+                    row["shader_clock_mhz_during_kernel"] = round(mhz, 1)
+                    row["clocked_build_gemm_ms"] = round(clocked_ms, 5)
+                    row["frac_vs_peak_at_kernel_clock"] = round(ops / (row["gemm_ms"] * 1e-3) / (256 * 64 * mhz * 1e6), 4)
+                    log("  clock during the kernel:", row["shader_clock_mhz_during_kernel"], "MHz; fraction of 256 CU x 64 lanes at that clock:",
+                        row["frac_vs_peak_at_kernel_clock"])
+            sweep.append(row)
             if (ab, wb) == (2, 2):  # the same pair with two's-complement activations (only the sign of the MSB planes differs)
                 a_twos = torch.as_tensor(inputs.uniform_values((cs.M, cs.K), ab, inputs.TWOS, inputs.seed_for(5, 0) + 3), device=dev)
                 dlrt.dlrt_pack_bitplanes(a_twos, ab, inputs.TWOS, out=ts["A"])

@@ -50,12 +50,15 @@ def _compile(unit, extra) -> str:
 
 def build_library(extra_flags=()) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    units = UNITS + [("probe.hip", "probe.o", [])]
+    # the probe library carries the block kernel once more, with per-block clock sampling compiled in
+    probe_units = [("probe.hip", "probe.o", [])] + \
+                  [("contract.hip", f"probe_contract_a{b}.o", [f"-DDLRT_ABITS={b}", "-DDLRT_CLOCK_PROBE"]) for b in (2, 4)]
+    units = UNITS + probe_units
     with ThreadPoolExecutor(max_workers=min(len(units), os.cpu_count() or 4, 16)) as pool:
         objs = list(pool.map(lambda u: _compile(u, list(extra_flags)), units))
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-rpath,/opt/rocm/lib"]
-    subprocess.run([*link, "-o", LIB, *objs[:-1]], check=True)
-    subprocess.run([*link, "-o", PROBE_LIB, objs[-1]], check=True)
+    subprocess.run([*link, "-o", LIB, *objs[:len(UNITS)]], check=True)
+    subprocess.run([*link, "-o", PROBE_LIB, *objs[len(UNITS):]], check=True)
     return LIB
 
 

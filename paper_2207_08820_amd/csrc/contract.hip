@@ -76,6 +76,9 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     __shared__ uint4 ldsA[2 * kTileA];
     __shared__ uint4 ldsW[2 * kTileW];
 
+#ifdef DLRT_CLOCK_PROBE
+    const unsigned long long probe_c0 = clock64(), probe_r0 = wall_clock64();
+#endif
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int tilesN = (g.N + BN - 1) / BN;
@@ -398,6 +401,12 @@ __global__ __launch_bounds__(kThreads, DLRT_WAVES_PER_EU) void contract_kernel(c
     };
     if (m0 + BM <= g.M && n0 + BN <= g.N) write_tile(std::true_type{});
     else write_tile(std::false_type{});
+#ifdef DLRT_CLOCK_PROBE
+    if (g.clocks && tid == 0) {
+        g.clocks[2 * (size_t)blockIdx.x] = clock64() - probe_c0;
+        g.clocks[2 * (size_t)blockIdx.x + 1] = wall_clock64() - probe_r0;
+    }
+#endif
 }
 
 template <int B> struct LaneTile { static constexpr int value = B <= 2 ? 4 : 2; };

@@ -42,6 +42,10 @@ struct ContractArgs {
     int half_rows;      // block kernel: tiles of half the usual height (32 instead of 64 rows, 16 instead of 32)
     int xcd_split;      // block kernel: 0, or 1 + log2(c) of the r x c split (r * c = 8) of the tile grid over the 8 dies
     uint32_t a_bytes;   // panel kernel: size of the activation tensor in bytes (at most 2^31)
+    // Null in the library.  The benchmark's probe library builds the block kernel a second time with
+    // DLRT_CLOCK_PROBE: each block then leaves here how many shader-clock cycles and how many ticks of the
+    // constant-rate counter it lived ([2 * block], [2 * block + 1]), i.e. the clock the chip ran the kernel at.
+    unsigned long long *clocks;
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1

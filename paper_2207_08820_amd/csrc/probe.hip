@@ -6,11 +6,18 @@
 //                         pair per plane pair and 32 reduction elements): the lane-op rate the VALUs sustain
 //                         at a given number of waves per SIMD, and, from the shader-clock and constant-rate
 //                         counters read at both ends of the loop, the clock the chip really ran at;
+//   * dlrt_probe_gemm_clocks - the library's own block kernel (contract.hip, built a second time into this
+//                         library with DLRT_CLOCK_PROBE) on a packed GEMM, every block leaving its lifetime on
+//                         both counters: the clock during the kernel the roofline fraction is quoted for, which
+//                         differs from the clock under the register-only loop (power management);
 //   * dlrt_probe_copy   - a plain device copy: the HBM bandwidth a simple kernel reaches;
 //   * dlrt_probe_empty  - an empty kernel: the floor of a dependent launch.
 // Like the library, every call only enqueues on the caller's stream; bench.py does the timing.
 //
 //   int  dlrt_probe_valu(int blocks, int iters, uint64_t *clocks /* device, 2 per block */, uint32_t *sink /* device, 256 per block */, void *stream);
+//   int  dlrt_probe_gemm_clocks(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int K, int abits /* 2 or 4 */, int wbits,
+//                               uint64_t *clocks /* device, 2 per 64 x 64 (abits 2) or 32 x (64 / 32) tile */, void *stream);
+//                               unsigned activations, two's-complement weights, M, N multiples of 64, K of 128, 16-byte aligned
 //   int  dlrt_probe_copy(const void *src, void *dst, size_t bytes /* multiple of 16 */, void *stream);
 //   int  dlrt_probe_empty(void *stream);
 //   int  dlrt_probe_wall_clock_khz(void);     rate of the constant counter, 0 if unknown
@@ -18,6 +25,8 @@
 // Return value: 0 on success, 1 if the launch failed.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "launch.h"
 
 namespace {
 
@@ -38,6 +47,7 @@ __global__ __launch_bounds__(kThreads) void valu_probe_kernel(uint64_t *clocks, 
         for (int j = 0; j < kCols; ++j) acc[i][j] = 0;
 
     const uint64_t c0 = clock64(), r0 = wall_clock64();
+#pragma unroll 4
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < kRows; ++i) {
@@ -96,6 +106,24 @@ int dlrt_probe_valu(int blocks, int iters, uint64_t *clocks, uint32_t *sink, voi
     hipLaunchKernelGGL(valu_probe_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream), clocks,
                        sink, iters);
     return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int dlrt_probe_gemm_clocks(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int K, int abits, int wbits,
+                           uint64_t *clocks, void *stream)
+{
+    if (!A || !W || !C || !clocks || M <= 0 || N <= 0 || K <= 0 || M % 64 || N % 64 || K % 128) return 1;
+    if ((abits != 2 && abits != 4) || wbits < 1 || wbits > 4) return 1;
+    dlrt::ContractArgs g{};
+    g.A = A; g.W = W; g.M = M; g.N = N; g.Kw = K / 32;
+    g.a_msb_neg = 0; g.w_msb_neg = 1;
+    g.vec = 4;
+    g.clocks = reinterpret_cast<unsigned long long *>(clocks);
+    dlrt::FusedOut o{};
+    o.acc = C;
+    o.qbits = 1;
+    const dlrt_status st = abits == 2 ? dlrt::launch_contract_a2(g, o, wbits, false, false, static_cast<hipStream_t>(stream))
+                                      : dlrt::launch_contract_a4(g, o, wbits, false, false, static_cast<hipStream_t>(stream));
+    return st == DLRT_OK ? 0 : 1;
 }
 
 int dlrt_probe_copy(const void *src, void *dst, size_t bytes, void *stream)

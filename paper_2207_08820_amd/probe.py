@@ -25,6 +25,7 @@ def load():
         vp, i32 = ctypes.c_void_p, ctypes.c_int
         lib.dlrt_probe_valu.argtypes = [i32, i32, vp, vp, vp]
         lib.dlrt_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.dlrt_probe_gemm_clocks.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
         lib.dlrt_probe_empty.argtypes = [vp]
         _lib = lib
     return _lib
@@ -39,6 +40,19 @@ def valu(blocks: int, iters: int, clocks: torch.Tensor, sink: torch.Tensor):
     assert clocks.dtype == torch.int64 and clocks.numel() >= 2 * blocks and sink.dtype == torch.int32 and sink.numel() >= 256 * blocks
     if load().dlrt_probe_valu(blocks, iters, clocks.data_ptr(), sink.data_ptr(), _stream()):
         raise RuntimeError("dlrt_probe_valu: launch failed")
+
+
+def gemm_clocks(A: torch.Tensor, W: torch.Tensor, C: torch.Tensor, M: int, N: int, K: int, abits: int, wbits: int,
+                clocks: torch.Tensor):
+    """The library's block kernel on packed A [M, abits, K/32], W [N, wbits, K/32] (unsigned activations, two's
+    complement weights) with every block's lifetime on both counters in clocks (int64 [blocks, 2])."""
+    rows, cols = (64 if abits <= 2 else 32), (64 if wbits <= 2 else 32)
+    blocks = (M // rows) * (N // cols)
+    assert A.dtype == torch.int32 and A.numel() >= M * abits * (K // 32) and W.dtype == torch.int32 and W.numel() >= N * wbits * (K // 32)
+    assert C.dtype == torch.int32 and C.numel() >= M * N and clocks.dtype == torch.int64 and clocks.numel() >= 2 * blocks
+    if load().dlrt_probe_gemm_clocks(A.data_ptr(), W.data_ptr(), C.data_ptr(), M, N, K, abits, wbits, clocks.data_ptr(), _stream()):
+        raise RuntimeError("dlrt_probe_gemm_clocks: bad arguments or launch failed")
+    return blocks
 
 
 def copy(src: torch.Tensor, dst: torch.Tensor):
