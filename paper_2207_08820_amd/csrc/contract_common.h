@@ -127,6 +127,9 @@ __device__ __forceinline__ int fast_div(int n, uint32_t magic)
 
 // n / d where the host could not promise n * d < 2^32: magic 1 (no divisor has it) asks for the hardware's
 // division sequence instead, about ten times as many instructions.
-__device__ __forceinline__ int checked_div(int n, int d, uint32_t magic) { return magic == 1u ? n / d : fast_div(n, magic); }
+__device__ __forceinline__ int checked_div(int n, int d, uint32_t magic)
+{
+    return __builtin_expect(magic == 1u, 0) ? n / d : fast_div(n, magic);
+}
 
 }  // namespace

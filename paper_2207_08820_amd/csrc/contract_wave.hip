@@ -60,17 +60,18 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
 {
     const int which = blockIdx.y;
     const int tile = blockIdx.x;
-    // All arguments are fetched here, in one batch of scalar loads: left to itself the compiler loads each
-    // field where it is first used, and a wave that is alone on its SIMD then waits out a round trip to
-    // the scalar cache a dozen times before its first global load is even issued.
-    const ContractArgs g = pair.g[which];
-    const FusedOut o = pair.o[which];
-    const int steps_base = pair.steps_base[which], steps_rem = pair.steps_rem[which], tiles = pair.tiles[which];
-    const uint32_t magicSubN = pair.magicSubN[which];
-    const int subN = pair.subN[which], subM = pair.subM[which], die_bits = pair.die_bits[which], lc = pair.lc[which];
+    // All arguments are fetched here, in one batch of scalar loads from one base address: left to itself the
+    // compiler loads each field where it is first used, and a wave that is alone on its SIMD then waits out a
+    // round trip to the scalar cache a dozen times before its first global load is even issued.
+    const dlrt::WaveProblem &prob = pair.p[which];
+    const ContractArgs g = prob.g;
+    const FusedOut o = prob.o;
+    const int steps_base = prob.steps_base, steps_rem = prob.steps_rem, tiles = prob.tiles;
+    const uint32_t magicSubN = prob.magicSubN;
+    const int subN = prob.subN, subM = prob.subM, die_bits = prob.die_bits, lc = prob.lc;
     asm volatile("" ::"s"(subN), "s"(subM), "s"(die_bits), "s"(lc));
     asm volatile("" ::"s"(tiles), "s"(magicSubN), "s"(g.A), "s"(g.W), "s"(g.M), "s"(g.N), "s"(g.Kw), "s"(g.a_msb_neg), "s"(g.w_msb_neg), "s"(g.H),
-                 "s"(g.Wd), "s"(g.Cw), "s"(g.KW), "s"(g.Ho), "s"(g.Wo), "s"(g.sh), "s"(g.sw), "s"(g.ph), "s"(g.pw),
+                 "s"(g.Wd), "s"(g.Cw), "s"(g.KH), "s"(g.KW), "s"(g.Ho), "s"(g.Wo), "s"(g.sh), "s"(g.sw), "s"(g.ph), "s"(g.pw),
                  "s"(g.magicCw), "s"(g.magicKW), "s"(g.magicHW), "s"(g.magicWo), "s"(o.acc), "s"(o.y), "s"(o.q),
                  "s"(o.packed), "s"(o.scale), "s"(o.bias), "s"(o.qbits), "s"(steps_base), "s"(steps_rem));
     if (tile >= tiles) return;  // the other problem of the pair has more tiles
@@ -99,15 +100,60 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     const int tileM = (die >> lc) * subM + lm, tileN = (die & ((1 << lc) - 1)) * subN + ln;
     const int m0 = tileM * ROWS, n0 = tileN * 32;
 
-    // ---- staging slots: lane + 64 t; four consecutive lanes fetch the 64 contiguous bytes of one
-    // (row, plane).  Rows / columns beyond the matrix are clamped (loaded, never stored). ----
+    // this wave's slice of the reduction, in steps of 4 words.  The waves that start first (they are alone on
+    // their SIMD until the block's later waves arrive) take the odd steps, so that the waves sharing a SIMD
+    // finish together.
+    const int s_begin = ks * steps_base + min(ks, steps_rem), s_end = s_begin + steps_base + (ks < steps_rem ? 1 : 0);
+
+    // ---- staging slots: lane + 64 t; four consecutive lanes fetch the 64 contiguous bytes of one (row or
+    // column, plane).  Rows / columns beyond the matrix are clamped (loaded, never stored).  The weights come
+    // first: their addresses need no pixel arithmetic, so their first fetch is in flight while the activation
+    // side is still decoding its output pixels (a lone wave waits out every latency in full). ----
+    const uint32_t *srcW[NW];
+    int dstW[NW], k4W[NW];
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        const int s = lane + 64 * t;
+        const int k4 = s & 3, rp = s >> 2, plane = rp % WB, col = rp / WB;
+        // column c is read by lane lx = c / TN as its s = c % TN: place it so that lanes of
+        // consecutive lx read consecutive 16-byte units
+        dstW[t] = (k4 * WB + plane) * 32 + (col % TN) * LX + col / TN;
+        k4W[t] = k4;
+        srcW[t] = g.W + ((size_t)min(n0 + col, g.N - 1) * WB + plane) * g.Kw + k4 * 4;
+    }
+
+    uint4 stageA[NA], stageW[NW];
+    auto fetchW = [&](int kbase) {
+        if (kbase + 16 <= g.Kw) {  // all four steps inside the reduction: no guards
+#pragma unroll
+            for (int t = 0; t < NW; ++t) stageW[t] = load4<VEC>(srcW[t] + kbase);
+        } else {
+#pragma unroll
+            for (int t = 0; t < NW; ++t) stageW[t] = load4_tail<VEC>(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
+        }
+    };
+    fetchW(s_begin * 4);
+
+    // scale / bias of this lane's columns: fetched now so that their latency hides behind the reduction
+    float sc[TN], bs[TN];
+#pragma unroll
+    for (int s = 0; s < TN; ++s) sc[s] = bs[s] = 0.0f;
+    if (ks == 0 && o.scale) {
+#pragma unroll
+        for (int s = 0; s < TN; ++s) sc[s] = o.scale[min(n0 + lx * TN + s, g.N - 1)];
+        if (o.bias) {
+#pragma unroll
+            for (int s = 0; s < TN; ++s) bs[s] = o.bias[min(n0 + lx * TN + s, g.N - 1)];
+        }
+    }
+
     const uint32_t *srcA[NA];
     int dstA[NA], k4A[NA], ih0[NA], iw0[NA];
 #pragma unroll
     for (int t = 0; t < NA; ++t) {
         const int s = lane + 64 * t;
-        const int sc = s < UA ? s : 0;
-        const int k4 = sc & 3, rp = sc >> 2, plane = rp % AB, row = rp / AB;
+        const int slot = s < UA ? s : 0;
+        const int k4 = slot & 3, rp = slot >> 2, plane = rp % AB, row = rp / AB;
         dstA[t] = s < UA ? (k4 * AB + plane) * ROWS + row : -1;
         k4A[t] = k4;
         const int m = min(m0 + row, g.M - 1);
@@ -124,20 +170,6 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
             srcA[t] = g.A + ((size_t)m * AB + plane) * g.Kw + k4 * 4;
         }
     }
-    const uint32_t *srcW[NW];
-    int dstW[NW], k4W[NW];
-#pragma unroll
-    for (int t = 0; t < NW; ++t) {
-        const int s = lane + 64 * t;
-        const int k4 = s & 3, rp = s >> 2, plane = rp % WB, col = rp / WB;
-        // column c is read by lane lx = c / TN as its s = c % TN: place it so that lanes of
-        // consecutive lx read consecutive 16-byte units
-        dstW[t] = (k4 * WB + plane) * 32 + (col % TN) * LX + col / TN;
-        k4W[t] = k4;
-        srcW[t] = g.W + ((size_t)min(n0 + col, g.N - 1) * WB + plane) * g.Kw + k4 * 4;
-    }
-
-    uint4 stageA[NA], stageW[NW];
 
     // implicit im2col (see contract.hip): VEC words of one tap, zero outside the image / reduction
     auto tap_load = [&](int t, int kwd, uint32_t *out) {
@@ -160,7 +192,7 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
             out[0] = ok ? q : 0u;
         }
     };
-    auto fetch = [&](int kbase) {
+    auto fetchA = [&](int kbase) {
         if (CONV) {
 #pragma unroll
             for (int t = 0; t < NA; ++t) {
@@ -170,20 +202,14 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
                 stageA[t] = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
-        if (kbase + 16 <= g.Kw) {  // all four steps inside the reduction: no guards
-            if (!CONV) {
+        if (!CONV) {
+            if (kbase + 16 <= g.Kw) {
 #pragma unroll
                 for (int t = 0; t < NA; ++t) stageA[t] = load4<VEC>(srcA[t] + kbase);
-            }
-#pragma unroll
-            for (int t = 0; t < NW; ++t) stageW[t] = load4<VEC>(srcW[t] + kbase);
-        } else {
-            if (!CONV) {
+            } else {
 #pragma unroll
                 for (int t = 0; t < NA; ++t) stageA[t] = load4_tail<VEC>(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
             }
-#pragma unroll
-            for (int t = 0; t < NW; ++t) stageW[t] = load4_tail<VEC>(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
         }
     };
     auto commit = [&]() {
@@ -209,33 +235,17 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
             for (int n = 0; n < NG; ++n) acc[r][j][n] = 0;
         }
 
-    // scale / bias of this lane's columns: fetched now so that their latency hides behind the reduction
-    float sc[TN], bs[TN];
-#pragma unroll
-    for (int s = 0; s < TN; ++s) sc[s] = bs[s] = 0.0f;
-    if (ks == 0 && o.scale) {
-#pragma unroll
-        for (int s = 0; s < TN; ++s) sc[s] = o.scale[min(n0 + lx * TN + s, g.N - 1)];
-        if (o.bias) {
-#pragma unroll
-            for (int s = 0; s < TN; ++s) bs[s] = o.bias[min(n0 + lx * TN + s, g.N - 1)];
-        }
-    }
-
-    // this wave's slice of the reduction, in steps of 4 words
-    const int steps = (g.Kw + 3) / 4;
-    // The waves that start first (they are alone on their SIMD until the block's later waves arrive) take
-    // the odd steps, so that the waves sharing a SIMD finish together.
-    const int s_begin = ks * steps_base + min(ks, steps_rem), s_end = s_begin + steps_base + (ks < steps_rem ? 1 : 0);
-
     if (s_begin < s_end) {
-        fetch(s_begin * 4);
+        fetchA(s_begin * 4);
         commit();
     }
     for (int c0 = s_begin; c0 < s_end; c0 += 4) {
         const int nst = min(4, s_end - c0);
         const bool more = c0 + 4 < s_end;
-        if (more) fetch((c0 + 4) * 4);
+        if (more) {
+            fetchW((c0 + 4) * 4);
+            fetchA((c0 + 4) * 4);
+        }
 
         uint4 av[2][TM][AB], wv[2][TN][WB];
         auto lds_load = [&](int b, int k4) {
@@ -404,14 +414,14 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
         dlrt::WavePair pair{};
         int64_t tiles = 0;
         for (int i = 0; i < count; ++i) {
-            pair.g[i] = g[i];
-            pair.o[i] = o[i];
+            pair.p[i].g = g[i];
+            pair.p[i].o = o[i];
             const int steps = (g[i].Kw + 3) / 4;
-            pair.steps_base[i] = steps / ksplit;
-            pair.steps_rem[i] = steps % ksplit;
+            pair.p[i].steps_base = steps / ksplit;
+            pair.p[i].steps_rem = steps % ksplit;
             const int64_t t = (int64_t)((g[i].M + ROWS - 1) / ROWS) * ((g[i].N + 31) / 32);
             if (t > 0x7fffffffLL) return DLRT_ERR_SHAPE;
-            pair.tiles[i] = (int)t;
+            pair.p[i].tiles = (int)t;
             // split of the tile grid over the 8 dies: r x c = 8 with the least fetch among those that divide it
             const int64_t tm = (g[i].M + ROWS - 1) / ROWS, tn = (g[i].N + 31) / 32;
             int lc = -1;
@@ -422,12 +432,12 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
                 const double fetch = (double)c * g[i].M * AB + (double)r * g[i].N * WB;
                 if (lc < 0 || fetch < best) { best = fetch; lc = l; }
             }
-            pair.die_bits[i] = lc < 0 ? 0 : 3;
-            pair.lc[i] = lc < 0 ? 0 : lc;
+            pair.p[i].die_bits = lc < 0 ? 0 : 3;
+            pair.p[i].lc = lc < 0 ? 0 : lc;
             const int64_t sn = lc < 0 ? tn : tn >> lc;  // a local index < t is divided by sn
-            pair.subN[i] = (int)sn;
-            pair.subM[i] = lc < 0 ? 0 : (int)(tm >> (3 - lc));
-            pair.magicSubN[i] = t * sn >= (1LL << 32) ? 1u : sn == 1 ? 0u : (uint32_t)(((1ULL << 32) + sn - 1) / sn);
+            pair.p[i].subN = (int)sn;
+            pair.p[i].subM = lc < 0 ? 0 : (int)(tm >> (3 - lc));
+            pair.p[i].magicSubN = t * sn >= (1LL << 32) ? 1u : sn == 1 ? 0u : (uint32_t)(((1ULL << 32) + sn - 1) / sn);
             if (t > tiles) tiles = t;
         }
         const size_t lds_bytes = (size_t)ksplit * units * 16;

@@ -59,18 +59,22 @@ dlrt_status launch_contract_a3(const ContractArgs &g, const FusedOut &o, int wbi
 dlrt_status launch_contract_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, hipStream_t stream);
 
 // Kernel argument of the per-wave kernel: one problem, or two of the same bit widths in one launch.
-// blockIdx.y names the problem, so a wave knows from its first instruction where its arguments lie and
-// fetches them in one round trip; the grid is as wide as the larger problem and the surplus blocks of
-// the smaller one leave at once.
-struct WavePair {
-    ContractArgs g[2];
-    FusedOut o[2];
-    int steps_base[2], steps_rem[2];  // 4-word steps per wave: base, and one more for the first `rem` waves
-    int tiles[2];
+// blockIdx.y names the problem, so a wave knows from its first instruction where its arguments lie; everything a
+// problem needs sits in ONE struct so that the wave fetches it in a single batch of scalar loads from one base
+// address (a lone wave pays every round trip to the scalar cache in full).  The grid is as wide as the larger
+// problem and the surplus blocks of the smaller one leave at once.
+struct WaveProblem {
+    ContractArgs g;
+    FusedOut o;
+    int steps_base, steps_rem;  // 4-word steps per wave: base, and one more for the first `rem` waves
+    int tiles;
     // tile index -> tile: the low die_bits bits pick one of r x c parts of the tile grid (c = 2^lc), the rest a
     // tile inside it, row-major over subN columns (die_bits = lc = 0, subN = ceil(N / 32): plain row-major order)
-    int die_bits[2], lc[2], subN[2], subM[2];
-    uint32_t magicSubN[2];  // for (tile >> die_bits) / subN; same convention as ContractArgs::magicHW
+    int die_bits, lc, subN, subM;
+    uint32_t magicSubN;  // for (tile >> die_bits) / subN; same convention as ContractArgs::magicHW
+};
+struct WavePair {
+    WaveProblem p[2];
 };
 
 // Per-wave kernel (contract_wave.hip with -DDLRT_ABITS=n); g / o point at `count` (1 or 2) problems.
