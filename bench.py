@@ -20,6 +20,7 @@ import numpy as np
 
 # plain 32-bit VALU rate of the chip: 256 compute units x 64 lanes per clock x 2.4 GHz
 VALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
+HBM_PEAK_BYTES = 8e12
 # HBM bytes per launch of the 4096^3 A2W2 GEMM kernel come from the committed rocprofv3 --pmc summary
 # (counters cannot be read from inside this script): its FETCH_SIZE / WRITE_SIZE table, KiB per dispatch,
 # each scaled by what the same counter reads for a plain copy of known size in the same file.
@@ -137,6 +138,31 @@ def measure_denominators(dev):
     return out
 
 
+def pack_bandwidth(dlrt, dev, launch_floor_us):
+    """The bitplane packer (HBM bound) where bandwidth binds: uint8 -> 2 planes at 20 MiB of traffic (the headline
+    GEMM's operand, a launch-bound size), 160 MiB (inside the 256 MB last-level cache once warm) and 640 MiB
+    (beyond it: HBM proper).  Algorithmic bytes = rows * K * (1 + 2 / 8)."""
+    import torch
+
+    rows_out = []
+    for rows, K in ((4096, 4096), (16384, 8192), (32768, 16384)):
+        src = torch.randint(0, 4, (rows, K), dtype=torch.uint8, device=dev)
+        out = torch.empty((rows, 2, K // 32), dtype=torch.int32, device=dev)
+        fn = lambda: dlrt.dlrt_pack_bitplanes(src, 2, 0, out=out)
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ms = min(time_events(fn, 10) for _ in range(3))
+        nbytes = rows * K * 1.25
+        row = {"rows": rows, "K": K, "MiB": round(nbytes / 2 ** 20, 1), "us": round(ms * 1e3, 2),
+               "TBps": round(nbytes / (ms * 1e-3) / 1e12, 3), "frac_of_8_TBps": round(nbytes / (ms * 1e-3) / HBM_PEAK_BYTES, 4)}
+        if launch_floor_us:
+            row["launch_floor_us"] = launch_floor_us
+        rows_out.append(row)
+        del src, out
+    return rows_out
+
+
 def gemm_workload(abits, wbits, size, dev):
     import torch
 
@@ -181,9 +207,6 @@ def make_step(dlrt, t, gemm_events=None, fused=True):
             dlrt.dlrt_epilogue_f32(t["C"], t["scale"], out_f32=t["Y"])
 
     return step
-
-
-HBM_PEAK_BYTES = 8e12
 
 
 def layer_floors(L, abits, wbits, qbits, batch=1):
@@ -431,6 +454,9 @@ def main():
         extra[name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()}
         extra[name + "_per_layer"] = per_layer
         log(f"{name}: {res}")
+
+    extra["pack_kernel_u8_to_2_planes"] = pack_bandwidth(dlrt, dev, floor_us)
+    log("pack kernel:", extra["pack_kernel_u8_to_2_planes"])
 
     # comparison variant (not the judged path): the same GEMM on the unpacked int8 values with matrix instructions
     a_i8 = t["a"].view(torch.int8)
