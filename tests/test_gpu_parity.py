@@ -629,9 +629,7 @@ def test_gemm_fused_large_shapes(dlrt, oracle, abits, wbits, ea, ew, qbits, M, N
     assert dlrt.dlrt_query_plan(M, N, K, abits, wbits)["kernel"] == "block"
     a = inputs.uniform_values((M, K), abits, ea, 41000 + M)
     w = inputs.uniform_values((N, K), wbits, ew, 42000 + N)
-    ref = (a.astype(np.int64) @ w.astype(np.int64).T).astype(np.int32)
-    rows = rng(M).choice(M, size=16, replace=False)
-    assert np.array_equal(ref[rows], oracle.gemm_i32(a[rows], w))  # the numpy product is only a stand-in for speed
+    ref = oracle.gemm_i32(a, w)  # every output against the oracle
     scale, bias = calibrate(ref)
     scale, bias = (scale * (1 << qbits) / 4).astype(np.float32), (bias * (1 << qbits) / 4).astype(np.float32)
     y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=qbits)
@@ -983,9 +981,7 @@ def test_gemm_ragged_large_shape_block_kernel(dlrt, oracle):
         a = inputs.uniform_values((M, K), abits, ea, 31000 + M)
         w = inputs.uniform_values((N, K), wbits, ew, 32000 + N)
         got = gpu_gemm(dlrt, a, w, abits, wbits, ea, ew)
-        assert np.array_equal(got, a.astype(np.int64) @ w.astype(np.int64).T), (abits, wbits)
-        rows = rng(M).choice(M, size=16, replace=False)
-        assert np.array_equal(got[rows], oracle.gemm_i32(a[rows], w))
+        assert np.array_equal(got, oracle.gemm_i32(a, w)), (abits, wbits)  # every output against the oracle
 
 
 # ---- comparison variant: int8 matrix-instruction GEMM on the unpacked values ----------------------------
