@@ -29,8 +29,8 @@
 // zero padding costs one select per 16-byte group instead of one per word, and the addresses are 32-bit.
 //
 // Limits (checked by the launcher, contract_dispatch.hip): reduction words a multiple of 4 and 16-byte aligned
-// operands; for a convolution a whole number of 4-word groups per tap (channels a multiple of 128) and fewer
-// than 2^24 pixels per image; activations of at most 2^31 bytes; NC * abits * wbits <= 64 accumulators.
+// operands; for a convolution a whole number of 4-word groups per tap (channels a multiple of 128); activations
+// of at most 2^31 bytes; NC * abits * wbits <= 64 accumulators.
 //
 // Compiled once per activation bit width (-DDLRT_ABITS=1..4), like contract.hip.
 #include <hip/hip_runtime.h>
@@ -114,11 +114,14 @@ __device__ inline u32x4 load16(BufferResource, uint32_t) { return u32x4{0u, 0u, 
 #endif
 
 template <int AB, int WB, int NC, int P, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g, const FusedOut o, const int panels)
+__global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g, const FusedOut o, const int panels,
+                                                            const uint32_t magic_groups /* for division by panels * P / 4 */)
 {
     static_assert(P % 4 == 0 && NC % 8 == 0, "panels of whole 16-byte groups, whole output bytes");
     constexpr int G = P / 4;                 // 16-byte groups per panel and plane
-    extern __shared__ uint4 lds[];           // [NC][WB][panels * G] groups: the wave's weights, zero beyond Kw / N
+    // The wave's weights, zero beyond Kw / N: [panel][NC * WB][G] groups, so that within a panel every read is
+    // the panel's base address plus a compile-time offset.
+    extern __shared__ uint4 lds[];
 
     const int lane = threadIdx.x;
     const int kg = g.Kw >> 2;                // groups of the reduction
@@ -135,19 +138,17 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
     const int n0 = col_group * NC;
     const bool row_ok = m < g.M;
 
-    // ---- the wave's weights -> LDS.  Columns n0 .. n0 + NC - 1 are one contiguous run of the packed tensor. ----
+    // ---- the wave's weights -> LDS.  Columns n0 .. n0 + NC - 1 are one contiguous run of the packed tensor,
+    // [column][plane][group]; group k of (column, plane) ci goes to panel k / G, slot ci * G + k % G. ----
     {
         const uint4 *src = reinterpret_cast<const uint4 *>(g.W) + (size_t)n0 * WB * kg;
         const int cols = min(NC, g.N - n0);
-        if (kg_pad == kg && cols == NC) {
-            for (int u = lane; u < NC * WB * kg; u += 64) lds[u] = src[u];
-        } else {
-            for (int u = lane; u < NC * WB * kg_pad; u += 64) {
-                const int ci = u / kg_pad, k = u - ci * kg_pad;  // (column, plane) pair and group
-                const bool ok = k < kg && ci < cols * WB;
-                const uint4 q = src[ok ? ci * kg + k : 0];
-                lds[u] = ok ? q : make_uint4(0u, 0u, 0u, 0u);
-            }
+        for (int u = lane; u < NC * WB * kg_pad; u += 64) {
+            const int ci = fast_div(u, magic_groups), k = u - ci * kg_pad;  // (column, plane) pair, group of the padded reduction
+            const bool ok = k < kg && ci < cols * WB;
+            const uint4 q = src[ok ? ci * kg + k : 0];
+            const int panel = k / G;
+            lds[(panel * (NC * WB) + ci) * G + (k - panel * G)] = ok ? q : make_uint4(0u, 0u, 0u, 0u);
         }
         // read back by the other lanes of this wave only
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -174,6 +175,9 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
         lane_base = (uint32_t)mc * (uint32_t)(AB * g.Kw * 4);
     }
     const uint32_t pixel_bytes = AB * g.Cw * 4;
+    // byte offset of the lane's tap (0, 0), which may lie outside the image (the sum wraps; only taps inside the
+    // image are ever used, and for those the per-tap delta brings it back in range)
+    const uint32_t tap00 = lane_base + ((uint32_t)ih0 * (uint32_t)g.Wd + (uint32_t)iw0) * pixel_bytes;
 
     int acc[NC][AB][WB];
 #pragma unroll
@@ -200,9 +204,9 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
                 const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;  // all uniform: the scalar unit's work
                 const int ih = ih0 + kh, iw = iw0 + kw;
                 const bool ok = k < g.Kw && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
-                // fewer than 2^24 pixels per image and fewer than 2^24 bytes per pixel: 24-bit multiplies are exact
-                const uint32_t pixel = __umul24((uint32_t)ih, (uint32_t)g.Wd) + (uint32_t)iw;
-                offset = ok ? lane_base + __umul24(pixel, pixel_bytes) + 4u * cw : kOutOfRange;
+                // (kh * W + kw) pixels and cw words further than tap (0, 0): a uniform delta, one add per lane
+                const uint32_t delta = (uint32_t)(kh * g.Wd + kw) * pixel_bytes + 4u * cw;
+                offset = ok ? tap00 + delta : kOutOfRange;
             } else {
                 offset = k < g.Kw ? lane_base + 4u * k : kOutOfRange;
             }
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
 
         // ---- against every column and weight plane of the wave: the (column, plane)'s P words come from LDS as
         // broadcast reads, fetched one (column, plane) ahead of the one being multiplied ----
-        const uint4 *wl = lds + p * G;
+        const uint4 *wl = lds + p * (NC * WB * G);
         uint4 wbuf[2][G];
 #pragma unroll
         for (int q = 0; q < G; ++q) wbuf[0][q] = wl[q];
@@ -230,7 +234,7 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
             const int c = ci / WB, i = ci - c * WB;
             if (ci + 1 < NC * WB) {
 #pragma unroll
-                for (int q = 0; q < G; ++q) wbuf[(ci + 1) & 1][q] = wl[(ci + 1) * kg_pad + q];
+                for (int q = 0; q < G; ++q) wbuf[(ci + 1) & 1][q] = wl[(ci + 1) * G + q];
             }
 #pragma unroll
             for (int j = 0; j < AB; ++j)
@@ -326,8 +330,10 @@ dlrt_status launch_one(const ContractArgs &g, const FusedOut &o, hipStream_t str
     const int64_t bx = ((int64_t)g.M + 63) / 64, by = (g.N + NC - 1) / NC;
     const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies
     if (blocks > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    const uint32_t groups = (uint32_t)panels * (P / 4);  // ceil(2^32 / groups), 0 standing for a divisor of 1
+    const uint32_t magic_groups = groups == 1 ? 0u : (uint32_t)((0x100000000ULL + groups - 1) / groups);
     return dlrt::enqueue(contract_panel_kernel<AB, WB, NC, P, BIPOLAR, CONV>, dim3((unsigned)blocks), dim3(64), lds_bytes,
-                         stream, g, o, panels);
+                         stream, g, o, panels, magic_groups);
 }
 
 template <int WB, int NC, bool BIPOLAR, bool CONV>

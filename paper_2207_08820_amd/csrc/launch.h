@@ -98,7 +98,7 @@ dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, 
 // walked in panels of 12 or 16 words against weights held in LDS; for long reductions with many rows.  ncols is
 // 8, 16 or 32 with ncols * abits * wbits <= 64 accumulators per lane.  Needs Kw % 4 == 0 and 16-byte aligned
 // operands (vec == 4), at most 64 KB of weights per wave, an activation tensor of at most 2^31 bytes (g.a_bytes),
-// and for a convolution Cw % 4 == 0 and fewer than 2^24 pixels per image.
+// and for a convolution Cw % 4 == 0.
 inline bool panel_kernel_has(const ContractArgs &g, int abits, int wbits, bool conv, int ncols, int64_t a_bytes)
 {
     if (ncols != 8 && ncols != 16 && ncols != 32) return false;
@@ -106,7 +106,7 @@ inline bool panel_kernel_has(const ContractArgs &g, int abits, int wbits, bool c
     const int64_t padded = (int64_t)((g.Kw + p - 1) / p) * p;  // words per column and plane
     if (g.Kw % 4 != 0 || g.vec != 4 || ncols * abits * wbits > 64 || ncols * wbits * padded * 4 > 65536) return false;
     if (a_bytes > (1LL << 31)) return false;
-    return !conv || (g.Cw % 4 == 0 && (int64_t)g.H * g.Wd < (1 << 24));
+    return !conv || g.Cw % 4 == 0;
 }
 dlrt_status launch_panels_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 dlrt_status launch_panels_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
