@@ -474,6 +474,21 @@ def main():
                                       "speedup_over_bit_serial_a2w2_kernel": round(gemm_ms / mfma_ms, 2)}
     log("unpacked int8 MFMA GEMM (comparison):", extra["unpacked_i8_mfma_gemm"])
 
+    # second comparison variant: unpacked signed 4-bit values with the VALU's 8-way dot product (peak 16 ops per lane-op)
+    a4, w4 = dlrt.dlrt_pack_nibbles(a_i8), dlrt.dlrt_pack_nibbles(t["w"])
+
+    def dot8():
+        dlrt.dlrt_unpacked_gemm_i4(a4, w4, c.K, out=t["C"])
+
+    for _ in range(3):
+        dot8()
+    torch.cuda.synchronize()
+    dot8_ms = time_events(dot8, 20)
+    extra["unpacked_i4_dot8_gemm"] = {"ms": round(dot8_ms, 5), "effective_tops": round(2.0 * macs / (dot8_ms * 1e-3) / 1e12, 1),
+                                      "frac_of_dot8_valu_peak_629_TOPS": round(2.0 * macs / (dot8_ms * 1e-3) / (16 * VALU_PEAK_LANE_OPS), 4),
+                                      "speedup_over_bit_serial_a2w2_kernel": round(gemm_ms / dot8_ms, 2)}
+    log("unpacked int4 dot8 GEMM (comparison):", extra["unpacked_i4_dot8_gemm"])
+
     if not args.no_sweep:
         from paper_2207_08820_amd import inputs
 

@@ -228,6 +228,20 @@ dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, 
                                   int64_t K, void *stream);
 
 /*
+ * Second comparison variant, not the bit-serial path: the same integer GEMM on unpacked SIGNED 4-bit values (one
+ * per nibble) with the VALU's eight-way dot-product instruction.  Section V's bit-serial sum costs
+ * abits * wbits / 16 lane-ops per multiply-add, this instruction 1 / 8 at any width up to 4 bits: the yardstick
+ * for where bit-serial arithmetic stops paying on this chip's vector units.
+ *   dlrt_pack_nibbles: src int8 [rows][K] with values in [-8, 7] -> dst words [rows][K / 8], element k in bits
+ *                      4 (k % 8) .. 4 (k % 8) + 3 of word k / 8 (the low four bits of its two's-complement pattern).
+ *   dlrt_unpacked_gemm_i4: C[m][n] = sum_k A[m][k] * W[n][k], int32, row-major, leading dimension N, on such words.
+ * K must be a multiple of 32 (DLRT_ERR_SHAPE otherwise) and src, dst, A, W 16-byte aligned (DLRT_ERR_ALIGN).
+ */
+dlrt_status dlrt_pack_nibbles(const int8_t *src, int64_t rows, int64_t K, uint32_t *dst, void *stream);
+dlrt_status dlrt_unpacked_gemm_i4(const uint32_t *A, const uint32_t *W, int32_t *C, int64_t M, int64_t N,
+                                  int64_t K, void *stream);
+
+/*
  * Dequantize / requantize epilogue (Section IV: t_hat = t_bar * s, then the quantizer again for
  * the next layer), per output channel:
  *   y = fmaf((float)acc[r][c], scale[c], bias ? bias[c] : 0.0f)          -> out_f32 (may be NULL)

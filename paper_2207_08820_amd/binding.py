@@ -71,6 +71,10 @@ def load():
     lib.dlrt_query_plan.argtypes = [i64, i64, i64, i32, i32] + [ctypes.POINTER(ctypes.c_int)] * 4
     lib.dlrt_unpacked_gemm_i8.restype = i32
     lib.dlrt_unpacked_gemm_i8.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+    lib.dlrt_pack_nibbles.restype = i32
+    lib.dlrt_pack_nibbles.argtypes = [vp, i64, i64, vp, vp]
+    lib.dlrt_unpacked_gemm_i4.restype = i32
+    lib.dlrt_unpacked_gemm_i4.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     lib.dlrt_epilogue_f32.restype = i32
     lib.dlrt_epilogue_f32.argtypes = [vp, vp, vp, i64, i32, vp, vp, i32, vp]
     _lib = lib
@@ -288,6 +292,31 @@ def dlrt_unpacked_gemm_i8(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor | 
         raise ValueError(f"W: reduction length {W.shape[1]} differs from A's {K}")
     _expect(out, torch.int32, M * N, "out")
     _check(lib.dlrt_unpacked_gemm_i8(_ptr(A), _ptr(W), _ptr(out), M, N, K, _stream()), "dlrt_unpacked_gemm_i8")
+    return out
+
+
+def dlrt_pack_nibbles(src: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Comparison variant: int8 values in [-8, 7], [rows, K] -> int32 words [rows, K / 8], one signed nibble per element."""
+    lib = load()
+    rows, K = src.shape
+    if out is None:
+        out = torch.empty((rows, K // 8), dtype=torch.int32, device=src.device)
+    _expect(src, (torch.int8, torch.uint8), rows * K, "src")
+    _expect(out, torch.int32, rows * (K // 8), "out")
+    _check(lib.dlrt_pack_nibbles(_ptr(src), rows, K, _ptr(out), _stream()), "dlrt_pack_nibbles")
+    return out
+
+
+def dlrt_unpacked_gemm_i4(A: torch.Tensor, W: torch.Tensor, K: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Comparison variant: nibble-packed A [M, K / 8], W [N, K / 8] (dlrt_pack_nibbles) -> int32 [M, N]."""
+    lib = load()
+    M, N = A.shape[0], W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _expect(A, torch.int32, M * (K // 8), "A")
+    _expect(W, torch.int32, N * (K // 8), "W")
+    _expect(out, torch.int32, M * N, "out")
+    _check(lib.dlrt_unpacked_gemm_i4(_ptr(A), _ptr(W), _ptr(out), M, N, K, _stream()), "dlrt_unpacked_gemm_i4")
     return out
 
 

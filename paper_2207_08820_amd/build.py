@@ -19,7 +19,8 @@ LIB = os.path.join(HERE, "libdlrt_hip.so")
 PROBE_LIB = os.path.join(HERE, "libdlrt_probe.so")
 # (source, object name, extra defines); the contraction kernels are built once per activation bit width
 UNITS = [("api.hip", "api.o", []), ("pack.hip", "pack.o", []), ("epilogue.hip", "epilogue.o", []),
-         ("contract_dispatch.hip", "contract_dispatch.o", []), ("unpacked_mfma.hip", "unpacked_mfma.o", [])] + \
+         ("contract_dispatch.hip", "contract_dispatch.o", []), ("unpacked_mfma.hip", "unpacked_mfma.o", []),
+         ("unpacked_dot8.hip", "unpacked_dot8.o", [])] + \
         [("contract_rows.hip", f"contract_rows_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)] + \
         [("contract.hip", f"contract_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)] + \
         [("contract_wave.hip", f"contract_wave_a{b}.o", [f"-DDLRT_ABITS={b}"]) for b in (1, 2, 3, 4)] + \

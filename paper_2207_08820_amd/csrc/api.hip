@@ -246,6 +246,25 @@ dlrt_status dlrt_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, 
     return dlrt::launch_unpacked_gemm_i8(A, W, C, (int)M, (int)N, (int)K, as_stream(stream));
 }
 
+dlrt_status dlrt_pack_nibbles(const int8_t *src, int64_t rows, int64_t K, uint32_t *dst, void *stream)
+{
+    if (!src || !dst) return DLRT_ERR_NULL;
+    if (rows <= 0 || K <= 0 || K % 32 != 0) return DLRT_ERR_SHAPE;
+    if (rows > kMaxDim || K > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return DLRT_ERR_ALIGN;
+    return dlrt::launch_pack_nibbles(src, rows, K, dst, as_stream(stream));
+}
+
+dlrt_status dlrt_unpacked_gemm_i4(const uint32_t *A, const uint32_t *W, int32_t *C, int64_t M, int64_t N, int64_t K,
+                                  void *stream)
+{
+    if (!A || !W || !C) return DLRT_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || K % 32 != 0) return DLRT_ERR_SHAPE;
+    if (M > kMaxDim || N > kMaxDim || K > 0x7fffffff) return DLRT_ERR_SHAPE;
+    if (!aligned16(A) || !aligned16(W)) return DLRT_ERR_ALIGN;
+    return dlrt::launch_unpacked_gemm_i4(A, W, C, (int)M, (int)N, (int)K, as_stream(stream));
+}
+
 dlrt_status dlrt_epilogue_f32(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
                               float *out_f32, uint8_t *out_q, int qbits, void *stream)
 {

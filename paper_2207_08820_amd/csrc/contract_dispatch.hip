@@ -164,7 +164,7 @@ bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits)
     if (!dlrt::row_kernel_has(Kw) || (Kw > 16 && wbits > 2)) return false;
     if (M < 2048) return false;  // lanes idle on few rows (none measured below 3136)
     if (((M + 63) / 64 + 7) * ((N + 31) / 32) > 0x7fffffffLL) return false;  // more blocks than a grid holds
-    const int64_t from = Kw == 1 ? 256 : Kw == 2 ? 384 : Kw <= 4 ? 1024 : Kw <= 8 ? 3072 : Kw == 9 ? 1536 : Kw <= 16 ? 12288 : 4096;
+    const int64_t from = Kw == 1 ? 256 : Kw == 2 ? 384 : Kw <= 4 ? 1024 : Kw <= 9 ? 1536 : Kw <= 16 ? 12288 : 3072;
     return row_kernel_waves(M, N) >= from;
 }
 

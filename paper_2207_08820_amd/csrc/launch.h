@@ -158,6 +158,10 @@ dlrt_status launch_pack(const PackArgs &p, hipStream_t stream);
 dlrt_status launch_unpacked_gemm_i8(const int8_t *A, const int8_t *W, int32_t *C, int M, int N, int K,
                                     hipStream_t stream);
 
+// 8-way dot-product GEMM on unpacked signed 4-bit values (comparison variant); K % 32 == 0, 16-byte aligned rows.
+dlrt_status launch_unpacked_gemm_i4(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int K, hipStream_t stream);
+dlrt_status launch_pack_nibbles(const int8_t *src, int64_t rows, int64_t K, uint32_t *dst, hipStream_t stream);
+
 dlrt_status launch_epilogue(const int32_t *acc, const float *scale, const float *bias, int64_t rows, int C,
                             float *out_f32, uint8_t *out_q, int qbits, hipStream_t stream);
 

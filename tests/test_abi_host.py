@@ -44,7 +44,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["dlrt_bitserial_conv2d", "dlrt_bitserial_conv2d_fused", "dlrt_bitserial_conv2d_fused_pair", "dlrt_bitserial_gemm", "dlrt_bitserial_gemm_fused", "dlrt_epilogue_f32", "dlrt_pack_bitplanes",
-                     "dlrt_pack_conv_weights", "dlrt_pack_conv_weights_per_channel", "dlrt_packed_words", "dlrt_query_plan", "dlrt_status_string", "dlrt_unpacked_gemm_i8"]
+                     "dlrt_pack_conv_weights", "dlrt_pack_conv_weights_per_channel", "dlrt_pack_nibbles", "dlrt_packed_words", "dlrt_query_plan", "dlrt_status_string",
+                     "dlrt_unpacked_gemm_i4", "dlrt_unpacked_gemm_i8"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -116,6 +117,17 @@ def test_unpacked_gemm_rejects_bad_arguments_before_launch(lib):
     assert u(FAKE, FAKE, FAKE, 4, 4, 40, NULL) == ERR_SHAPE  # K not a multiple of 16
     assert u(FAKE, FAKE, FAKE, 0, 4, 64, NULL) == ERR_SHAPE
     assert u(FAKE + 8, FAKE, FAKE, 4, 4, 64, NULL) == ERR_ALIGN
+    lib.dlrt_unpacked_gemm_i4.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int64] * 3 + [ctypes.c_void_p]
+    u4 = lib.dlrt_unpacked_gemm_i4
+    assert u4(FAKE, NULL, FAKE, 4, 4, 64, NULL) == ERR_NULL
+    assert u4(FAKE, FAKE, FAKE, 4, 4, 48, NULL) == ERR_SHAPE  # K not a multiple of 32
+    assert u4(FAKE, FAKE + 8, FAKE, 4, 4, 64, NULL) == ERR_ALIGN
+    lib.dlrt_pack_nibbles.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+    pn = lib.dlrt_pack_nibbles
+    assert pn(NULL, 4, 64, FAKE, NULL) == ERR_NULL
+    assert pn(FAKE, 4, 40, FAKE, NULL) == ERR_SHAPE
+    assert pn(FAKE, 0, 64, FAKE, NULL) == ERR_SHAPE
+    assert pn(FAKE + 4, 4, 64, FAKE, NULL) == ERR_ALIGN
 
 
 def test_pack_and_epilogue_reject_bad_arguments_before_launch(lib):

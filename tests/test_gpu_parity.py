@@ -1007,6 +1007,30 @@ def test_unpacked_gemm_i8_agrees_with_the_bit_serial_gemm_at_full_size(dlrt, ora
     assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("M,N,K", [(128, 128, 256), (1, 1, 32), (200, 300, 224), (130, 70, 1056), (257, 129, 4096)])
+def test_unpacked_gemm_i4_matches_oracle(dlrt, oracle, M, N, K):
+    """The 8-way dot-product variant on signed 4-bit values: every value of [-8, 7] on both sides, ragged tiles,
+    reductions that are not whole 256-element chunks."""
+    r = rng(M * 11 + N)
+    a = r.integers(-8, 8, size=(M, K)).astype(np.int8)
+    w = r.integers(-8, 8, size=(N, K)).astype(np.int8)
+    A4, W4 = dlrt.dlrt_pack_nibbles(dev(a)), dlrt.dlrt_pack_nibbles(dev(w))
+    got = dlrt.dlrt_unpacked_gemm_i4(A4, W4, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.gemm_i32(a, w))
+
+
+def test_unpacked_gemm_i4_agrees_with_the_bit_serial_gemm_at_full_size(dlrt, oracle):
+    c, a, w = inputs.config5(2, 2)
+    got = dlrt.dlrt_unpacked_gemm_i4(dlrt.dlrt_pack_nibbles(dev(a.astype(np.int8))), dlrt.dlrt_pack_nibbles(dev(w)), c.K)
+    ref = gpu_gemm(dlrt, a, w, 2, 2, c.enc_a, c.enc_w)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    rows = rng(57).choice(c.M, size=32, replace=False)
+    assert np.array_equal(got[rows], oracle.gemm_i32(a[rows], w))
+    assert np.array_equal(got, ref)
+
+
 # ---- error handling with real buffers ------------------------------------------------------------------
 def test_errors_raise_and_launch_nothing(dlrt):
     a = torch.zeros((4, 2, 1), dtype=torch.int32, device=DEV)
