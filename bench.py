@@ -85,6 +85,7 @@ def time_graph(fn, reps=20, replays=5):
             fn()
     graph.replay()
     torch.cuda.synchronize()
+    time_events(graph.replay, replays)  # discarded: the first pass after an idle spell runs at a clock still ramping up
     return time_events(graph.replay, replays) / reps
 
 
@@ -253,9 +254,7 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_
         torch.cuda.synchronize()
         return {}, [{"layer": pl.spec.name, "M": batch * pl.spec.M, "N": pl.spec.Co, "K": pl.spec.K} for pl in stack.layers]
     stack.capture(x0)
-    for _ in range(5):
-        stack.replay()
-    torch.cuda.synchronize()
+    time_events(stack.replay, iters)  # warm-up, discarded (the first pass after the host-side set-up measured 0.4 to 3 % slow)
     out["graph_fused_ms"] = time_events(stack.replay, iters)
     out["eager_fused_ms"] = time_events(lambda: stack.run(x0), iters)
     per_layer = []
@@ -276,10 +275,15 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_
     out["sum_bound_us"] = round(sum(p["bound_us"] for p in per_layer), 3)
     if batch > 1:
         macs = batch * sum(L.macs for L in layers)
+        # With kernels of tens of microseconds the host keeps ahead of the GPU, and the eagerly enqueued chain
+        # measured 0.5 to 1.6 % FASTER than the graph's replay: the batched figures are of the faster of the two.
+        best = min(out["graph_fused_ms"], out["eager_fused_ms"])
         out["batch"] = batch
-        out["images_per_s"] = batch / (out["graph_fused_ms"] * 1e-3)
-        out["effective_tops"] = 2.0 * macs / (out["graph_fused_ms"] * 1e-3) / 1e12
-        out["valu_frac"] = out["sum_valu_floor_us"] / (out["graph_fused_ms"] * 1e3)
+        out["fused_ms"] = best
+        out["launched"] = "graph" if best == out["graph_fused_ms"] else "eager"
+        out["images_per_s"] = batch / (best * 1e-3)
+        out["effective_tops"] = 2.0 * macs / (best * 1e-3) / 1e12
+        out["valu_frac"] = out["sum_valu_floor_us"] / (best * 1e3)
         return out, per_layer
 
     unfused = ConvStack(layers, weights, scales, biases, 2, wbits, enc_w, device=dev, fused=False)

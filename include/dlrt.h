@@ -155,7 +155,9 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
  * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  tile_rows = 64 asks for the row kernel (one output
  * pixel per lane; convolutions with KH*KW*ceil(Ci/32) <= 16 or = 18, DLRT_ERR_SHAPE otherwise);
- * ksplit then is the number of 32-column groups a wave covers (0: planned).  tile_rows = 128 asks for the panel
+ * ksplit then is the number of 8-column groups a wave covers (0: planned; 4 n for whole output words, or 1 or 2,
+ * which need Co a multiple of 32, unsigned activations and no output but out_packed; DLRT_ERR_SHAPE
+ * otherwise).  tile_rows = 128 asks for the panel
  * kernel (one output pixel per lane, the reduction walked in panels against weights held in LDS; needs Ci a
  * multiple of 128, abits * wbits * 8 * ksplit <= 64 and at most 2^31 bytes of activations, DLRT_ERR_SHAPE
  * otherwise); ksplit (0 or 1, 2, 4) then is the number of 8-column groups a wave covers.  The result does not
@@ -205,7 +207,9 @@ dlrt_status dlrt_bitserial_conv2d_fused_pair(const dlrt_conv_problem *first, con
  *   *block_kernel = 0: the latency kernel (one wave per tile_rows x 32 tile, ksplit waves split K)
  *   *block_kernel = 2: the row kernel (one output row per lane: a wave covers 64 rows x tile_cols columns);
  *                      taken when the reduction is at most 16 packed words (or 18) and the problem has
- *                      enough 64-row x 32-column waves for that reduction length.
+ *                      enough 64-row x 32-column waves for that reduction length.  tile_cols is the answer for
+ *                      a call that writes only out_packed from unsigned activations (16 columns are possible
+ *                      there); any other call gets whole words, at least 32.
  *   *block_kernel = 3: the panel kernel (one output row per lane, 64 rows x tile_cols columns per wave, the
  *                      reduction walked in panels against weights in LDS); taken for long reductions with
  *                      many rows.  The answer assumes 16-byte aligned operands and, for a convolution, a

@@ -57,13 +57,13 @@ dlrt_status launch_rows(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, in
 }
 
 dlrt_status launch_panels(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
-                          bool conv, int ncols, hipStream_t stream)
+                          bool conv, int ncols, int kwaves, hipStream_t stream)
 {
     switch (abits) {
-    case 1: return dlrt::launch_panels_a1(g, o, wbits, bipolar, conv, ncols, stream);
-    case 2: return dlrt::launch_panels_a2(g, o, wbits, bipolar, conv, ncols, stream);
-    case 3: return dlrt::launch_panels_a3(g, o, wbits, bipolar, conv, ncols, stream);
-    case 4: return dlrt::launch_panels_a4(g, o, wbits, bipolar, conv, ncols, stream);
+    case 1: return dlrt::launch_panels_a1(g, o, wbits, bipolar, conv, ncols, kwaves, stream);
+    case 2: return dlrt::launch_panels_a2(g, o, wbits, bipolar, conv, ncols, kwaves, stream);
+    case 3: return dlrt::launch_panels_a3(g, o, wbits, bipolar, conv, ncols, kwaves, stream);
+    case 4: return dlrt::launch_panels_a4(g, o, wbits, bipolar, conv, ncols, kwaves, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -183,13 +183,49 @@ bool prefer_panel_kernel(int64_t M, int N, int Kw, int abits, int wbits)
            block_tiles((int)M, N, abits, wbits) < 2048;
 }
 
-// Row kernel: a wave covers 64 rows x ncols columns.  32 columns (one output word per row) measured fastest
-// or within 3 % of it at every size: more, shorter waves balance better over the SIMDs than the saved
-// activation loads are worth.  Only from about 32 K waves on do wider waves gain those few per cent.
-int plan_rows(int64_t M, int N)
+// Panel kernel: how many waves of a block share a tile's reduction.  One wave per 64 x 8 tile is the least
+// overhead, but a launch of only a few tiles per SIMD takes as long as the SIMD with the most of them: 3136 tiles
+// on 1024 SIMDs are four on some and three on most, a third more time than work.  With the reduction shared by
+// s waves the units are s times as many and 1 / s as long; each further wave costs about 200 instructions (its
+// own addresses and start, the exchange of partial sums) against the tile's 2 * abits * wbits * 8 * Kw.
+int plan_panel_waves(int64_t M, int N, int Kw, int abits, int wbits)
 {
+    const double per_simd = (double)(((M + 63) / 64) * ((N + 7) / 8)) / 1024.0;
+    const double tile = 2.0 * abits * wbits * 8 * Kw;
+    int best = 1;
+    double best_cost = 1e300;
+    for (int s = 1; s <= dlrt::kPanelMaxWaves; ++s) {
+        if (dlrt::panel_words(Kw, s) == 0) continue;
+        const double units = per_simd * s;
+        const double cost = (double)(int64_t)(units + 0.999999) / units * (1.0 + 200.0 * (s - 1) / tile);
+        if (cost < 0.98 * best_cost) { best_cost = cost; best = s; }
+    }
+    return best;
+}
+
+// Row kernel: a wave covers 64 rows x ncols columns.  32 columns (one output word per row) measured fastest
+// or within 3 % of it wherever there are many waves: more, shorter waves balance better over the SIMDs than the
+// saved activation loads are worth, and only from about 32 K waves on do wider waves gain a few per cent.
+// With FEW waves per SIMD the whole number of waves a SIMD ends up with decides (6272 equal waves on 1024 SIMDs
+// are seven on some and six on the rest: the launch takes seven waves' time, 14 % more than its work), and waves
+// of 16 columns, which write half an output word each, divide more finely at the price of fetching every
+// activation row twice as often.  The choice follows a model fitted to measurements of eight layer shapes at 8, 16,
+// 32 and 64 columns: time ~ ceil(waves per SIMD) / (waves per SIMD) x (1 + 200 / instructions per wave's columns),
+// 200 being a wave's own cost (im2col addresses, loads, start and end) in VALU instructions.  `halves`: the call
+// writes nothing but the packed output, from unsigned activations (the only path with sub-word stores).
+int plan_rows(int64_t M, int N, int Kw, int abits, int wbits, bool halves)
+{
+    const int64_t row_blocks = (M + 63) / 64;
     int ncols = 32;
-    while (ncols < 128 && ncols < N && ((M + 63) / 64) * ((N + ncols - 1) / ncols) > 32768) ncols *= 2;
+    if (halves && N % 32 == 0 && row_blocks * (N / 32) >= 1024) {
+        auto cost = [&](int nc) {
+            const double per_simd = (double)(row_blocks * (N / nc)) / 1024.0;
+            const double column = 2.0 * abits * wbits * Kw + 10.0;  // AND/BCNT pairs and the epilogue of one output
+            return (double)(int64_t)(per_simd + 0.999999) / per_simd * (1.0 + 200.0 / (nc * column));
+        };
+        if (cost(16) < 0.98 * cost(32)) ncols = 16;
+    }
+    while (ncols >= 32 && ncols < 128 && ncols < N && row_blocks * ((N + ncols - 1) / ncols) > 32768) ncols *= 2;
     return ncols;
 }
 
@@ -204,7 +240,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
     if (prefer_rows_kernel(M, N, Kw, wbits)) {
         if (block_kernel) *block_kernel = 2;
         if (tile_rows) *tile_rows = 64;
-        if (tile_cols) *tile_cols = plan_rows(M, N);
+        if (tile_cols) *tile_cols = plan_rows(M, N, Kw, abits, wbits, true);  // as for a chained layer (packed output only)
         if (ksplit) *ksplit = 1;
         return;
     }
@@ -212,7 +248,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
         if (block_kernel) *block_kernel = 3;
         if (tile_rows) *tile_rows = 64;
         if (tile_cols) *tile_cols = 8;
-        if (ksplit) *ksplit = 1;
+        if (ksplit) *ksplit = plan_panel_waves(M, N, Kw, abits, wbits);
         return;
     }
     if (!wave && prefer_half_rows(M, N, abits, wbits)) rows /= 2;
@@ -236,11 +272,15 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     g.a_msb_neg = a_msb_neg; g.w_msb_neg = w_msb_neg;
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
-    if (prefer_rows_kernel(M, N, Kw, wbits)) return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N), stream);
+    const bool halves = o.packed && !o.acc && !o.y && !o.q && !a_msb_neg;
+    if (prefer_rows_kernel(M, N, Kw, wbits))
+        return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves), stream);
     const int64_t a_bytes = (int64_t)M * abits * Kw * 4;
     if (prefer_panel_kernel(M, N, Kw, abits, wbits) && panel_kernel_has(g, abits, wbits, false, 8, a_bytes)) {
         g.a_bytes = (uint32_t)a_bytes;
-        return launch_panels(g, o, abits, wbits, bipolar, false, 8, stream);
+        int kwaves = plan_panel_waves(M, N, Kw, abits, wbits);
+        if (!panel_kernel_has(g, abits, wbits, false, 8, a_bytes, kwaves)) kwaves = 1;
+        return launch_panels(g, o, abits, wbits, bipolar, false, 8, kwaves, stream);
     }
     if (prefer_wave_kernel(M, N, abits, wbits)) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
@@ -318,24 +358,27 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
     const bool conv = !pointwise(c);
     const bool rows_fit = row_kernel_has(g.Kw);
     const int64_t x_bytes = (int64_t)c.N * c.H * c.W * abits * c.Cw * 4;
-    if (tile_rows == 128) {  // hint: the panel kernel, 8 * ksplit columns per wave
-        const int ncols = ksplit == 0 ? 8 : 8 * ksplit;
-        if (!panel_kernel_has(g, abits, wbits, conv, ncols, x_bytes)) return DLRT_ERR_SHAPE;
+    const int rows_ncols = plan_rows(g.M, g.N, g.Kw, abits, wbits, o.packed && !o.acc && !o.y && !o.q && !a_msb_neg);
+    if (tile_rows >= 128 && tile_rows % 128 == 0) {  // hint: the panel kernel, 8 * ksplit columns per block,
+        const int ncols = ksplit == 0 ? 8 : 8 * ksplit, kwaves = tile_rows / 128;  // tile_rows / 128 waves sharing the reduction
+        if (kwaves > kPanelMaxWaves || !panel_kernel_has(g, abits, wbits, conv, ncols, x_bytes, kwaves)) return DLRT_ERR_SHAPE;
         ContractArgs gp = g;
         gp.a_bytes = (uint32_t)x_bytes;
-        return launch_panels(gp, o, abits, wbits, bipolar, conv, ncols, stream);
+        return launch_panels(gp, o, abits, wbits, bipolar, conv, ncols, kwaves, stream);
     }
-    if (tile_rows == 64) {  // hint: the row kernel, ksplit groups of 32 columns per wave
-        if (!rows_fit || ksplit < 0 || ksplit > 2048) return DLRT_ERR_SHAPE;
-        return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 32 * ksplit : plan_rows(g.M, g.N), stream);
+    if (tile_rows == 64) {  // hint: the row kernel, 8 * ksplit columns per wave
+        if (!rows_fit || ksplit < 0 || ksplit > 8192) return DLRT_ERR_SHAPE;
+        return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 8 * ksplit : rows_ncols, stream);
     }
     if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits))
-        return launch_rows(g, o, abits, wbits, bipolar, conv, plan_rows(g.M, g.N), stream);
+        return launch_rows(g, o, abits, wbits, bipolar, conv, rows_ncols, stream);
     if (tile_rows == 0 && ksplit == 0 && prefer_panel_kernel(g.M, g.N, g.Kw, abits, wbits) &&
         panel_kernel_has(g, abits, wbits, conv, 8, x_bytes)) {
         ContractArgs gp = g;
         gp.a_bytes = (uint32_t)x_bytes;
-        return launch_panels(gp, o, abits, wbits, bipolar, conv, 8, stream);
+        int kwaves = plan_panel_waves(g.M, g.N, g.Kw, abits, wbits);
+        if (!panel_kernel_has(g, abits, wbits, conv, 8, x_bytes, kwaves)) kwaves = 1;
+        return launch_panels(gp, o, abits, wbits, bipolar, conv, 8, kwaves, stream);
     }
     if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
         const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);

@@ -51,6 +51,8 @@ namespace {
 using dlrt::ContractArgs;
 using dlrt::FusedOut;
 
+constexpr int kMaxWaves = dlrt::kPanelMaxWaves;  // waves of a block that may share one tile's reduction
+
 __device__ __forceinline__ uint32_t dot4(uint32_t a, uint32_t b, uint32_t c)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -114,18 +116,22 @@ __device__ inline u32x4 load16(BufferResource, uint32_t) { return u32x4{0u, 0u, 
 #endif
 
 template <int AB, int WB, int NC, int P, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g, const FusedOut o, const int panels,
-                                                            const uint32_t magic_groups /* for division by panels * P / 4 */)
+__global__ __launch_bounds__(64 * kMaxWaves) void contract_panel_kernel(const ContractArgs g, const FusedOut o, const int panels,
+                                                                        const int kwaves /* waves of the block; divides panels */,
+                                                                        const uint32_t magic_groups /* for division by panels / kwaves * P / 4 */)
 {
     static_assert(P % 4 == 0 && NC % 8 == 0, "panels of whole 16-byte groups, whole output bytes");
     constexpr int G = P / 4;                 // 16-byte groups per panel and plane
-    // The wave's weights, zero beyond Kw / N: [panel][NC * WB][G] groups, so that within a panel every read is
-    // the panel's base address plus a compile-time offset.
+    // The block's weights, zero beyond Kw / N: [panel][NC * WB][G] groups, so that within a panel every read is
+    // the panel's base address plus a compile-time offset.  Behind them, when several waves share the reduction,
+    // the partial sums of waves 1 .. kwaves - 1.
     extern __shared__ uint4 lds[];
 
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform, and known to be
     const int kg = g.Kw >> 2;                // groups of the reduction
-    const int kg_pad = panels * G;
+    const int my_panels = panels / kwaves, p_begin = wave * my_panels, p_end = p_begin + my_panels;
+    const int kg_mine = my_panels * G;       // groups of this wave's panels (padded reduction)
     // block -> (row block, column group): the column groups of one row block are numbered 8 apart, so that they
     // run on the same die one after the other and the rows' activations reach that die's L2 once
     const int col_groups = (g.N + NC - 1) / NC;
@@ -138,13 +144,14 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
     const int n0 = col_group * NC;
     const bool row_ok = m < g.M;
 
-    // ---- the wave's weights -> LDS.  Columns n0 .. n0 + NC - 1 are one contiguous run of the packed tensor,
-    // [column][plane][group]; group k of (column, plane) ci goes to panel k / G, slot ci * G + k % G. ----
+    // ---- the wave's weights (its panels of every column and plane) -> LDS.  Columns n0 .. n0 + NC - 1 are one
+    // contiguous run of the packed tensor, [column][plane][group]; group k of (column, plane) ci goes to panel
+    // k / G, slot ci * G + k % G. ----
     {
         const uint4 *src = reinterpret_cast<const uint4 *>(g.W) + (size_t)n0 * WB * kg;
         const int cols = min(NC, g.N - n0);
-        for (int u = lane; u < NC * WB * kg_pad; u += 64) {
-            const int ci = fast_div(u, magic_groups), k = u - ci * kg_pad;  // (column, plane) pair, group of the padded reduction
+        for (int u = lane; u < NC * WB * kg_mine; u += 64) {
+            const int ci = fast_div(u, magic_groups), k = p_begin * G + (u - ci * kg_mine);  // (column, plane) pair, group of the padded reduction
             const bool ok = k < kg && ci < cols * WB;
             const uint4 q = src[ok ? ci * kg + k : 0];
             const int panel = k / G;
@@ -190,7 +197,7 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
 #pragma unroll
     for (int j = 0; j < AB; ++j) rowpc[j] = 0;
 
-    for (int p = 0; p < panels; ++p) {
+    for (int p = p_begin; p < p_end; ++p) {
         // ---- this lane's P words of every activation plane; groups beyond the reduction and taps outside the
         // image read as zero (an out-of-range offset) ----
         uint32_t a[AB][P];
@@ -247,6 +254,41 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
                     and_popc(acc[c][j][i], a[j][4 * q + 3], w.w);
                 }
             __builtin_amdgcn_sched_barrier(0);  // one (column, plane) at a time: keeps the reads one step ahead, not sixteen
+        }
+    }
+
+    // ---- several waves: the partial sums of the others meet in wave 0, which alone goes on.  (All waves of a
+    // block share the row block, so the early exit above takes all of them or none.) ----
+    if (kwaves > 1) {
+        constexpr int SLOTS = NC * AB * WB + (BIPOLAR ? AB : 0);
+        int *red = reinterpret_cast<int *>(lds + panels * (NC * WB * G));  // [wave - 1][slot][lane]
+        if (wave > 0) {
+            int *mine = red + (wave - 1) * (SLOTS * 64) + lane;
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+                for (int j = 0; j < AB; ++j)
+#pragma unroll
+                    for (int i = 0; i < WB; ++i) mine[((c * AB + j) * WB + i) * 64] = acc[c][j][i];
+            if (BIPOLAR) {
+#pragma unroll
+                for (int j = 0; j < AB; ++j) mine[(NC * AB * WB + j) * 64] = rowpc[j];
+            }
+        }
+        __syncthreads();
+        if (wave > 0) return;
+        for (int w = 1; w < kwaves; ++w) {
+            const int *theirs = red + (w - 1) * (SLOTS * 64) + lane;
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+                for (int j = 0; j < AB; ++j)
+#pragma unroll
+                    for (int i = 0; i < WB; ++i) acc[c][j][i] += theirs[((c * AB + j) * WB + i) * 64];
+            if (BIPOLAR) {
+#pragma unroll
+                for (int j = 0; j < AB; ++j) rowpc[j] += theirs[(NC * AB * WB + j) * 64];
+            }
         }
     }
 
@@ -321,55 +363,59 @@ __global__ __launch_bounds__(64) void contract_panel_kernel(const ContractArgs g
 }
 
 template <int WB, int NC, int P, bool BIPOLAR, bool CONV>
-dlrt_status launch_one(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
+dlrt_status launch_one(const ContractArgs &g, const FusedOut &o, int kwaves, hipStream_t stream)
 {
     constexpr int AB = DLRT_ABITS;
     const int panels = (g.Kw + P - 1) / P;
-    const size_t lds_bytes = (size_t)NC * WB * panels * P * 4;  // the wave's weights over the padded reduction
+    if (kwaves < 1 || kwaves > kMaxWaves || panels % kwaves != 0) return DLRT_ERR_SHAPE;
+    // the block's weights over the padded reduction, and the partial sums of the waves beyond the first
+    const size_t lds_bytes = (size_t)NC * WB * panels * P * 4 + (size_t)(kwaves - 1) * (NC * AB * WB + AB) * 64 * 4;
     if (lds_bytes > 65536) return DLRT_ERR_SHAPE;
     const int64_t bx = ((int64_t)g.M + 63) / 64, by = (g.N + NC - 1) / NC;
     const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies
     if (blocks > 0x7fffffffLL) return DLRT_ERR_SHAPE;
-    const uint32_t groups = (uint32_t)panels * (P / 4);  // ceil(2^32 / groups), 0 standing for a divisor of 1
+    const uint32_t groups = (uint32_t)(panels / kwaves) * (P / 4);  // ceil(2^32 / groups), 0 standing for a divisor of 1
     const uint32_t magic_groups = groups == 1 ? 0u : (uint32_t)((0x100000000ULL + groups - 1) / groups);
-    return dlrt::enqueue(contract_panel_kernel<AB, WB, NC, P, BIPOLAR, CONV>, dim3((unsigned)blocks), dim3(64), lds_bytes,
-                         stream, g, o, panels, magic_groups);
+    return dlrt::enqueue(contract_panel_kernel<AB, WB, NC, P, BIPOLAR, CONV>, dim3((unsigned)blocks), dim3(64 * kwaves),
+                         lds_bytes, stream, g, o, panels, kwaves, magic_groups);
 }
 
 template <int WB, int NC, bool BIPOLAR, bool CONV>
-dlrt_status pick_p(const ContractArgs &g, const FusedOut &o, hipStream_t stream)
+dlrt_status pick_p(const ContractArgs &g, const FusedOut &o, int kwaves, hipStream_t stream)
 {
-    // panels of 12 words when they divide the reduction (3x3 taps: 9 * Cw words) and 16 do not, else of 16
-    if (g.Kw % 12 == 0 && g.Kw % 16 != 0) return launch_one<WB, NC, 12, BIPOLAR, CONV>(g, o, stream);
-    return launch_one<WB, NC, 16, BIPOLAR, CONV>(g, o, stream);
+    switch (dlrt::panel_words(g.Kw, kwaves)) {
+    case 12: return launch_one<WB, NC, 12, BIPOLAR, CONV>(g, o, kwaves, stream);
+    case 16: return launch_one<WB, NC, 16, BIPOLAR, CONV>(g, o, kwaves, stream);
+    }
+    return DLRT_ERR_SHAPE;  // no panel length that the waves share evenly
 }
 
 // ncols: 8, 16 or 32 columns per wave (NC * abits * wbits <= 64 accumulators)
 template <int WB, bool BIPOLAR, bool CONV>
-dlrt_status pick_panel(const ContractArgs &g, const FusedOut &o, int ncols, hipStream_t stream)
+dlrt_status pick_panel(const ContractArgs &g, const FusedOut &o, int ncols, int kwaves, hipStream_t stream)
 {
     constexpr int AB = DLRT_ABITS;
     if constexpr (AB * WB <= 2) {
-        if (ncols == 32) return pick_p<WB, 32, BIPOLAR, CONV>(g, o, stream);
+        if (ncols == 32) return pick_p<WB, 32, BIPOLAR, CONV>(g, o, kwaves, stream);
     }
     if constexpr (AB * WB <= 4) {
-        if (ncols == 16) return pick_p<WB, 16, BIPOLAR, CONV>(g, o, stream);
+        if (ncols == 16) return pick_p<WB, 16, BIPOLAR, CONV>(g, o, kwaves, stream);
     }
     if constexpr (AB * WB <= 8) {
-        if (ncols == 8) return pick_p<WB, 8, BIPOLAR, CONV>(g, o, stream);
+        if (ncols == 8) return pick_p<WB, 8, BIPOLAR, CONV>(g, o, kwaves, stream);
     }
     return DLRT_ERR_SHAPE;  // never planned
 }
 
 template <bool CONV>
-dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, int ncols, hipStream_t stream)
+dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, int ncols, int kwaves, hipStream_t stream)
 {
     switch (wbits) {
     case 1:
-        return bipolar ? pick_panel<1, true, CONV>(g, o, ncols, stream) : pick_panel<1, false, CONV>(g, o, ncols, stream);
-    case 2: return pick_panel<2, false, CONV>(g, o, ncols, stream);
-    case 3: return pick_panel<3, false, CONV>(g, o, ncols, stream);
-    case 4: return pick_panel<4, false, CONV>(g, o, ncols, stream);
+        return bipolar ? pick_panel<1, true, CONV>(g, o, ncols, kwaves, stream) : pick_panel<1, false, CONV>(g, o, ncols, kwaves, stream);
+    case 2: return pick_panel<2, false, CONV>(g, o, ncols, kwaves, stream);
+    case 3: return pick_panel<3, false, CONV>(g, o, ncols, kwaves, stream);
+    case 4: return pick_panel<4, false, CONV>(g, o, ncols, kwaves, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -382,9 +428,10 @@ namespace dlrt {
 #define DLRT_CAT(a, b) DLRT_CAT2(a, b)
 
 dlrt_status DLRT_CAT(launch_panels_a, DLRT_ABITS)(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar,
-                                                   bool conv, int ncols, hipStream_t stream)
+                                                   bool conv, int ncols, int kwaves, hipStream_t stream)
 {
-    return conv ? pick_wbits<true>(g, o, wbits, bipolar, ncols, stream) : pick_wbits<false>(g, o, wbits, bipolar, ncols, stream);
+    return conv ? pick_wbits<true>(g, o, wbits, bipolar, ncols, kwaves, stream)
+                : pick_wbits<false>(g, o, wbits, bipolar, ncols, kwaves, stream);
 }
 
 }  // namespace dlrt

@@ -13,8 +13,10 @@
 // activations itself (eight results at a time, gathered with dot products as the packing kernel does), so
 // the packed output needs no ballot or shuffle either.
 //
-// A wave covers 64 rows x `ncols` columns (a multiple of 32, so that waves own whole output words);
-// the grid is one one-wave block per (64 rows, ncols columns).  int32 / float / uint8 outputs are written one
+// A wave covers 64 rows x `ncols` columns: a multiple of 32, so that waves own whole output words, or, on the
+// packed-only path and when N fills whole words, 16 or 8, written as halves or bytes of the words (finer units
+// for launches of only a few waves per SIMD).  The grid is one wave per (64 rows, ncols columns), four to a block.
+// int32 / float / uint8 outputs are written one
 // element per lane with a row stride between lanes: correct, but only the packed output is a fast path.
 //
 // Measured and dropped: software-pipelining the scalar loads (the next group's weights requested while this
@@ -351,12 +353,19 @@ __global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock) void contract_rows_
             if (shift == 24 || n + 8 == n1) {
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    if (p < o.qbits && row_ok) o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)] = word[p];
+                    if (p < o.qbits && row_ok) {
+                        uint32_t *dst = &o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)];
+                        // a wave of 16 or 8 columns owns a half or a byte of the word (N is then a multiple of 32,
+                        // so that every byte of every word has an owner)
+                        if (ncols >= 32) *dst = word[p];
+                        else if (ncols == 16) reinterpret_cast<uint16_t *>(dst)[(n >> 4) & 1] = (uint16_t)(word[p] >> (n & 16));
+                        else reinterpret_cast<uint8_t *>(dst)[(n >> 3) & 3] = (uint8_t)(word[p] >> shift);
+                    }
                     word[p] = 0u;
                 }
             }
         }
-        for (; n < n1; ++n)  // the last columns of a ragged N
+        for (; n < n1; ++n)  // the last columns of a ragged N (whole-word waves only)
             add_bits(n, (uint32_t)requantized(output(n, exact_tag, horner_tag), n, bias_tag));
     };
     if (packed_only && !g.a_msb_neg) {
@@ -388,6 +397,14 @@ __global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock) void contract_rows_
 template <int AB, int WB, int KW, bool BIPOLAR>
 dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
 {
+    // Waves of 8 or 16 columns write single bytes or halves of the packed words: only on the path that writes
+    // nothing else, and only when N fills whole words (no ragged tail, no zero fill for anyone to own).
+    if (ncols < 32) {
+        const bool packed_only = o.packed && !o.acc && !o.y && !o.q && !g.a_msb_neg;
+        if ((ncols != 8 && ncols != 16) || !packed_only || g.N % 32 != 0) return DLRT_ERR_SHAPE;
+    } else if (ncols % 32 != 0) {
+        return DLRT_ERR_SHAPE;
+    }
     const int64_t bx = ((int64_t)g.M + kRowsPerBlock - 1) / kRowsPerBlock, by = (g.N + ncols - 1) / ncols;
     // per die: its share of the row blocks (padded to the 8 dies) times the column groups, kWavesPerBlock to a block
     const int64_t per_die = ((bx + 7) / 8 * by + kWavesPerBlock - 1) / kWavesPerBlock;

@@ -94,24 +94,42 @@ dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, 
 dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
 
-// Panel kernel (contract_panels.hip): one output row per lane, 64 rows x ncols columns per wave, the reduction
+// Panel kernel (contract_panels.hip): one output row per lane, 64 rows x ncols columns per block, the reduction
 // walked in panels of 12 or 16 words against weights held in LDS; for long reductions with many rows.  ncols is
-// 8, 16 or 32 with ncols * abits * wbits <= 64 accumulators per lane.  Needs Kw % 4 == 0 and 16-byte aligned
-// operands (vec == 4), at most 64 KB of weights per wave, an activation tensor of at most 2^31 bytes (g.a_bytes),
+// 8, 16 or 32 with ncols * abits * wbits <= 64 accumulators per lane.  kwaves (1 .. 4) waves of a block share the
+// tile, each walking an equal number of panels, their partial sums added through LDS: smaller units of work for
+// launches that are only a few waves per SIMD.  Needs Kw % 4 == 0 and 16-byte aligned
+// operands (vec == 4), at most 64 KB of LDS per block, an activation tensor of at most 2^31 bytes (g.a_bytes),
 // and for a convolution Cw % 4 == 0.
-inline bool panel_kernel_has(const ContractArgs &g, int abits, int wbits, bool conv, int ncols, int64_t a_bytes)
+constexpr int kPanelMaxWaves = 4;
+
+// Panel length for a reduction of Kw words shared by kwaves waves: 12 when the reduction is a whole number of
+// 12-word panels and not of 16-word ones, else 16; the other length where only it gives a number of panels
+// that the waves share evenly (and divides the reduction exactly).  0: neither does.
+inline int panel_words(int Kw, int kwaves)
+{
+    const int first = Kw % 12 == 0 && Kw % 16 != 0 ? 12 : 16, second = 28 - first;
+    if (kwaves < 1 || kwaves > kPanelMaxWaves) return 0;
+    if (((Kw + first - 1) / first) % kwaves == 0) return first;
+    if (Kw % second == 0 && (Kw / second) % kwaves == 0) return second;
+    return 0;
+}
+
+inline bool panel_kernel_has(const ContractArgs &g, int abits, int wbits, bool conv, int ncols, int64_t a_bytes, int kwaves = 1)
 {
     if (ncols != 8 && ncols != 16 && ncols != 32) return false;
-    const int p = g.Kw % 12 == 0 && g.Kw % 16 != 0 ? 12 : 16;
+    const int p = panel_words(g.Kw, kwaves);
+    if (p == 0) return false;
     const int64_t padded = (int64_t)((g.Kw + p - 1) / p) * p;  // words per column and plane
-    if (g.Kw % 4 != 0 || g.vec != 4 || ncols * abits * wbits > 64 || ncols * wbits * padded * 4 > 65536) return false;
+    const int64_t lds = ncols * wbits * padded * 4 + (int64_t)(kwaves - 1) * (ncols * abits * wbits + abits) * 256;
+    if (g.Kw % 4 != 0 || g.vec != 4 || ncols * abits * wbits > 64 || lds > 65536) return false;
     if (a_bytes > (1LL << 31)) return false;
     return !conv || g.Cw % 4 == 0;
 }
-dlrt_status launch_panels_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
-dlrt_status launch_panels_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
-dlrt_status launch_panels_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
-dlrt_status launch_panels_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_panels_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int kwaves, hipStream_t stream);
+dlrt_status launch_panels_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int kwaves, hipStream_t stream);
+dlrt_status launch_panels_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int kwaves, hipStream_t stream);
+dlrt_status launch_panels_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int kwaves, hipStream_t stream);
 
 // Conv geometry handed from the C ABI to the launcher.
 struct ConvShape {

@@ -184,8 +184,9 @@ def test_planner_choices_for_the_benchmark_workloads(lib):
     assert query(lib, 409600, 64, 288, 2, 1)[0] == ROWS
     assert query(lib, 200704, 64, 576, 2, 2)[0] == ROWS
     assert query(lib, 50176, 128, 1152, 2, 2) == (PANELS, 64, 8, 1)
-    assert query(lib, 12544, 256, 2304, 2, 2) == (PANELS, 64, 8, 1)
-    assert query(lib, 3136, 512, 4608, 2, 2) == (PANELS, 64, 8, 1)
+    assert query(lib, 12544, 256, 2304, 2, 2) == (PANELS, 64, 8, 2)   # 6.1 tiles per SIMD: two waves share each
+    assert query(lib, 3136, 512, 4608, 2, 2)[:3] == (PANELS, 64, 8) and query(lib, 3136, 512, 4608, 2, 2)[3] >= 2
+    assert query(lib, 200704, 64, 576, 2, 2) == (ROWS, 64, 16, 1)     # 6.1 waves per SIMD: half-word waves
     assert lib.dlrt_query_plan(0, 4, 32, 2, 2, None, None, None, None) == ERR_SHAPE
     assert lib.dlrt_query_plan(4, 4, 32, 2, 7, None, None, None, None) == ERR_BITS
 
@@ -205,11 +206,11 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
         Kw = -(-K // 32)
         tn = 4 if w <= 2 else 2
         assert kind in (WAVE, BLOCK, ROWS, PANELS)
-        if kind == ROWS:    # the whole reduction in a lane's registers, whole output words per wave
-            assert Kw <= 16 or (Kw == 18 and w <= 2)
-            assert rows == 64 and ks == 1 and cols % 32 == 0 and 32 <= cols <= 128
+        if kind == ROWS:    # the whole reduction in a lane's registers; whole output words per wave, or halves
+            assert Kw <= 16 or (Kw == 18 and w <= 2)   # of them where N fills whole words and waves are few
+            assert rows == 64 and ks == 1 and (cols in (32, 64, 128) or (cols == 16 and N % 32 == 0))
         elif kind == PANELS:  # accumulators per lane, the wave's weights in LDS, whole 16-byte groups
-            assert rows == 64 and ks == 1 and cols in (8, 16, 32)
+            assert rows == 64 and 1 <= ks <= 4 and cols in (8, 16, 32)   # ks waves share a tile's reduction
             assert cols * a * w <= 64 and Kw % 4 == 0 and cols * w * (Kw + 15) // 16 * 16 * 4 <= 65536
         elif kind == BLOCK:
             full = 16 * [4, 4, 2, 2][a - 1]
@@ -234,9 +235,13 @@ def test_hints_override_the_plan_or_are_refused(lib):
     enc = [2, 2, UNSIGNED, TWOS]
     big = [64, 28, 28, 128, 128, 3, 3, 1, 1, 1, 1]     # the planner's choice here is the panel kernel
     small = [1, 8, 8, 32, 16, 3, 3, 1, 1, 1, 1]
-    for shape, hint, expect in ((small, (8, 1), None), (small, (64, 0), None), (small, (64, 5000), ERR_SHAPE),
+    for shape, hint, expect in ((small, (8, 1), None), (small, (64, 0), None), (small, (64, 10000), ERR_SHAPE), (small, (64, 3), ERR_SHAPE),
+                                (small, (64, 2), ERR_SHAPE),       # 16 columns per wave need whole output words,
                                 (small, (128, 0), ERR_SHAPE),     # 32 channels: not whole 16-byte groups per tap
                                 (big, (128, 3), ERR_SHAPE), (big, (128, 4), ERR_SHAPE), (big, (12, 1), ERR_SHAPE),
+                                (big, (256, 1), ERR_SHAPE),       # 36 words are 3 panels of 12: two waves cannot share them
+                                (big, (640, 1), ERR_SHAPE),       # at most four waves share a tile
+                                (big, (200, 1), ERR_SHAPE),
                                 (big, (64, 1), ERR_SHAPE)):       # 36 words do not fit a lane's registers
         if expect is not None:  # refused on the host: nothing is launched, so fake pointers are safe
             assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, hint[0], hint[1], NULL) == expect

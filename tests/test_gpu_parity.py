@@ -466,23 +466,40 @@ ROW_KERNEL_SHAPES = [
     (1, 6, 6, 500, 12, 1, 1, 1),     # sixteen words of channels, 1x1 with padding (border outputs are the bias)
     (2, 9, 10, 64, 40, 3, 1, 1),     # 3x3 over two words of channels: eighteen words, batch 2
     (1, 11, 8, 48, 70, 3, 2, 1),     # the same with ragged channels, stride 2 and a ragged third output word
+    (2, 9, 10, 64, 96, 3, 1, 1),     # eighteen words, three whole output words (waves of 8 and 16 columns apply)
+    (1, 20, 20, 32, 64, 3, 2, 1),    # nine words, two whole output words, stride 2
 ]
 
 
 @pytest.mark.parametrize("shape", ROW_KERNEL_SHAPES)
 def test_conv_fused_row_kernel_all_encodings(dlrt, oracle, shape):
     """tile_rows = 64 selects the kernel with one output row per lane; ksplit then is the number of
-    32-column groups a wave covers (0: planned).  Every output kind, and the packed-only fast path."""
+    8-column groups a wave covers (0: planned).  Every output kind, and the packed-only fast path; waves of 8 and
+    16 columns (bytes and halves of the output words) exist on that path only, for whole output words and
+    unsigned activations, and are refused elsewhere."""
     N, H, W, Ci, Co, k, stride, pad = shape
     cases = [(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2), (1, 1, UNSIGNED, TWOS, 1),
              (4, 4, UNSIGNED, TWOS, 4), (3, 2, TWOS, UNSIGNED, 3), (2, 4, UNSIGNED, TWOS, 2), (3, 3, TWOS, TWOS, 2)]
     for idx, (abits, wbits, ea, ew, qbits) in enumerate(cases):
         x = inputs.uniform_values((N, H, W, Ci), abits, ea, 28000 + idx + H)
         w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 29000 + idx + Ci)
-        for groups in (0, 1, 3):
+        for groups in (0, 4, 12):
             fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups)
             fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
                        packed_only=True)
+        for groups in (1, 2):
+            if Co % 32 == 0 and ea == UNSIGNED:
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
+                           packed_only=True)
+            else:
+                with pytest.raises(dlrt.DlrtError):
+                    fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64,
+                               ksplit=groups, packed_only=True)
+            with pytest.raises(dlrt.DlrtError):  # any further output: whole words only
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups)
+        with pytest.raises(dlrt.DlrtError):
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=3,
+                       packed_only=True)      # 24 columns: neither a part of a word nor whole words
 
 
 PANEL_KERNEL_SHAPES = [
@@ -499,6 +516,19 @@ PANEL_KERNEL_SHAPES = [
     (2, 9, 10, 384, 24, 2, 1, 1),    # 2x2 taps of twelve words: 48 words, divisible by both panel lengths
     (1, 20, 20, 128, 16, 1, 2, 0),   # strided 1x1 (one tap): four words; 100 output rows
 ]
+
+
+def panel_words(Kw, waves):
+    """Panel length the kernel uses when `waves` waves share a reduction of Kw words (0: none): 12 when the
+    reduction is whole 12-word panels and not whole 16-word ones, else 16; the other length only if it divides the
+    reduction exactly; the number of panels must divide evenly over the waves."""
+    first = 12 if Kw % 12 == 0 and Kw % 16 != 0 else 16
+    second = 28 - first
+    if -(-Kw // first) % waves == 0:
+        return first
+    if Kw % second == 0 and (Kw // second) % waves == 0:
+        return second
+    return 0
 
 
 @pytest.mark.parametrize("shape", PANEL_KERNEL_SHAPES)
@@ -518,6 +548,21 @@ def test_conv_fused_panel_kernel_all_encodings(dlrt, oracle, shape):
             fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128, ksplit=g)
             fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128, ksplit=g,
                        packed_only=True)
+        # tile_rows = 128 s: s waves of a block share the tile's reduction, an equal number of panels each; a
+        # split that no panel length (12 or 16 words) allows is refused
+        Kw = k * k * ((Ci + 31) // 32)
+        for s in (2, 3, 4):
+            g = groups[-1]
+            P = panel_words(Kw, s)
+            # the block's weights over the padded reduction and the partial sums of the waves beyond the first
+            lds = 8 * max(g, 1) * wbits * (-(-Kw // P) * P if P else 0) * 4 + (s - 1) * (8 * max(g, 1) * abits * wbits + abits) * 256
+            if P and lds <= 65536:
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128 * s, ksplit=g)
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128 * s, ksplit=g,
+                           packed_only=True)
+            else:
+                with pytest.raises(dlrt.DlrtError):
+                    fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128 * s, ksplit=g)
 
 
 def test_conv_fused_panel_kernel_rejects_what_it_cannot_hold(dlrt):
