@@ -304,12 +304,13 @@ __global__ __launch_bounds__(64 * kMaxWaves) void contract_panel_kernel(const Co
         int t = 0;
 #pragma unroll
         for (int j = 0; j < AB; ++j) {
-            int part = BIPOLAR ? 2 * acc[c][j][0] - rowpc[j] : 0;
+            // plane 0 of an operand of two or more bits always weighs +1: it starts the sum without a multiply
+            int part = BIPOLAR ? 2 * acc[c][j][0] - rowpc[j] : WB > 1 ? acc[c][j][0] : mad24(acc[c][j][0], wcoef[0], 0);
             if (!BIPOLAR) {
 #pragma unroll
-                for (int i = 0; i < WB; ++i) part = mad24(acc[c][j][i], wcoef[i], part);
+                for (int i = 1; i < WB; ++i) part = mad24(acc[c][j][i], wcoef[i], part);
             }
-            t = mad24(part, acoef[j], t);
+            t = (AB > 1 && j == 0) ? part : mad24(part, acoef[j], t);
         }
         total[c] = t;
     }
