@@ -55,7 +55,7 @@ def build_library(extra_flags=()) -> str:
     os.makedirs(OBJ, exist_ok=True)
     # the probe library carries the block kernel once more, with per-block clock sampling compiled in
     probe_units = [("probe.hip", "probe.o", [])] + \
-                  [("contract.hip", f"probe_contract_a{b}.o", [f"-DDLRT_ABITS={b}", "-DDLRT_CLOCK_PROBE"]) for b in (2, 4)]
+                  [("contract.hip", f"probe_contract_a{b}.o", [f"-DDLRT_ABITS={b}", "-DDLRT_CLOCK_PROBE"]) for b in (1, 2, 3, 4)]
     units = UNITS + probe_units
     with ThreadPoolExecutor(max_workers=min(len(units), os.cpu_count() or 4, 16)) as pool:
         objs = list(pool.map(lambda u: _compile(u, list(extra_flags)), units))

@@ -8,15 +8,16 @@
 //                         counters read at both ends of the loop, the clock the chip really ran at;
 //   * dlrt_probe_gemm_clocks - the library's own block kernel (contract.hip, built a second time into this
 //                         library with DLRT_CLOCK_PROBE) on a packed GEMM, every block leaving its lifetime on
-//                         both counters: the clock during the kernel the roofline fraction is quoted for, which
-//                         differs from the clock under the register-only loop (power management);
+//                         both counters: the clock during the kernel the roofline fraction is quoted for (after
+//                         an idle spell the chip takes tens of milliseconds of load to reach its steady clock, so
+//                         a fraction of the nominal peak means little without it);
 //   * dlrt_probe_copy   - a plain device copy: the HBM bandwidth a simple kernel reaches;
 //   * dlrt_probe_empty  - an empty kernel: the floor of a dependent launch.
 // Like the library, every call only enqueues on the caller's stream; bench.py does the timing.
 //
 //   int  dlrt_probe_valu(int blocks, int iters, uint64_t *clocks /* device, 2 per block */, uint32_t *sink /* device, 256 per block */, void *stream);
-//   int  dlrt_probe_gemm_clocks(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int K, int abits /* 2 or 4 */, int wbits,
-//                               uint64_t *clocks /* device, 2 per 64 x 64 (abits 2) or 32 x (64 / 32) tile */, void *stream);
+//   int  dlrt_probe_gemm_clocks(const uint32_t *A, const uint32_t *W, int32_t *C, int M, int N, int K, int abits, int wbits,
+//                               uint64_t *clocks /* device, 2 per tile of (64 or, for 3 and 4 bits, 32) rows x columns */, void *stream);
 //                               unsigned activations, two's-complement weights, M, N multiples of 64, K of 128, 16-byte aligned
 //   int  dlrt_probe_copy(const void *src, void *dst, size_t bytes /* multiple of 16 */, void *stream);
 //   int  dlrt_probe_empty(void *stream);
@@ -112,7 +113,7 @@ int dlrt_probe_gemm_clocks(const uint32_t *A, const uint32_t *W, int32_t *C, int
                            uint64_t *clocks, void *stream)
 {
     if (!A || !W || !C || !clocks || M <= 0 || N <= 0 || K <= 0 || M % 64 || N % 64 || K % 128) return 1;
-    if ((abits != 2 && abits != 4) || wbits < 1 || wbits > 4) return 1;
+    if (abits < 1 || abits > 4 || wbits < 1 || wbits > 4) return 1;
     dlrt::ContractArgs g{};
     g.A = A; g.W = W; g.M = M; g.N = N; g.Kw = K / 32;
     g.a_msb_neg = 0; g.w_msb_neg = 1;
@@ -121,8 +122,11 @@ int dlrt_probe_gemm_clocks(const uint32_t *A, const uint32_t *W, int32_t *C, int
     dlrt::FusedOut o{};
     o.acc = C;
     o.qbits = 1;
-    const dlrt_status st = abits == 2 ? dlrt::launch_contract_a2(g, o, wbits, false, false, static_cast<hipStream_t>(stream))
-                                      : dlrt::launch_contract_a4(g, o, wbits, false, false, static_cast<hipStream_t>(stream));
+    const hipStream_t q = static_cast<hipStream_t>(stream);
+    const dlrt_status st = abits == 1   ? dlrt::launch_contract_a1(g, o, wbits, false, false, q)
+                           : abits == 2 ? dlrt::launch_contract_a2(g, o, wbits, false, false, q)
+                           : abits == 3 ? dlrt::launch_contract_a3(g, o, wbits, false, false, q)
+                                        : dlrt::launch_contract_a4(g, o, wbits, false, false, q);
     return st == DLRT_OK ? 0 : 1;
 }
 
