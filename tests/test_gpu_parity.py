@@ -1076,6 +1076,42 @@ def test_unpacked_gemm_i4_agrees_with_the_bit_serial_gemm_at_full_size(dlrt, ora
     assert np.array_equal(got, ref)
 
 
+# ---- seeded random shapes, encodings and kernel hints ---------------------------------------------------------
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_random_convs_planned_and_hinted_match_the_oracle(dlrt, oracle, seed):
+    """Random small convolutions over every bit width and encoding: the planned kernel with every kind of output,
+    and the chained-layer call (packed output only) under a random row- or panel-kernel hint; a hint the kernels
+    do not have must be refused, any other must give the oracle's words."""
+    r = rng(seed)
+    ran = refused = 0
+    for case in range(60):
+        abits, wbits, qbits = int(r.integers(1, 5)), int(r.integers(1, 5)), int(r.integers(1, 5))
+        ea = int(r.choice([UNSIGNED, UNSIGNED, TWOS]))
+        ew = BIPOLAR if wbits == 1 and r.random() < 0.5 else int(r.choice([UNSIGNED, TWOS]))
+        k = int(r.choice([1, 3, 3]))
+        stride, pad = int(r.choice([1, 1, 2])), k // 2
+        panel = r.random() < 0.5
+        if panel:   # whole 16-byte groups per tap
+            Ci, Co = int(r.choice([128, 256, 384, 512])), int(r.choice([8, 24, 32, 64, 72, 128]))
+            hint = (128 * int(r.integers(1, 5)), int(r.choice([1, 1, 2, 4])))
+        else:       # at most 18 reduction words
+            Ci, Co = int(r.choice([16, 32, 64, 100, 128] if k == 1 else [16, 32, 64])), int(r.choice([32, 64, 96, 128, 40]))
+            hint = (64, int(r.choice([1, 2, 4, 8, 12])))
+        H, W, N = int(r.choice([6, 20, 33])), int(r.choice([7, 24, 40])), int(r.choice([1, 2, 5]))
+        x = inputs.uniform_values((N, H, W, Ci), abits, ea, 50000 + 100 * seed + case)
+        w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 60000 + 100 * seed + case)
+        if case % 3 == 0:
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits)
+        try:
+            fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=hint[0], ksplit=hint[1],
+                       packed_only=True)
+            ran += 1
+        except dlrt.DlrtError as e:
+            assert e.code == 3, (case, hint)   # a shape / hint the kernel does not have: nothing was launched
+            refused += 1
+    assert ran >= 20 and refused >= 5, (ran, refused)
+
+
 # ---- error handling with real buffers ------------------------------------------------------------------
 def test_errors_raise_and_launch_nothing(dlrt):
     a = torch.zeros((4, 2, 1), dtype=torch.int32, device=DEV)
