@@ -210,10 +210,11 @@ int plan_panel_waves(int64_t M, int N, int Kw, int abits, int wbits)
 // are seven on some and six on the rest: the launch takes seven waves' time, 14 % more than its work), and waves
 // of 16 columns, which write half an output word each, divide more finely at the price of fetching every
 // activation row twice as often.  The choice follows a model fitted to measurements of eight layer shapes at 8, 16,
-// 32 and 64 columns: time ~ ceil(waves per SIMD) / (waves per SIMD) x (1 + 200 / instructions per wave's columns),
-// 200 being a wave's own cost (im2col addresses, loads, start and end) in VALU instructions.  `halves`: the call
-// writes nothing but the packed output, from unsigned activations (the only path with sub-word stores).
-int plan_rows(int64_t M, int N, int Kw, int abits, int wbits, bool halves)
+// 32 and 64 columns: time ~ ceil(waves per SIMD) / (waves per SIMD) x (1 + P / instructions per wave's columns),
+// P being a wave's own cost in VALU instructions: 200 for a convolution (im2col addresses, loads, start and end),
+// 80 for a GEMM or 1x1 convolution (the row's words are one run).  `halves`: the call writes nothing but the
+// packed output, from unsigned activations (the only path with sub-word stores).
+int plan_rows(int64_t M, int N, int Kw, int abits, int wbits, bool halves, bool conv)
 {
     const int64_t row_blocks = (M + 63) / 64;
     int ncols = 32;
@@ -221,7 +222,7 @@ int plan_rows(int64_t M, int N, int Kw, int abits, int wbits, bool halves)
         auto cost = [&](int nc) {
             const double per_simd = (double)(row_blocks * (N / nc)) / 1024.0;
             const double column = 2.0 * abits * wbits * Kw + 10.0;  // AND/BCNT pairs and the epilogue of one output
-            return (double)(int64_t)(per_simd + 0.999999) / per_simd * (1.0 + 200.0 / (nc * column));
+            return (double)(int64_t)(per_simd + 0.999999) / per_simd * (1.0 + (conv ? 200.0 : 80.0) / (nc * column));
         };
         if (cost(16) < 0.98 * cost(32)) ncols = 16;
     }
@@ -240,7 +241,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
     if (prefer_rows_kernel(M, N, Kw, wbits)) {
         if (block_kernel) *block_kernel = 2;
         if (tile_rows) *tile_rows = 64;
-        if (tile_cols) *tile_cols = plan_rows(M, N, Kw, abits, wbits, true);  // as for a chained layer (packed output only)
+        if (tile_cols) *tile_cols = plan_rows(M, N, Kw, abits, wbits, true, true);  // as for a chained conv layer (packed output only)
         if (ksplit) *ksplit = 1;
         return;
     }
@@ -274,7 +275,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     g.vec = va < vw ? va : vw;
     const bool halves = o.packed && !o.acc && !o.y && !o.q && !a_msb_neg;
     if (prefer_rows_kernel(M, N, Kw, wbits))
-        return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves), stream);
+        return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves, false), stream);
     const int64_t a_bytes = (int64_t)M * abits * Kw * 4;
     if (prefer_panel_kernel(M, N, Kw, abits, wbits) && panel_kernel_has(g, abits, wbits, false, 8, a_bytes)) {
         g.a_bytes = (uint32_t)a_bytes;
@@ -358,7 +359,7 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
     const bool conv = !pointwise(c);
     const bool rows_fit = row_kernel_has(g.Kw);
     const int64_t x_bytes = (int64_t)c.N * c.H * c.W * abits * c.Cw * 4;
-    const int rows_ncols = plan_rows(g.M, g.N, g.Kw, abits, wbits, o.packed && !o.acc && !o.y && !o.q && !a_msb_neg);
+    const int rows_ncols = plan_rows(g.M, g.N, g.Kw, abits, wbits, o.packed && !o.acc && !o.y && !o.q && !a_msb_neg, conv);
     if (tile_rows >= 128 && tile_rows % 128 == 0) {  // hint: the panel kernel, 8 * ksplit columns per block,
         const int ncols = ksplit == 0 ? 8 : 8 * ksplit, kwaves = tile_rows / 128;  // tile_rows / 128 waves sharing the reduction
         if (kwaves > kPanelMaxWaves || !panel_kernel_has(g, abits, wbits, conv, ncols, x_bytes, kwaves)) return DLRT_ERR_SHAPE;
