@@ -308,8 +308,9 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_
     out["sum_bound_us"] = round(sum(p["bound_us"] for p in per_layer), 3)
     if batch > 1:
         macs = batch * sum(L.macs for L in layers)
-        # With kernels of tens of microseconds the host keeps ahead of the GPU, and the eagerly enqueued chain
-        # measured 0.5 to 1.6 % FASTER than the graph's replay: the batched figures are of the faster of the two.
+        # With kernels of tens of microseconds the host keeps ahead of the GPU, and the eagerly enqueued chain and
+        # the graph's replay come within 1 to 3 % of each other, either way round: the batched figures are of the
+        # faster of the two.
         best = min(out["graph_fused_ms"], out["eager_fused_ms"])
         out["batch"] = batch
         out["fused_ms"] = best
