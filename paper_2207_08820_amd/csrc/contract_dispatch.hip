@@ -188,8 +188,12 @@ bool prefer_panel_kernel(int64_t M, int N, int Kw, int abits, int wbits)
 // on 1024 SIMDs are four on some and three on most, a third more time than work.  With the reduction shared by
 // s waves the units are s times as many and 1 / s as long; each further wave costs about 200 instructions (its
 // own addresses and start, the exchange of partial sums) against the tile's 2 * abits * wbits * 8 * Kw.
+// A SIMD holds eight of these waves at once and issues at full rate only with several of them: the waves beyond
+// a multiple of eight run as a last, thinner round, at the rate the register-only AND + popcount loop measured
+// for that many waves per SIMD (0.72 of the full rate for one wave, 0.85 for two, 0.94 for four).
 int plan_panel_waves(int64_t M, int N, int Kw, int abits, int wbits)
 {
+    static const double rate[9] = {1.0, 0.715, 0.85, 0.90, 0.94, 0.955, 0.97, 0.985, 1.0};
     const double per_simd = (double)(((M + 63) / 64) * ((N + 7) / 8)) / 1024.0;
     const double tile = 2.0 * abits * wbits * 8 * Kw;
     int best = 1;
@@ -197,7 +201,9 @@ int plan_panel_waves(int64_t M, int N, int Kw, int abits, int wbits)
     for (int s = 1; s <= dlrt::kPanelMaxWaves; ++s) {
         if (dlrt::panel_words(Kw, s) == 0) continue;
         const double units = per_simd * s;
-        const double cost = (double)(int64_t)(units + 0.999999) / units * (1.0 + 200.0 * (s - 1) / tile);
+        const int64_t most = (int64_t)(units + 0.999999);  // waves of the fullest SIMD
+        const double rounds = (double)(most / 8 * 8) + (most % 8 ? (most % 8) / rate[most % 8] : 0.0);
+        const double cost = rounds / units * (1.0 + 200.0 * (s - 1) / tile);
         if (cost < 0.98 * best_cost) { best_cost = cost; best = s; }
     }
     return best;

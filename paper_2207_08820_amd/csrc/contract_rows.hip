@@ -110,8 +110,11 @@ __device__ __forceinline__ uint32_t byte_from_float(float v, uint32_t x)
 #endif
 }
 
+// The longest register rows (16 and 18 words) are compiled for six resident waves per SIMD: left alone the compiler
+// takes 108 registers (four waves) for its prologue's address arithmetic; at 80 nothing spills and the layers of
+// 200704 x 64 x 576 and 50176 x 128 x 576 run 2 % faster (the last, thin round of waves is fuller).  Seven would spill.
 template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
-__global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
+__global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock, (KW >= 16 && WB <= 2 ? 6 : 1)) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
                                                                        const int ncols,
                                                                        const uint32_t *__restrict__ Wp,
                                                                        const float *__restrict__ scale,
