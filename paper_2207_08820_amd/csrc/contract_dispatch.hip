@@ -32,9 +32,33 @@ dlrt_status by_abits(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int a
     return DLRT_ERR_BITS;
 }
 
-dlrt_status wave_by_abits(const dlrt::ContractArgs *g, const dlrt::FusedOut *o, int count, int abits, int wbits,
+// The per-wave kernel addresses its operands with 32-bit byte offsets into buffer resources (loads beyond a
+// tensor return zeros): both tensors must stay below 2^31 bytes.  Sizes in bytes, 0 if the kernel cannot take them.
+bool wave_operand_bytes(const dlrt::ContractArgs &g, int abits, int wbits, bool conv, uint32_t *a_bytes, uint32_t *w_bytes)
+{
+    const int64_t wb = (int64_t)g.N * wbits * g.Kw * 4;
+    int64_t ab = (int64_t)g.M * abits * g.Kw * 4;
+    if (conv) {
+        ab = (int64_t)g.M / ((int64_t)g.Ho * g.Wo) * g.H * g.Wd * abits * g.Cw * 4;
+        // the tap arithmetic runs on 24-bit multiplies and a 16-bit reciprocal of KW
+        if ((int64_t)g.KH * g.Wd + g.KW >= (1 << 24) || (int64_t)g.KH * g.KW * g.KW >= 65536 || abits * g.Cw * 4 >= (1 << 24))
+            return false;
+        if (g.Kw >= (1 << 24) || (g.tapShift == 16 && g.tapMul != 1 && (int64_t)g.Kw * g.Cw >= 65536)) return false;
+    }
+    if (ab > (1LL << 31) || wb > (1LL << 31)) return false;
+    *a_bytes = (uint32_t)ab;
+    *w_bytes = (uint32_t)wb;
+    return true;
+}
+
+dlrt_status wave_by_abits(const dlrt::ContractArgs *g_in, const dlrt::FusedOut *o, int count, int abits, int wbits,
                           bool bipolar, bool conv, int tm, int ksplit, hipStream_t stream)
 {
+    dlrt::ContractArgs g[2];
+    for (int i = 0; i < count; ++i) {
+        g[i] = g_in[i];
+        if (!wave_operand_bytes(g[i], abits, wbits, conv, &g[i].a_bytes, &g[i].w_bytes)) return DLRT_ERR_SHAPE;
+    }
     switch (abits) {
     case 1: return dlrt::launch_wave_a1(g, o, count, wbits, bipolar, conv, tm, ksplit, stream);
     case 2: return dlrt::launch_wave_a2(g, o, count, wbits, bipolar, conv, tm, ksplit, stream);
@@ -242,7 +266,8 @@ namespace dlrt {
 
 void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, int *tile_rows, int *tile_cols, int *ksplit)
 {
-    const bool wave = prefer_wave_kernel(M, N, abits, wbits);
+    const bool wave = prefer_wave_kernel(M, N, abits, wbits) && (int64_t)M * abits * Kw * 4 <= (1LL << 31) &&
+                      (int64_t)N * wbits * Kw * 4 <= (1LL << 31);  // (its operands are addressed with 32-bit offsets)
     int rows = block_tile(abits), cols = block_tile(wbits), ks = 1;
     if (prefer_rows_kernel(M, N, Kw, wbits)) {
         if (block_kernel) *block_kernel = 2;
@@ -289,7 +314,8 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
         if (!panel_kernel_has(g, abits, wbits, false, 8, a_bytes, kwaves)) kwaves = 1;
         return launch_panels(g, o, abits, wbits, bipolar, false, 8, kwaves, stream);
     }
-    if (prefer_wave_kernel(M, N, abits, wbits)) {
+    uint32_t ab = 0, wb = 0;
+    if (prefer_wave_kernel(M, N, abits, wbits) && wave_operand_bytes(g, abits, wbits, false, &ab, &wb)) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
         return wave_by_abits(g, o, abits, wbits, bipolar, false, p.tm, p.ksplit, stream);
     }
@@ -311,6 +337,11 @@ static ContractArgs conv_args(const uint32_t *X, const uint32_t *Wp, const ConvS
     g.sh = c.sh; g.sw = c.sw; g.ph = c.ph; g.pw = c.pw;
     g.magicCw = magic_for(c.Cw);
     g.magicKW = magic_for(c.KW);
+    g.magicKW16 = (uint32_t)((65536 + c.KW - 1) / c.KW);
+    g.tapMul = (uint32_t)((65536 + c.Cw - 1) / c.Cw);
+    g.tapShift = 16;
+    for (int b = 0; b < 24; ++b)
+        if (c.Cw == 1 << b) { g.tapMul = 1; g.tapShift = (uint32_t)b; }
     // row m < M is divided by Ho * Wo, the remainder (< Ho * Wo) by Wo: the multiply-high division is exact
     // while dividend * divisor stays below 2^32
     const int64_t hw = (int64_t)c.Ho * c.Wo;
@@ -387,7 +418,9 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
         if (!panel_kernel_has(g, abits, wbits, conv, 8, x_bytes, kwaves)) kwaves = 1;
         return launch_panels(gp, o, abits, wbits, bipolar, conv, 8, kwaves, stream);
     }
-    if (tile_rows > 0 || ksplit > 0 || prefer_wave_kernel(g.M, g.N, abits, wbits)) {
+    uint32_t ab = 0, wb = 0;
+    if (tile_rows > 0 || ksplit > 0 ||
+        (prefer_wave_kernel(g.M, g.N, abits, wbits) && wave_operand_bytes(g, abits, wbits, conv, &ab, &wb))) {
         const WavePlan p = plan_wave(g.M, g.N, g.Kw, abits, wbits, tile_rows, ksplit);
         if (!p.found) return DLRT_ERR_SHAPE;  // the hints name a tile the kernel does not have
         return wave_by_abits(g, o, abits, wbits, bipolar, conv, p.tm, p.ksplit, stream);

@@ -34,6 +34,67 @@ using dlrt::FusedOut;
 
 template <int WB> struct WaveTN { static constexpr int value = WB <= 2 ? 4 : 2; };
 
+// Operands are fetched through buffer resources: a 32-bit byte offset per lane instead of a 64-bit address,
+// and a load at an offset beyond the tensor returns zeros without touching memory, which is how words beyond the
+// reduction and taps outside the image become zero (one select on the offset instead of one per loaded word).
+// A wave at batch 1 is alone on its SIMD, so every instruction of this address arithmetic is exposed time.
+constexpr uint32_t kOutOfRange = 0x80000000u;  // beyond any tensor this kernel accepts (at most 2^31 bytes)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#if defined(__HIP_DEVICE_COMPILE__)
+using BufferResource = __amdgpu_buffer_rsrc_t;
+__device__ __forceinline__ BufferResource make_resource(const uint32_t *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(base), 0, bytes, 0x00020000);
+}
+// VEC words at byte offset `offset` into out[0 .. VEC - 1]
+template <int VEC>
+__device__ __forceinline__ void load_words(BufferResource r, uint32_t offset, uint32_t *out)
+{
+    if (VEC == 4) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, offset, 0, 0);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    } else if (VEC == 2) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, offset, 0, 0);
+        out[0] = v.x; out[1] = v.y;
+    } else {
+        out[0] = __builtin_amdgcn_raw_buffer_load_b32(r, offset, 0, 0);
+    }
+}
+// a * b + c on operands below 2^24, b uniform over the wave: one full-rate instruction (a 32-bit multiply runs
+// at a quarter of that rate)
+__device__ __forceinline__ uint32_t mad24(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t d;
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(b), "v"(c));
+    return d;
+}
+// a * b on full 32-bit operands, b uniform.  Kept out of the compiler's sight: left to itself it folds such a
+// product and a following add into a 64-bit multiply-add whose addend's upper half is whatever register follows,
+// and waits for that register's pending load.
+__device__ __forceinline__ uint32_t mul32(uint32_t a, uint32_t b)
+{
+    uint32_t d;
+    asm("v_mul_lo_u32 %0, %1, %2" : "=v"(d) : "v"(a), "s"(b));
+    return d;
+}
+// the same on signed 24-bit operands
+__device__ __forceinline__ int mad24s(int a, int b, int c)
+{
+    int d;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(b), "v"(c));
+    return d;
+}
+#else
+__device__ inline int mad24s(int a, int b, int c) { return a * b + c; }
+__device__ inline uint32_t mul32(uint32_t a, uint32_t b) { return a * b; }
+struct BufferResource { const uint32_t *base; };  // host pass of the single-source compile: never executed
+__device__ inline BufferResource make_resource(const uint32_t *base, uint32_t) { return BufferResource{base}; }
+template <int VEC>
+__device__ inline void load_words(BufferResource, uint32_t, uint32_t *out) { for (int e = 0; e < VEC; ++e) out[e] = 0u; }
+__device__ inline uint32_t mad24(uint32_t a, uint32_t b, uint32_t c) { return a * b + c; }
+#endif
+
 // OR of `v` over each aligned group of LX (8 or 16) consecutive lanes, left in every lane of the group.
 // DPP lane swaps within a row of 16 lanes: the two quad permutations give every lane its quad's OR, the
 // half-row mirror (lane i <-> 7 - i) then brings in the other quad of the group of 8, the row mirror
@@ -69,7 +130,7 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     const int steps_base = prob.steps_base, steps_rem = prob.steps_rem, tiles = prob.tiles;
     const uint32_t magicSubN = prob.magicSubN;
     const int subN = prob.subN, subM = prob.subM, die_bits = prob.die_bits, lc = prob.lc;
-    asm volatile("" ::"s"(subN), "s"(subM), "s"(die_bits), "s"(lc));
+    asm volatile("" ::"s"(subN), "s"(subM), "s"(die_bits), "s"(lc), "s"(g.a_bytes), "s"(g.w_bytes), "s"(g.tapMul), "s"(g.tapShift), "s"(g.magicKW16));
     asm volatile("" ::"s"(tiles), "s"(magicSubN), "s"(g.A), "s"(g.W), "s"(g.M), "s"(g.N), "s"(g.Kw), "s"(g.a_msb_neg), "s"(g.w_msb_neg), "s"(g.H),
                  "s"(g.Wd), "s"(g.Cw), "s"(g.KH), "s"(g.KW), "s"(g.Ho), "s"(g.Wo), "s"(g.sh), "s"(g.sw), "s"(g.ph), "s"(g.pw),
                  "s"(g.magicCw), "s"(g.magicKW), "s"(g.magicHW), "s"(g.magicWo), "s"(o.acc), "s"(o.y), "s"(o.q),
@@ -109,7 +170,8 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     // column, plane).  Rows / columns beyond the matrix are clamped (loaded, never stored).  The weights come
     // first: their addresses need no pixel arithmetic, so their first fetch is in flight while the activation
     // side is still decoding its output pixels (a lone wave waits out every latency in full). ----
-    const uint32_t *srcW[NW];
+    const BufferResource rW = make_resource(g.W, g.w_bytes), rA = make_resource(g.A, g.a_bytes);
+    uint32_t offW[NW];  // byte offset of the slot's four words at reduction word 0
     int dstW[NW], k4W[NW];
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
@@ -119,18 +181,25 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
         // consecutive lx read consecutive 16-byte units
         dstW[t] = (k4 * WB + plane) * 32 + (col % TN) * LX + col / TN;
         k4W[t] = k4;
-        srcW[t] = g.W + ((size_t)min(n0 + col, g.N - 1) * WB + plane) * g.Kw + k4 * 4;
+        offW[t] = ((uint32_t)(min(n0 + col, g.N - 1) * WB + plane) * (uint32_t)g.Kw + (uint32_t)(k4 * 4)) * 4u;
     }
 
     uint4 stageA[NA], stageW[NW];
-    auto fetchW = [&](int kbase) {
-        if (kbase + 16 <= g.Kw) {  // all four steps inside the reduction: no guards
+    // Four words of one row (or column) and plane, VEC at a time; a group at or beyond the reduction's end reads
+    // as zero.  k0: the reduction word the slot starts at; off: the byte offset of that word.
+    auto fetch_row = [&](BufferResource r, uint32_t off, int k0, bool guard) {
+        uint32_t w[4];
 #pragma unroll
-            for (int t = 0; t < NW; ++t) stageW[t] = load4<VEC>(srcW[t] + kbase);
-        } else {
-#pragma unroll
-            for (int t = 0; t < NW; ++t) stageW[t] = load4_tail<VEC>(srcW[t] + kbase, kbase + k4W[t] * 4, g.Kw);
+        for (int e = 0; e < 4; e += VEC) {
+            const uint32_t o4 = off + 4u * e;
+            load_words<VEC>(r, guard && k0 + e >= g.Kw ? kOutOfRange : o4, w + e);
         }
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    };
+    auto fetchW = [&](int kbase) {
+        const bool guard = kbase + 16 > g.Kw;  // uniform: all four steps inside the reduction need no guards
+#pragma unroll
+        for (int t = 0; t < NW; ++t) stageW[t] = fetch_row(rW, offW[t] + 4u * kbase, kbase + k4W[t] * 4, guard);
     };
     fetchW(s_begin * 4);
 
@@ -147,8 +216,12 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
         }
     }
 
-    const uint32_t *srcA[NA];
+    // Activations.  GEMM: like the weights.  Convolution (implicit im2col, see contract.hip): the slot's output
+    // pixel gives the byte offset of its tap (0, 0), which may lie outside the image (the sum wraps; a tap is only
+    // read where it lies inside, and there the tap's own offset brings the sum back into the tensor).
+    uint32_t offA[NA];
     int dstA[NA], k4A[NA], ih0[NA], iw0[NA];
+    const uint32_t pixel_bytes = (uint32_t)(AB * g.Cw * 4);
 #pragma unroll
     for (int t = 0; t < NA; ++t) {
         const int s = lane + 64 * t;
@@ -163,34 +236,27 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
             const int hw = g.Ho * g.Wo;
             const int n = checked_div(m, hw, g.magicHW), rem = m - n * hw;
             const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
-            ih0[t] = oh * g.sh - g.ph;
-            iw0[t] = ow * g.sw - g.pw;
-            srcA[t] = g.A + (size_t)n * g.H * g.Wd * AB * g.Cw + plane * g.Cw;
+            ih0[t] = (int)mad24((uint32_t)oh, (uint32_t)g.sh, (uint32_t)-g.ph);
+            iw0[t] = (int)mad24((uint32_t)ow, (uint32_t)g.sw, (uint32_t)-g.pw);
+            const uint32_t pixel00 = (uint32_t)mad24s(ih0[t], g.Wd, (int)mul32((uint32_t)n, (uint32_t)(g.H * g.Wd))) + (uint32_t)iw0[t];
+            offA[t] = mul32(pixel00, pixel_bytes) + (uint32_t)(plane * g.Cw * 4);
         } else {
-            srcA[t] = g.A + ((size_t)m * AB + plane) * g.Kw + k4 * 4;
+            offA[t] = ((uint32_t)(m * AB + plane) * (uint32_t)g.Kw + (uint32_t)(k4 * 4)) * 4u;
         }
     }
 
-    // implicit im2col (see contract.hip): VEC words of one tap, zero outside the image / reduction
+    // VEC words of one tap: reduction word kwd -> (tap, channel word) -> (kh, kw); zero beyond the reduction and
+    // outside the image.  Both divisions are a 24-bit multiply and a shift with constants from the host (a plain
+    // shift when Cw is a power of two): full-rate instructions where a multiply-high division takes quarter-rate
+    // ones, and no branch between the cases.
+    const uint32_t magicKW16 = g.magicKW16;  // exact for tap * KW < 65536 (checked by the launcher)
     auto tap_load = [&](int t, int kwd, uint32_t *out) {
-        bool ok = kwd < g.Kw;
-        const int kc = ok ? kwd : 0;
-        const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
-        const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
+        const int tap = (int)(mad24((uint32_t)kwd, g.tapMul, 0u) >> g.tapShift), c = mad24s(tap, -g.Cw, kwd);
+        const int kh = (int)(mad24((uint32_t)tap, magicKW16, 0u) >> 16), kw = mad24s(kh, -g.KW, tap);
         const int ih = ih0[t] + kh, iw = iw0[t] + kw;
-        ok = ok && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
-        const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
-        const uint32_t *p = srcA[t] + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
-        if (VEC == 4) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(p);
-            out[0] = ok ? q.x : 0u; out[1] = ok ? q.y : 0u; out[2] = ok ? q.z : 0u; out[3] = ok ? q.w : 0u;
-        } else if (VEC == 2) {
-            const uint2 q = *reinterpret_cast<const uint2 *>(p);
-            out[0] = ok ? q.x : 0u; out[1] = ok ? q.y : 0u;
-        } else {
-            const uint32_t q = *p;
-            out[0] = ok ? q : 0u;
-        }
+        const bool ok = kwd < g.Kw && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
+        const uint32_t delta = mad24(mad24((uint32_t)kh, (uint32_t)g.Wd, (uint32_t)kw), pixel_bytes, (uint32_t)c << 2);
+        load_words<VEC>(rA, ok ? offA[t] + delta : kOutOfRange, out);
     };
     auto fetchA = [&](int kbase) {
         if (CONV) {
@@ -203,13 +269,9 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
             }
         }
         if (!CONV) {
-            if (kbase + 16 <= g.Kw) {
+            const bool guard = kbase + 16 > g.Kw;
 #pragma unroll
-                for (int t = 0; t < NA; ++t) stageA[t] = load4<VEC>(srcA[t] + kbase);
-            } else {
-#pragma unroll
-                for (int t = 0; t < NA; ++t) stageA[t] = load4_tail<VEC>(srcA[t] + kbase, kbase + k4A[t] * 4, g.Kw);
-            }
+            for (int t = 0; t < NA; ++t) stageA[t] = fetch_row(rA, offA[t] + 4u * kbase, kbase + k4A[t] * 4, guard);
         }
     };
     auto commit = [&]() {

@@ -41,7 +41,8 @@ struct ContractArgs {
     int vec;            // widest aligned load, in words, usable on both operands (4, 2 or 1)
     int half_rows;      // block kernel: tiles of half the usual height (32 instead of 64 rows, 16 instead of 32)
     int xcd_split;      // block kernel: 0, or 1 + log2(c) of the r x c split (r * c = 8) of the tile grid over the 8 dies
-    uint32_t a_bytes;   // panel kernel: size of the activation tensor in bytes (at most 2^31)
+    uint32_t a_bytes;   // panel and per-wave kernels: size of the activation tensor in bytes (at most 2^31)
+    uint32_t w_bytes;   // per-wave kernel: size of the weight tensor in bytes (at most 2^31)
     // Null in the library.  The benchmark's probe library builds the block kernel a second time with
     // DLRT_CLOCK_PROBE: each block then leaves here how many shader-clock cycles and how many ticks of the
     // constant-rate counter it lived ([2 * block], [2 * block + 1]), i.e. the clock the chip ran the kernel at.
@@ -49,6 +50,9 @@ struct ContractArgs {
     // convolution geometry (unused by GEMM)
     int H, Wd, Cw, KH, KW, Ho, Wo, sh, sw, ph, pw;
     uint32_t magicCw, magicKW;  // ceil(2^32 / Cw), ceil(2^32 / KW); 0 stands for a divisor of 1
+    uint32_t tapMul, tapShift;  // per-wave kernel: word / Cw = (word * tapMul) >> tapShift: (1, log2 Cw) for a power of two,
+                                // else (ceil(2^16 / Cw), 16), exact while Kw * Cw < 2^16
+    uint32_t magicKW16;         // ceil(2^16 / KW): tap / KW = (tap * magicKW16) >> 16 while tap * KW < 2^16
     uint32_t magicHW, magicWo;  // the same for Ho * Wo and Wo (output row -> image, pixel); 1: divide in hardware
 };
 

@@ -215,7 +215,8 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
         elif kind == BLOCK:
             full = 16 * [4, 4, 2, 2][a - 1]
             assert (cols, ks) == (16 * [4, 4, 2, 2][w - 1], 1) and rows in (full, full // 2)
-            assert 2 * N > cols                                             # a tile is never mostly padding
+            # a tile is never mostly padding, unless an operand is too large for the per-wave kernel's 32-bit offsets
+            assert 2 * N > cols or M * a * Kw * 4 > 2 ** 31 or N * w * Kw * 4 > 2 ** 31
         else:
             tm = rows // (2 * tn)
             assert cols == 32 and rows == 2 * tn * tm and tm in (1, 2, 4) and ks in (1, 2, 4, 8)
@@ -242,6 +243,8 @@ def test_hints_override_the_plan_or_are_refused(lib):
                                 (big, (256, 1), ERR_SHAPE),       # 36 words are 3 panels of 12: two waves cannot share them
                                 (big, (640, 1), ERR_SHAPE),       # at most four waves share a tile
                                 (big, (200, 1), ERR_SHAPE),
+                                # 14 GB of activations: beyond the 32-bit offsets of the per-wave kernel
+                                ([1, 30000, 30000, 64, 16, 3, 3, 1, 1, 1, 1], (8, 1), ERR_SHAPE),
                                 (big, (64, 1), ERR_SHAPE)):       # 36 words do not fit a lane's registers
         if expect is not None:  # refused on the host: nothing is launched, so fake pointers are safe
             assert f(FAKE, FAKE, FAKE, NULL, *shape, *enc, FAKE, NULL, NULL, NULL, 2, hint[0], hint[1], NULL) == expect
