@@ -380,24 +380,35 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
             total[r][s] = sum;
         }
 
-    // ---- add the slices of the other waves (the sum is linear in the slices) ----
+    // ---- add the slices of the other waves (the sum is linear in the slices).  A wave leaves its partial sums
+    // in its OWN staging region (it is done with it; nobody else ever touches it), so one barrier is enough, and
+    // wave 0 fetches all of them before it adds any: up to seven independent rounds of LDS reads in flight
+    // instead of a loop of dependent ones (a region beyond ksplit reads wave 0's own, and is not added). ----
     if (ksplit > 1) {
-        int *red = reinterpret_cast<int *>(lds);
-        __syncthreads();  // every wave is done with its staging region
         if (ks > 0) {
+            int *mine = reinterpret_cast<int *>(la) + lane;
 #pragma unroll
             for (int r = 0; r < TM; ++r)
 #pragma unroll
-                for (int s = 0; s < TN; ++s) red[((ks - 1) * TM * TN + r * TN + s) * 64 + lane] = total[r][s];
+                for (int s = 0; s < TN; ++s) mine[(r * TN + s) * 64] = total[r][s];
         }
         __syncthreads();
         if (ks > 0) return;
-        for (int k = 1; k < ksplit; ++k) {
+        int part[7][TM][TN];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            const int *theirs = reinterpret_cast<const int *>(lds + (k < ksplit ? k : 0) * (UA + UW)) + lane;
 #pragma unroll
             for (int r = 0; r < TM; ++r)
 #pragma unroll
-                for (int s = 0; s < TN; ++s) total[r][s] += red[((k - 1) * TM * TN + r * TN + s) * 64 + lane];
+                for (int s = 0; s < TN; ++s) part[k - 1][r][s] = theirs[(r * TN + s) * 64];
         }
+#pragma unroll
+        for (int k = 1; k < 8; ++k)
+#pragma unroll
+            for (int r = 0; r < TM; ++r)
+#pragma unroll
+                for (int s = 0; s < TN; ++s) total[r][s] += k < ksplit ? part[k - 1][r][s] : 0;
     }
 
     // ---- fused epilogue on the registers of wave 0.  A wave at batch 1 is alone on its SIMD, so every taken
