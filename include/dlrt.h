@@ -150,7 +150,7 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  * only out_acc is given; bias may be NULL; qbits in 1..4 (read when out_q or out_packed is given).
  * out_packed must be 16-byte aligned.  tile_rows and ksplit are tuning hints for the latency-oriented
  * kernel that small layers get: 0 lets the library plan (large problems then take the throughput kernel,
- * which has no hints); otherwise tile_rows is the number of output pixels per wave tile (8, 16 or 32 for
+ * which has no hints); otherwise tile_rows is the number of output pixels per wave tile (4, 8, 16 or 32 for
  * wbits <= 2; 4, 8 or 16 for wbits >= 3) and ksplit (1, 2, 4, 8) the number of waves that split the
  * reduction; a combination the kernels do not have (more than 72 accumulators per lane, or more
  * than 64 KB of LDS per block) returns DLRT_ERR_SHAPE.  tile_rows = 64 asks for the row kernel (one output

@@ -51,6 +51,18 @@ template <int N>
 __device__ __forceinline__ void and_popc_group(int (&acc)[N], uint32_t a, const uint32_t (&w)[N]);
 
 template <>
+__device__ __forceinline__ void and_popc_group<2>(int (&acc)[2], uint32_t a, const uint32_t (&w)[2])
+{
+    uint32_t t0, t1;
+    asm("v_and_b32 %2, %4, %5\n\t"
+        "v_and_b32 %3, %4, %6\n\t"
+        "v_bcnt_u32_b32 %0, %2, %0\n\t"
+        "v_bcnt_u32_b32 %1, %3, %1"
+        : "+v"(acc[0]), "+v"(acc[1]), "=&v"(t0), "=&v"(t1)
+        : "v"(a), "v"(w[0]), "v"(w[1]));
+}
+
+template <>
 __device__ __forceinline__ void and_popc_group<4>(int (&acc)[4], uint32_t a, const uint32_t (&w)[4])
 {
     uint32_t t0, t1;

@@ -146,14 +146,20 @@ struct WavePlan {
 // best in total and within 8 % on every single layer.
 WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hint, int ksplit_hint)
 {
-    const int tn = wbits <= 2 ? 4 : 2, ly = 2 * tn;
     const int steps = (Kw + 3) / 4;
     WavePlan best{1, 1, false};
     double best_cost = 1e300;
-    for (int tm = 1; tm <= 4; tm *= 2) {
-        if (tm * tn * abits * wbits > 72) break;
-        if (tile_rows_hint > 0 && ly * tm != tile_rows_hint) continue;
-        const int rows = ly * tm;
+    // tm = 0: the half tile of 4 rows x 32 columns that narrow weights have besides their 8-row one (2 columns per
+    // lane instead of 4).  Half the work per wave and twice the tiles: it pays where the 8-row tiles are so few that
+    // most compute units would stay idle while a few run all the waves of a deep reduction (a 7 x 7 layer over 512
+    // channels is 112 tiles of 8 rows, each split over 8 waves on ONE compute unit).  Only then, or by hint.
+    const bool few_tiles = (int64_t)((M + 7) / 8) * ((N + 31) / 32) <= 128;
+    for (int tm = wbits <= 2 ? 0 : 1; tm <= 4; tm = tm ? tm * 2 : 1) {
+        const int tn = wbits <= 2 && tm > 0 ? 4 : 2, ly = 2 * tn, tmv = tm ? tm : 1;
+        if (tmv * tn * abits * wbits > 72) break;
+        const int rows = ly * tmv;
+        if (tile_rows_hint > 0 && rows != tile_rows_hint) continue;
+        if (tm == 0 && tile_rows_hint == 0 && !few_tiles) continue;
         const int64_t tiles = (int64_t)((M + rows - 1) / rows) * ((N + 31) / 32);
         for (int ks = 1; ks <= 8; ks *= 2) {
             if (ksplit_hint > 0 && ks != ksplit_hint) continue;
@@ -164,9 +170,9 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
             // a lone wave keeps a SIMD about 70 % busy; with several waves per SIMD they cover each other
             const double over = (double)tiles * ks / 1024;
             const double eff = over <= 1 ? 0.7 : (0.7 + 0.12 * (over - 1) < 0.95 ? 0.7 + 0.12 * (over - 1) : 0.95);
-            const double valu = (double)spw * 4 * tm * tn * abits * wbits * 2 * 4 / eff;
+            const double valu = (double)spw * 4 * tmv * tn * abits * wbits * 2 * 4 / eff;
             const double load = (double)spw * (abits * rows + wbits * 32) * 16 / 32;
-            const double cost = (valu + load) * (over > 1 ? over : 1.0) + (ks > 1 ? 500 + 120 * ks : 0) + (tm - 1) * 150;
+            const double cost = (valu + load) * (over > 1 ? over : 1.0) + (ks > 1 ? 500 + 120 * ks : 0) + (tmv - 1) * 150;
             if (cost < best_cost) { best_cost = cost; best = WavePlan{tm, ks, true}; }
         }
     }
@@ -286,7 +292,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
     if (!wave && prefer_half_rows(M, N, abits, wbits)) rows /= 2;
     if (wave) {
         const WavePlan p = plan_wave(M, N, Kw, abits, wbits, 0, 0);
-        rows = (wbits <= 2 ? 8 : 4) * p.tm;
+        rows = p.tm ? (wbits <= 2 ? 8 : 4) * p.tm : 4;
         cols = 32;
         ks = p.ksplit;
     }

@@ -116,7 +116,9 @@ __device__ __forceinline__ uint32_t or_across(uint32_t v)
 
 // One launch can carry two independent problems of the same bit widths (e.g. the two convolutions that
 // read the same activations): blockIdx.y picks the problem.
-template <int AB, int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
+// TN: output columns per lane (4 for 1- and 2-bit weights, 2 for wider ones; 2 also for narrow weights in the
+// "half" tile of (64 / 16) * TM = 4 rows, for layers with so few rows that 8-row tiles leave most of the chip idle).
+template <int AB, int WB, int TM, int VEC, bool BIPOLAR, bool CONV, int TN>
 __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair pair, const int ksplit)
 {
     const int which = blockIdx.y;
@@ -136,7 +138,6 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
                  "s"(g.magicCw), "s"(g.magicKW), "s"(g.magicHW), "s"(g.magicWo), "s"(o.acc), "s"(o.y), "s"(o.q),
                  "s"(o.packed), "s"(o.scale), "s"(o.bias), "s"(o.qbits), "s"(steps_base), "s"(steps_rem));
     if (tile >= tiles) return;  // the other problem of the pair has more tiles
-    constexpr int TN = WaveTN<WB>::value;
     constexpr int LX = 32 / TN, LY = 64 / LX;
     constexpr int ROWS = LY * TM;     // rows of the wave tile; it is 32 columns wide
     constexpr int UA = 4 * AB * ROWS; // 16-byte units of one staged A chunk (4 steps x planes x rows)
@@ -474,11 +475,10 @@ __global__ __launch_bounds__(512) void contract_wave_kernel(const dlrt::WavePair
     }
 }
 
-template <int WB, int TM, int VEC, bool BIPOLAR, bool CONV>
+template <int WB, int TM, int VEC, bool BIPOLAR, bool CONV, int TN = WaveTN<WB>::value>
 dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int ksplit, hipStream_t stream)
 {
     constexpr int AB = DLRT_ABITS;
-    constexpr int TN = WaveTN<WB>::value;
     if constexpr (TM * TN * AB * WB > 72) {
         return DLRT_ERR_SHAPE;  // never planned: too many accumulators per lane
     } else {
@@ -514,24 +514,29 @@ dlrt_status launch(const ContractArgs *g, const FusedOut *o, int count, int kspl
             if (t > tiles) tiles = t;
         }
         const size_t lds_bytes = (size_t)ksplit * units * 16;
-        return dlrt::enqueue(contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV>, dim3((unsigned)tiles, (unsigned)count),
+        return dlrt::enqueue(contract_wave_kernel<AB, WB, TM, VEC, BIPOLAR, CONV, TN>, dim3((unsigned)tiles, (unsigned)count),
                              dim3(64 * ksplit), lds_bytes, stream, pair, ksplit);
     }
 }
 
-template <int WB, int TM, bool BIPOLAR, bool CONV>
+template <int WB, int TM, bool BIPOLAR, bool CONV, int TN = WaveTN<WB>::value>
 dlrt_status pick_vec(const ContractArgs *g, const FusedOut *o, int count, int ksplit, hipStream_t stream)
 {
     int vec = g[0].vec;  // both problems of a pair are loaded with the narrower of their widths
     if (count > 1 && g[1].vec < vec) vec = g[1].vec;
-    if (vec == 4) return launch<WB, TM, 4, BIPOLAR, CONV>(g, o, count, ksplit, stream);
-    if (vec == 2) return launch<WB, TM, 2, BIPOLAR, CONV>(g, o, count, ksplit, stream);
-    return launch<WB, TM, 1, BIPOLAR, CONV>(g, o, count, ksplit, stream);
+    if (vec == 4) return launch<WB, TM, 4, BIPOLAR, CONV, TN>(g, o, count, ksplit, stream);
+    if (vec == 2) return launch<WB, TM, 2, BIPOLAR, CONV, TN>(g, o, count, ksplit, stream);
+    return launch<WB, TM, 1, BIPOLAR, CONV, TN>(g, o, count, ksplit, stream);
 }
 
+// tm: rows per lane (1, 2, 4), or 0 for the half tile of 4 rows (1- and 2-bit weights; wider ones have it as tm = 1)
 template <int WB, bool BIPOLAR, bool CONV>
 dlrt_status pick_tm(const ContractArgs *g, const FusedOut *o, int count, int tm, int ksplit, hipStream_t stream)
 {
+    if constexpr (WB <= 2) {
+        if (tm == 0) return pick_vec<WB, 1, BIPOLAR, CONV, 2>(g, o, count, ksplit, stream);
+    }
+    if (tm == 0) return DLRT_ERR_SHAPE;
     if (tm == 4) return pick_vec<WB, 4, BIPOLAR, CONV>(g, o, count, ksplit, stream);
     if (tm == 2) return pick_vec<WB, 2, BIPOLAR, CONV>(g, o, count, ksplit, stream);
     return pick_vec<WB, 1, BIPOLAR, CONV>(g, o, count, ksplit, stream);

@@ -607,9 +607,11 @@ def test_conv_fused_every_tile_height_and_reduction_split_gives_the_same_result(
     """The tuning hints select the wave tile and how many waves split the reduction; all must agree."""
     x = inputs.uniform_values((1, 13, 11, 160), 2, UNSIGNED, 777)
     w = inputs.uniform_values((72, 3, 3, 160), 2, TWOS, 778)
-    for tile_rows in (8, 16, 32):
+    for tile_rows in (4, 8, 16, 32):  # 4: the half tile (two columns per lane) that narrow weights have besides the others
         for ksplit in (1, 2, 4, 8):
             fused_case(dlrt, oracle, x, w, 1, 1, 2, 2, UNSIGNED, TWOS, 2, tile_rows, ksplit)
+            if tile_rows == 4:
+                fused_case(dlrt, oracle, x, w, 1, 1, 2, 2, UNSIGNED, TWOS, 2, tile_rows, ksplit, packed_only=True)
     x4 = inputs.uniform_values((1, 9, 9, 96), 4, UNSIGNED, 779)
     w4 = inputs.uniform_values((40, 3, 3, 96), 4, TWOS, 780)
     for tile_rows in (4, 8):
@@ -619,6 +621,17 @@ def test_conv_fused_every_tile_height_and_reduction_split_gives_the_same_result(
     wb = inputs.uniform_values((33, 3, 3, 64), 1, BIPOLAR, 782)
     for ksplit in (1, 2, 4):
         fused_case(dlrt, oracle, xb, wb, 1, 1, 2, 1, UNSIGNED, BIPOLAR, 2, 8, ksplit)
+        fused_case(dlrt, oracle, xb, wb, 1, 1, 2, 1, UNSIGNED, BIPOLAR, 2, 4, ksplit)
+    # few rows, many channels, a deep reduction: the planner's own choice is the half tile here
+    xs = inputs.uniform_values((1, 7, 7, 256), 2, UNSIGNED, 783)
+    ws = inputs.uniform_values((96, 3, 3, 256), 2, TWOS, 784)
+    assert dlrt.dlrt_query_plan(49, 96, 9 * 256, 2, 2)["tile_rows"] == 4
+    fused_case(dlrt, oracle, xs, ws, 1, 1, 2, 2, UNSIGNED, TWOS, 2)
+    fused_case(dlrt, oracle, xs, ws, 1, 1, 2, 2, UNSIGNED, TWOS, 2, packed_only=True)
+    x1 = inputs.uniform_values((1, 5, 5, 128), 1, UNSIGNED, 785)
+    w1 = inputs.uniform_values((64, 3, 3, 128), 1, TWOS, 786)
+    for ksplit in (1, 4):
+        fused_case(dlrt, oracle, x1, w1, 1, 1, 1, 1, UNSIGNED, TWOS, 1, 4, ksplit)   # two accumulators per activation word
 
 
 def test_conv_fused_pair_two_problems_in_one_launch(dlrt, oracle):
