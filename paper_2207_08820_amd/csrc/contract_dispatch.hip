@@ -189,11 +189,17 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
 // pays for 1- and 2-bit weights (A4W4 measured half the block kernel's speed).
 int64_t row_kernel_waves(int64_t M, int N) { return ((M + 63) / 64) * ((N + 31) / 32); }
 
-bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits)
+// `halves`: the call may use waves of 8 or 16 columns (nothing but the packed output, unsigned activations, whole
+// output words).  Such waves fill the chip at a quarter of the rows, which moves the row kernel's territory down to
+// single images: from 800 waves of 8 columns on it measured 5 to 25 % faster than the tiled kernels on every
+// layer tried with a reduction of up to 9 words, or 18 (6400 .. 25600 pixels x 32 .. 128 channels, A2W1), slower
+// below (1600 pixels x 128 channels, 3136 x 64 at 18 words).
+bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits, bool halves)
 {
     if (!dlrt::row_kernel_has(Kw) || (Kw > 16 && wbits > 2)) return false;
     if (M < 2048) return false;  // lanes idle on few rows (none measured below 3136)
-    if (((M + 63) / 64 + 7) * ((N + 31) / 32) > 0x7fffffffLL) return false;  // more blocks than a grid holds
+    if (((M + 63) / 64 + 7) * ((N + 7) / 8) > 0x7fffffffLL) return false;  // more blocks than a grid holds
+    if (halves && N % 32 == 0 && (Kw <= 9 || Kw == 18) && ((M + 63) / 64) * (N / 8) >= 800) return true;
     const int64_t from = Kw == 1 ? 256 : Kw == 2 ? 384 : Kw <= 4 ? 1024 : Kw <= 9 ? 1536 : Kw <= 16 ? 12288 : 3072;
     return row_kernel_waves(M, N) >= from;
 }
@@ -254,7 +260,11 @@ int plan_rows(int64_t M, int N, int Kw, int abits, int wbits, bool halves, bool 
 {
     const int64_t row_blocks = (M + 63) / 64;
     int ncols = 32;
-    if (halves && N % 32 == 0 && row_blocks * (N / 32) >= 1024) {
+    if (halves && N % 32 == 0 && row_blocks * (N / 32) < 1024) {
+        // a launch that cannot fill the chip with 32-column waves (single images): the widest waves that still make
+        // about 1500 of them, else the narrowest (measured on eight such layers: the best or within 3 % of it)
+        ncols = row_blocks * (N / 16) >= 1536 ? 16 : 8;
+    } else if (halves && N % 32 == 0) {
         auto cost = [&](int nc) {
             const double per_simd = (double)(row_blocks * (N / nc)) / 1024.0;
             const double column = 2.0 * abits * wbits * Kw + 10.0;  // AND/BCNT pairs and the epilogue of one output
@@ -275,7 +285,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
     const bool wave = prefer_wave_kernel(M, N, abits, wbits) && (int64_t)M * abits * Kw * 4 <= (1LL << 31) &&
                       (int64_t)N * wbits * Kw * 4 <= (1LL << 31);  // (its operands are addressed with 32-bit offsets)
     int rows = block_tile(abits), cols = block_tile(wbits), ks = 1;
-    if (prefer_rows_kernel(M, N, Kw, wbits)) {
+    if (prefer_rows_kernel(M, N, Kw, wbits, true)) {  // (as for a chained layer: packed output only)
         if (block_kernel) *block_kernel = 2;
         if (tile_rows) *tile_rows = 64;
         if (tile_cols) *tile_cols = plan_rows(M, N, Kw, abits, wbits, true, true);  // as for a chained conv layer (packed output only)
@@ -311,7 +321,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
     const bool halves = o.packed && !o.acc && !o.y && !o.q && !a_msb_neg;
-    if (prefer_rows_kernel(M, N, Kw, wbits))
+    if (prefer_rows_kernel(M, N, Kw, wbits, halves))
         return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves, false), stream);
     const int64_t a_bytes = (int64_t)M * abits * Kw * 4;
     if (prefer_panel_kernel(M, N, Kw, abits, wbits) && panel_kernel_has(g, abits, wbits, false, 8, a_bytes)) {
@@ -376,7 +386,7 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     for (int i = 0; i < 2; ++i) {
         const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
         const int Kw = c[i].KH * c[i].KW * c[i].Cw;
-        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw, wbits);
+        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw, wbits, o[i].packed && !o[i].acc && !o[i].y && !o[i].q && !a_msb_neg);
     }
     if (!pairable) {
         for (int i = 0; i < 2; ++i) {
@@ -402,7 +412,8 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
     const bool conv = !pointwise(c);
     const bool rows_fit = row_kernel_has(g.Kw);
     const int64_t x_bytes = (int64_t)c.N * c.H * c.W * abits * c.Cw * 4;
-    const int rows_ncols = plan_rows(g.M, g.N, g.Kw, abits, wbits, o.packed && !o.acc && !o.y && !o.q && !a_msb_neg, conv);
+    const bool halves = o.packed && !o.acc && !o.y && !o.q && !a_msb_neg;
+    const int rows_ncols = plan_rows(g.M, g.N, g.Kw, abits, wbits, halves, conv);
     if (tile_rows >= 128 && tile_rows % 128 == 0) {  // hint: the panel kernel, 8 * ksplit columns per block,
         const int ncols = ksplit == 0 ? 8 : 8 * ksplit, kwaves = tile_rows / 128;  // tile_rows / 128 waves sharing the reduction
         if (kwaves > kPanelMaxWaves || !panel_kernel_has(g, abits, wbits, conv, ncols, x_bytes, kwaves)) return DLRT_ERR_SHAPE;
@@ -414,7 +425,7 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
         if (!rows_fit || ksplit < 0 || ksplit > 8192) return DLRT_ERR_SHAPE;
         return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 8 * ksplit : rows_ncols, stream);
     }
-    if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits))
+    if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits, halves))
         return launch_rows(g, o, abits, wbits, bipolar, conv, rows_ncols, stream);
     if (tile_rows == 0 && ksplit == 0 && prefer_panel_kernel(g.M, g.N, g.Kw, abits, wbits) &&
         panel_kernel_has(g, abits, wbits, conv, 8, x_bytes)) {
