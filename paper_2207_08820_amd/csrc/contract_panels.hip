@@ -123,8 +123,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void contract_panel_kernel(const Co
     static_assert(P % 4 == 0 && NC % 8 == 0, "panels of whole 16-byte groups, whole output bytes");
     constexpr int G = P / 4;                 // 16-byte groups per panel and plane
     // The block's weights, zero beyond Kw / N: [panel][NC * WB][G] groups, so that within a panel every read is
-    // the panel's base address plus a compile-time offset.  Behind them, when several waves share the reduction,
-    // the partial sums of waves 1 .. kwaves - 1.
+    // the panel's base address plus a compile-time offset.  When several waves share the reduction, the partial
+    // sums of waves 1 .. kwaves - 1 take the same memory after the last panel.
     extern __shared__ uint4 lds[];
 
     const int lane = threadIdx.x & 63;
@@ -184,7 +184,10 @@ __global__ __launch_bounds__(64 * kMaxWaves) void contract_panel_kernel(const Co
     const uint32_t pixel_bytes = AB * g.Cw * 4;
     // byte offset of the lane's tap (0, 0), which may lie outside the image (the sum wraps; only taps inside the
     // image are ever used, and for those the per-tap delta brings it back in range)
-    const uint32_t tap00 = lane_base + ((uint32_t)ih0 * (uint32_t)g.Wd + (uint32_t)iw0) * pixel_bytes;
+    uint32_t tap00 = lane_base + ((uint32_t)ih0 * (uint32_t)g.Wd + (uint32_t)iw0) * pixel_bytes;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(tap00));  // kept as one value: a tap's offset is then one add, not the pixel arithmetic over again
+#endif
 
     int acc[NC][AB][WB];
 #pragma unroll
@@ -261,7 +264,9 @@ __global__ __launch_bounds__(64 * kMaxWaves) void contract_panel_kernel(const Co
     // block share the row block, so the early exit above takes all of them or none.) ----
     if (kwaves > 1) {
         constexpr int SLOTS = NC * AB * WB + (BIPOLAR ? AB : 0);
-        int *red = reinterpret_cast<int *>(lds + panels * (NC * WB * G));  // [wave - 1][slot][lane]
+        // [wave - 1][slot][lane], in place of the weights, which no wave reads any more once all have arrived
+        int *red = reinterpret_cast<int *>(lds);
+        __syncthreads();
         if (wave > 0) {
             int *mine = red + (wave - 1) * (SLOTS * 64) + lane;
 #pragma unroll
@@ -369,8 +374,9 @@ dlrt_status launch_one(const ContractArgs &g, const FusedOut &o, int kwaves, hip
     constexpr int AB = DLRT_ABITS;
     const int panels = (g.Kw + P - 1) / P;
     if (kwaves < 1 || kwaves > kMaxWaves || panels % kwaves != 0) return DLRT_ERR_SHAPE;
-    // the block's weights over the padded reduction, and the partial sums of the waves beyond the first
-    const size_t lds_bytes = (size_t)NC * WB * panels * P * 4 + (size_t)(kwaves - 1) * (NC * AB * WB + AB) * 64 * 4;
+    // the block's weights over the padded reduction; later, in their place, the partial sums of the waves beyond the first
+    const size_t w_bytes = (size_t)NC * WB * panels * P * 4, sum_bytes = (size_t)(kwaves - 1) * (NC * AB * WB + AB) * 64 * 4;
+    const size_t lds_bytes = w_bytes > sum_bytes ? w_bytes : sum_bytes;
     if (lds_bytes > 65536) return DLRT_ERR_SHAPE;
     const int64_t bx = ((int64_t)g.M + 63) / 64, by = (g.N + NC - 1) / NC;
     const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies

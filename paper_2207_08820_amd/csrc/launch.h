@@ -125,7 +125,9 @@ inline bool panel_kernel_has(const ContractArgs &g, int abits, int wbits, bool c
     const int p = panel_words(g.Kw, kwaves);
     if (p == 0) return false;
     const int64_t padded = (int64_t)((g.Kw + p - 1) / p) * p;  // words per column and plane
-    const int64_t lds = ncols * wbits * padded * 4 + (int64_t)(kwaves - 1) * (ncols * abits * wbits + abits) * 256;
+    // the weights, and in their place after the last panel the partial sums of the waves beyond the first
+    const int64_t lds_w = ncols * wbits * padded * 4, lds_sums = (int64_t)(kwaves - 1) * (ncols * abits * wbits + abits) * 256;
+    const int64_t lds = lds_w > lds_sums ? lds_w : lds_sums;
     if (g.Kw % 4 != 0 || g.vec != 4 || ncols * abits * wbits > 64 || lds > 65536) return false;
     if (a_bytes > (1LL << 31)) return false;
     return !conv || g.Cw % 4 == 0;

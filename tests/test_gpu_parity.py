@@ -555,7 +555,7 @@ def test_conv_fused_panel_kernel_all_encodings(dlrt, oracle, shape):
             g = groups[-1]
             P = panel_words(Kw, s)
             # the block's weights over the padded reduction and the partial sums of the waves beyond the first
-            lds = 8 * max(g, 1) * wbits * (-(-Kw // P) * P if P else 0) * 4 + (s - 1) * (8 * max(g, 1) * abits * wbits + abits) * 256
+            lds = max(8 * max(g, 1) * wbits * (-(-Kw // P) * P if P else 0) * 4, (s - 1) * (8 * max(g, 1) * abits * wbits + abits) * 256)
             if P and lds <= 65536:
                 fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128 * s, ksplit=g)
                 fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=128 * s, ksplit=g,
