@@ -157,7 +157,9 @@ dlrt_status dlrt_bitserial_conv2d(const uint32_t *X, const uint32_t *Wp, int32_t
  * pixel per lane; convolutions with KH*KW*ceil(Ci/32) <= 16 or = 18, DLRT_ERR_SHAPE otherwise);
  * ksplit then is the number of 8-column groups a wave covers (0: planned; 4 n for whole output words, or 1 or 2,
  * which need Co a multiple of 32, unsigned activations and no output but out_packed; DLRT_ERR_SHAPE
- * otherwise).  tile_rows = 128 asks for the panel
+ * otherwise; a negative count -n: units of 8 n columns of which as many as the chip's dies all have go out as
+ * two waves of 4 n columns each, the form the planner gives the last units of a large launch; 4 n must
+ * itself be a width that exists).  tile_rows = 128 asks for the panel
  * kernel (one output pixel per lane, the reduction walked in panels against weights held in LDS; needs Ci a
  * multiple of 128, abits * wbits * 8 * ksplit <= 64 and at most 2^31 bytes of activations, DLRT_ERR_SHAPE
  * otherwise); ksplit (0 or 1, 2, 4) then is the number of 8-column groups a wave covers.  The result does not

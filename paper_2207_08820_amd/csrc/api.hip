@@ -201,7 +201,7 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
                                         uint32_t *out_packed, int qbits, int tile_rows, int ksplit, void *stream)
 {
     if (dlrt_status s = check_encodings(abits, wbits, enc_a, enc_w)) return s;
-    if (tile_rows < 0 || ksplit < 0) return DLRT_ERR_SHAPE;
+    if (tile_rows < 0 || (ksplit < 0 && tile_rows != 64)) return DLRT_ERR_SHAPE;  // (a negative width is a row-kernel hint)
     const dlrt_conv_problem p{X, Wp, scale, bias, N, H, W, Ci, Co, KH, KW, stride_h, stride_w, pad_h, pad_w,
                               out_acc, out_f32, out_q, out_packed, qbits};
     dlrt::ConvShape c{};

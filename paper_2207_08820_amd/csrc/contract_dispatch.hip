@@ -69,13 +69,13 @@ dlrt_status wave_by_abits(const dlrt::ContractArgs *g_in, const dlrt::FusedOut *
 }
 
 dlrt_status launch_rows(const dlrt::ContractArgs &g, const dlrt::FusedOut &o, int abits, int wbits, bool bipolar,
-                        bool conv, int ncols, hipStream_t stream)
+                        bool conv, int ncols, int fine_units, hipStream_t stream)
 {
     switch (abits) {
-    case 1: return dlrt::launch_rows_a1(g, o, wbits, bipolar, conv, ncols, stream);
-    case 2: return dlrt::launch_rows_a2(g, o, wbits, bipolar, conv, ncols, stream);
-    case 3: return dlrt::launch_rows_a3(g, o, wbits, bipolar, conv, ncols, stream);
-    case 4: return dlrt::launch_rows_a4(g, o, wbits, bipolar, conv, ncols, stream);
+    case 1: return dlrt::launch_rows_a1(g, o, wbits, bipolar, conv, ncols, fine_units, stream);
+    case 2: return dlrt::launch_rows_a2(g, o, wbits, bipolar, conv, ncols, fine_units, stream);
+    case 3: return dlrt::launch_rows_a3(g, o, wbits, bipolar, conv, ncols, fine_units, stream);
+    case 4: return dlrt::launch_rows_a4(g, o, wbits, bipolar, conv, ncols, fine_units, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -322,7 +322,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     g.vec = va < vw ? va : vw;
     const bool halves = o.packed && !o.acc && !o.y && !o.q && !a_msb_neg;
     if (prefer_rows_kernel(M, N, Kw, wbits, halves))
-        return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves, false), stream);
+        return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves, false), -1, stream);
     const int64_t a_bytes = (int64_t)M * abits * Kw * 4;
     if (prefer_panel_kernel(M, N, Kw, abits, wbits) && panel_kernel_has(g, abits, wbits, false, 8, a_bytes)) {
         g.a_bytes = (uint32_t)a_bytes;
@@ -422,11 +422,13 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
         return launch_panels(gp, o, abits, wbits, bipolar, conv, ncols, kwaves, stream);
     }
     if (tile_rows == 64) {  // hint: the row kernel, 8 * ksplit columns per wave
-        if (!rows_fit || ksplit < 0 || ksplit > 8192) return DLRT_ERR_SHAPE;
-        return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 8 * ksplit : rows_ncols, stream);
+        if (!rows_fit || ksplit < -8192 || ksplit > 8192) return DLRT_ERR_SHAPE;
+        // a positive hint: every wave that wide; a negative one: as many units as possible as two waves of half the width
+        return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 8 * ksplit : ksplit < 0 ? -8 * ksplit : rows_ncols,
+                           ksplit < 0 ? -2 : 0, stream);
     }
     if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits, halves))
-        return launch_rows(g, o, abits, wbits, bipolar, conv, rows_ncols, stream);
+        return launch_rows(g, o, abits, wbits, bipolar, conv, rows_ncols, -1, stream);
     if (tile_rows == 0 && ksplit == 0 && prefer_panel_kernel(g.M, g.N, g.Kw, abits, wbits) &&
         panel_kernel_has(g, abits, wbits, conv, 8, x_bytes)) {
         ContractArgs gp = g;

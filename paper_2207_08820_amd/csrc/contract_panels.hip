@@ -132,13 +132,17 @@ __global__ __launch_bounds__(64 * kMaxWaves) void contract_panel_kernel(const Co
     const int kg = g.Kw >> 2;                // groups of the reduction
     const int my_panels = panels / kwaves, p_begin = wave * my_panels, p_end = p_begin + my_panels;
     const int kg_mine = my_panels * G;       // groups of this wave's panels (padded reduction)
-    // block -> (row block, column group): the column groups of one row block are numbered 8 apart, so that they
-    // run on the same die one after the other and the rows' activations reach that die's L2 once
+    // block -> tile (row block, column group).  Consecutive blocks go to the chip's 8 dies in turn, each with an L2
+    // of its own: die d takes the d-th eighth of the tiles in row-major order, so that the column groups of one row
+    // block run on the same die one after the other (the rows' activations reach that die's L2 once) and the dies
+    // get the same number of tiles to within one (dealing out whole row blocks left one die with 7 of 49 and the
+    // others with 6: a sixth more time than work).
     const int col_groups = (g.N + NC - 1) / NC;
-    const int die = blockIdx.x & 7, local = blockIdx.x >> 3;
-    const int row_group = local / col_groups, col_group = local - row_group * col_groups;
-    const int row_block = row_group * 8 + die;
-    if ((int64_t)row_block * 64 >= g.M) return;
+    const int64_t tiles = (int64_t)((g.M + 63) >> 6) * col_groups;
+    const int die = blockIdx.x & 7;
+    const int tile = (int)((tiles * die) >> 3) + (int)(blockIdx.x >> 3);
+    if (tile >= (int)((tiles * (die + 1)) >> 3)) return;
+    const int row_block = tile / col_groups, col_group = tile - row_block * col_groups;
     const int m = row_block * 64 + lane;
     const int mc = min(m, g.M - 1);          // rows beyond the matrix repeat the last row and are never stored
     const int n0 = col_group * NC;
@@ -379,7 +383,7 @@ dlrt_status launch_one(const ContractArgs &g, const FusedOut &o, int kwaves, hip
     const size_t lds_bytes = w_bytes > sum_bytes ? w_bytes : sum_bytes;
     if (lds_bytes > 65536) return DLRT_ERR_SHAPE;
     const int64_t bx = ((int64_t)g.M + 63) / 64, by = (g.N + NC - 1) / NC;
-    const int64_t blocks = (bx + 7) / 8 * 8 * by;  // row blocks padded to the 8 dies
+    const int64_t blocks = (bx * by + 7) / 8 * 8;  // the tiles, an eighth to each die
     if (blocks > 0x7fffffffLL) return DLRT_ERR_SHAPE;
     const uint32_t groups = (uint32_t)(panels / kwaves) * (P / 4);  // ceil(2^32 / groups), 0 standing for a divisor of 1
     const uint32_t magic_groups = groups == 1 ? 0u : (uint32_t)((0x100000000ULL + groups - 1) / groups);

@@ -115,26 +115,33 @@ __device__ __forceinline__ uint32_t byte_from_float(float v, uint32_t x)
 // 200704 x 64 x 576 and 50176 x 128 x 576 run 2 % faster (the last, thin round of waves is fuller).  Seven would spill.
 template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
 __global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock, (KW >= 16 && WB <= 2 ? 6 : 1)) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
-                                                                       const int ncols,
+                                                                       const int ncols_full,
+                                                                       const int fine_units /* per die, at most the fewest units a die has */,
                                                                        const uint32_t *__restrict__ Wp,
                                                                        const float *__restrict__ scale,
                                                                        const float *__restrict__ bias)
 {
     // Wp / scale / bias repeat g.W / o.scale / o.bias as parameters of their own: only a read-only
     // pointer that provably aliases none of the stores is loaded through the scalar unit.
-    // Block -> (row block, column group).  Consecutive blocks go to the chip's 8 dies in turn, each with an
-    // L2 of its own, so the column groups of one row block are numbered 8 apart (plus the die): they land on
-    // the same die, one after the other, and the row's activations come from HBM once however the grid divides.
-    // The grid is padded to a multiple of 8 row blocks; the surplus blocks leave here.
-    const int col_groups = (g.N + ncols - 1) / ncols;
+    // Wave -> unit (row block, column group).  Consecutive blocks go to the chip's 8 dies in turn, each with an L2
+    // of its own: die d takes the d-th eighth of the units in row-major order, so that the column groups of one row
+    // block run on the same die one after the other (the row's activations come from HBM once however the grid
+    // divides) and the dies get the same number of units to within one.  The waves beyond a die's units leave here.
+    const int col_groups = (g.N + ncols_full - 1) / ncols_full;
+    const int64_t units = (int64_t)((g.M + kRowsPerBlock - 1) / kRowsPerBlock) * col_groups;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform, and known to be
     const int die = blockIdx.x & 7, local = (blockIdx.x >> 3) * kWavesPerBlock + wave;
-    const int row_group = local / col_groups, col_group = local - row_group * col_groups;
-    const int row_block = row_group * 8 + die;
-    if ((int64_t)row_block * kRowsPerBlock >= g.M) return;
+    const int first = (int)((units * die) >> 3), mine = (int)((units * (die + 1)) >> 3) - first;
+    // the die's last `fine_units` units are two waves of half the columns each, the others one wave: the blocks
+    // handed out last are the small ones, and the launch's last round of waves a short one
+    const int coarse = mine - fine_units, fine = local - coarse;
+    if (fine >= 2 * fine_units) return;
+    const int unit = first + (fine < 0 ? local : coarse + (fine >> 1));
+    const int ncols = fine < 0 ? ncols_full : ncols_full >> 1;
+    const int row_block = unit / col_groups, col_group = unit - row_block * col_groups;
     const int m = row_block * kRowsPerBlock + (threadIdx.x & 63);
     const int mc = min(m, g.M - 1);  // rows beyond the matrix are computed on the last row, never stored
-    const int n0 = col_group * ncols, n1 = min(n0 + ncols, g.N);
+    const int n0 = col_group * ncols_full + (fine < 0 ? 0 : (fine & 1) * ncols), n1 = min(n0 + ncols, g.N);
 
     // ---- this lane's activation row: abits planes of Kw words, zero beyond Kw.  For a convolution the
     // row is the im2col row of the lane's output pixel: word k is channel word c of tap (kh, kw), zero where
@@ -397,50 +404,89 @@ __global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock, (KW >= 16 && WB <= 
     }
 }
 
-template <int AB, int WB, int KW, bool BIPOLAR>
-dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
+// Whether waves of `ncols` columns exist for this call: whole output words, or, on the path that writes nothing but
+// the packed output and only when N fills whole words (no ragged tail, no zero fill for anyone to own), 16 or 8
+// columns, written as halves or single bytes of the words.
+inline bool has_width(const ContractArgs &g, const FusedOut &o, int ncols)
 {
-    // Waves of 8 or 16 columns write single bytes or halves of the packed words: only on the path that writes
-    // nothing else, and only when N fills whole words (no ragged tail, no zero fill for anyone to own).
-    if (ncols < 32) {
-        const bool packed_only = o.packed && !o.acc && !o.y && !o.q && !g.a_msb_neg;
-        if ((ncols != 8 && ncols != 16) || !packed_only || g.N % 32 != 0) return DLRT_ERR_SHAPE;
-    } else if (ncols % 32 != 0) {
-        return DLRT_ERR_SHAPE;
-    }
+    if (ncols >= 32) return ncols % 32 == 0;
+    const bool packed_only = o.packed && !o.acc && !o.y && !o.q && !g.a_msb_neg;
+    return (ncols == 8 || ncols == 16) && packed_only && g.N % 32 == 0;
+}
+
+// The last units of a die as waves of half the width.  A die holds `slots` waves at once (its compute units x the
+// workgroups of this kernel that one holds x the waves of a workgroup), all of one length, so a launch runs in
+// rounds: 1568 units on 768 slots are two full rounds and a third of 32 waves, which takes a whole wave's time at
+// the low issue rate of a lone wave (measured: 200704 x 64 x 576 spends 5 % of its time there, 50176 x 128 x 576
+// 9 %).  When the last round is at most a third full, its units - and as many again, for the dies and compute
+// units do not fill evenly - go out as two waves of half the columns each: the short round takes half as long.
+// Measured over tails of 1 to 13 times the remainder: flat within 1 % between 1.5 and 5 times.
+inline int planned_fine_units(int64_t units, int resident, bool halves_exist)
+{
+    const int cus = dlrt::compute_units();
+    if (!halves_exist || resident <= 0 || cus < 8) return 0;
+    const int64_t slots = (int64_t)(cus / 8) * resident * kWavesPerBlock;
+    const int64_t rest = units % slots;
+    if (units < slots || rest == 0 || 3 * rest > slots) return 0;
+    const int64_t fine = 2 * rest > slots / 8 ? 2 * rest : slots / 8;
+    return (int)(fine < units ? fine : units);
+}
+
+// fine_units: how many of each die's (64 rows, ncols columns) units, the last ones, go out as two waves of half the
+// columns each; -1: planned, -2: as many as every die has
+template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
+dlrt_status launch_one(const ContractArgs &g, const FusedOut &o, int ncols, int fine_units, hipStream_t stream)
+{
+    constexpr auto kernel = contract_rows_kernel<AB, WB, KW, BIPOLAR, CONV>;
+    if (!has_width(g, o, ncols)) return DLRT_ERR_SHAPE;
     const int64_t bx = ((int64_t)g.M + kRowsPerBlock - 1) / kRowsPerBlock, by = (g.N + ncols - 1) / ncols;
-    // per die: its share of the row blocks (padded to the 8 dies) times the column groups, kWavesPerBlock to a block
-    const int64_t per_die = ((bx + 7) / 8 * by + kWavesPerBlock - 1) / kWavesPerBlock;
+    // per die: an eighth of the units, to within one; kWavesPerBlock waves to a block
+    const int64_t most = (bx * by + 7) / 8, fewest = bx * by / 8;
+    const bool halves_exist = ncols % 2 == 0 && has_width(g, o, ncols / 2);
+    if (fine_units == -2) {
+        if (!halves_exist) return DLRT_ERR_SHAPE;
+        fine_units = (int)fewest;
+    } else if (fine_units < 0) {
+        fine_units = planned_fine_units(fewest, dlrt::resident_blocks<kernel>(kRowsPerBlock * kWavesPerBlock), halves_exist);
+    }
+    if (fine_units > fewest || (fine_units > 0 && !halves_exist)) return DLRT_ERR_SHAPE;
+    const int64_t per_die = (most + fine_units + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t blocks = 8 * per_die;
     if (blocks * kWavesPerBlock > 0x7fffffffLL) return DLRT_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks), block(kRowsPerBlock * kWavesPerBlock);
-    if (conv) return dlrt::enqueue(contract_rows_kernel<AB, WB, KW, BIPOLAR, true>, grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
-    return dlrt::enqueue(contract_rows_kernel<AB, WB, KW, BIPOLAR, false>, grid, block, 0, stream, g, o, ncols, g.W, o.scale, o.bias);
+    return dlrt::enqueue(kernel, dim3((unsigned)blocks), dim3(kRowsPerBlock * kWavesPerBlock), 0, stream, g, o, ncols, fine_units,
+                         g.W, o.scale, o.bias);
+}
+
+template <int AB, int WB, int KW, bool BIPOLAR>
+dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, int fine_units, hipStream_t stream)
+{
+    return conv ? launch_one<AB, WB, KW, BIPOLAR, true>(g, o, ncols, fine_units, stream)
+                : launch_one<AB, WB, KW, BIPOLAR, false>(g, o, ncols, fine_units, stream);
 }
 
 template <int AB, int WB, bool BIPOLAR>
-dlrt_status pick_kw(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, hipStream_t stream)
+dlrt_status pick_kw(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, int fine_units, hipStream_t stream)
 {
-    if (g.Kw <= 1) return launch_conv_or_gemm<AB, WB, 1, BIPOLAR>(g, o, conv, ncols, stream);
-    if (g.Kw <= 2) return launch_conv_or_gemm<AB, WB, 2, BIPOLAR>(g, o, conv, ncols, stream);
-    if (g.Kw <= 4) return launch_conv_or_gemm<AB, WB, 4, BIPOLAR>(g, o, conv, ncols, stream);
-    if (g.Kw <= 8) return launch_conv_or_gemm<AB, WB, 8, BIPOLAR>(g, o, conv, ncols, stream);
-    if (g.Kw == 9) return launch_conv_or_gemm<AB, WB, 9, BIPOLAR>(g, o, conv, ncols, stream);  // 3x3 taps of one word
-    if (g.Kw <= 16) return launch_conv_or_gemm<AB, WB, 16, BIPOLAR>(g, o, conv, ncols, stream);
-    if (g.Kw == 18) return launch_conv_or_gemm<AB, WB, 18, BIPOLAR>(g, o, conv, ncols, stream);  // 3x3 taps of two words
+    if (g.Kw <= 1) return launch_conv_or_gemm<AB, WB, 1, BIPOLAR>(g, o, conv, ncols, fine_units, stream);
+    if (g.Kw <= 2) return launch_conv_or_gemm<AB, WB, 2, BIPOLAR>(g, o, conv, ncols, fine_units, stream);
+    if (g.Kw <= 4) return launch_conv_or_gemm<AB, WB, 4, BIPOLAR>(g, o, conv, ncols, fine_units, stream);
+    if (g.Kw <= 8) return launch_conv_or_gemm<AB, WB, 8, BIPOLAR>(g, o, conv, ncols, fine_units, stream);
+    if (g.Kw == 9) return launch_conv_or_gemm<AB, WB, 9, BIPOLAR>(g, o, conv, ncols, fine_units, stream);  // 3x3 taps of one word
+    if (g.Kw <= 16) return launch_conv_or_gemm<AB, WB, 16, BIPOLAR>(g, o, conv, ncols, fine_units, stream);
+    if (g.Kw == 18) return launch_conv_or_gemm<AB, WB, 18, BIPOLAR>(g, o, conv, ncols, fine_units, stream);  // 3x3 taps of two words
     return DLRT_ERR_SHAPE;  // never planned: the reduction is too long for a lane's registers
 }
 
 template <int AB>
 dlrt_status pick_wbits(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols,
-                       hipStream_t stream)
+                       int fine_units, hipStream_t stream)
 {
     switch (wbits) {
     case 1:
-        return bipolar ? pick_kw<AB, 1, true>(g, o, conv, ncols, stream) : pick_kw<AB, 1, false>(g, o, conv, ncols, stream);
-    case 2: return pick_kw<AB, 2, false>(g, o, conv, ncols, stream);
-    case 3: return pick_kw<AB, 3, false>(g, o, conv, ncols, stream);
-    case 4: return pick_kw<AB, 4, false>(g, o, conv, ncols, stream);
+        return bipolar ? pick_kw<AB, 1, true>(g, o, conv, ncols, fine_units, stream) : pick_kw<AB, 1, false>(g, o, conv, ncols, fine_units, stream);
+    case 2: return pick_kw<AB, 2, false>(g, o, conv, ncols, fine_units, stream);
+    case 3: return pick_kw<AB, 3, false>(g, o, conv, ncols, fine_units, stream);
+    case 4: return pick_kw<AB, 4, false>(g, o, conv, ncols, fine_units, stream);
     }
     return DLRT_ERR_BITS;
 }
@@ -453,9 +499,9 @@ namespace dlrt {
 #define DLRT_CAT(a, b) DLRT_CAT2(a, b)
 
 dlrt_status DLRT_CAT(launch_rows_a, DLRT_ABITS)(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar,
-                                                 bool conv, int ncols, hipStream_t stream)
+                                                 bool conv, int ncols, int fine_units, hipStream_t stream)
 {
-    return pick_wbits<DLRT_ABITS>(g, o, wbits, bipolar, conv, ncols, stream);
+    return pick_wbits<DLRT_ABITS>(g, o, wbits, bipolar, conv, ncols, fine_units, stream);
 }
 
 }  // namespace dlrt

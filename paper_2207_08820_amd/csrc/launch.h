@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "dlrt.h"
 
 namespace dlrt {
@@ -20,6 +22,35 @@ dlrt_status enqueue(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_byte
     void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
     const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds_bytes, stream);
     return e == hipSuccess ? DLRT_OK : DLRT_ERR_LAUNCH;
+}
+
+// How many workgroups of `threads` threads (and `lds_bytes` of dynamic LDS) of `Kernel` one compute unit holds at
+// once, as the runtime computes it from the kernel's registers; asked once per kernel and kept.  0: not known
+// (the query failed), in which case callers plan as if they knew nothing about rounds of waves.
+template <auto Kernel>
+int resident_blocks(int threads, size_t lds_bytes = 0)
+{
+    static std::atomic<int> kept{0};   // (for lds_bytes = 0; a caller with LDS asks every time)
+    if (lds_bytes == 0) {
+        const int v = kept.load(std::memory_order_relaxed);
+        if (v > 0) return v;
+    }
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, Kernel, threads, lds_bytes) != hipSuccess || n <= 0) return 0;
+    if (lds_bytes == 0) kept.store(n, std::memory_order_relaxed);
+    return n;
+}
+
+// Compute units of the current device (256 on an MI355X, 32 per die), kept after the first call; 0: not known.
+inline int compute_units()
+{
+    static std::atomic<int> kept{0};
+    int v = kept.load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
+    kept.store(v, std::memory_order_relaxed);
+    return v;
 }
 
 // Optional outputs of the fused epilogue of both contraction kernels; any pointer may be null.
@@ -93,10 +124,10 @@ dlrt_status launch_wave_a4(const ContractArgs *g, const FusedOut *o, int count, 
 // taps of two words); GEMM or any convolution (a conv's words are those of its im2col row).  ncols: output
 // columns per wave, a multiple of 32.
 inline bool row_kernel_has(int Kw) { return Kw <= 16 || Kw == 18; }
-dlrt_status launch_rows_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
-dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
-dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
-dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, hipStream_t stream);
+dlrt_status launch_rows_a1(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
+dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
+dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
+dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
 
 // Panel kernel (contract_panels.hip): one output row per lane, 64 rows x ncols columns per block, the reduction
 // walked in panels of 12 or 16 words against weights held in LDS; for long reductions with many rows.  ncols is

@@ -502,6 +502,74 @@ def test_conv_fused_row_kernel_all_encodings(dlrt, oracle, shape):
                        packed_only=True)      # 24 columns: neither a part of a word nor whole words
 
 
+def test_conv_fused_row_kernel_half_width_waves(dlrt, oracle):
+    """A negative column-group hint sends out as many units as every die has as two waves of half the width each (the
+    planner does this to the last units of a launch of many rounds of waves), the rest as one wave: 50 row blocks
+    here, so that every die has units of both kinds.  Halves of whole words with any output, narrower ones
+    on the packed-only path."""
+    N, H, W, Ci, Co, k, stride, pad = 2, 40, 40, 32, 64, 3, 1, 1
+    for idx, (abits, wbits, ea, ew, qbits) in enumerate([(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2),
+                                                         (3, 2, TWOS, UNSIGNED, 3)]):
+        x = inputs.uniform_values((N, H, W, Ci), abits, ea, 28500 + idx)
+        w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 29500 + idx)
+        fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=-8)
+        fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=-8, packed_only=True)
+        for groups in (-2, -4):
+            if ea == UNSIGNED:
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
+                           packed_only=True)
+            else:
+                with pytest.raises(dlrt.DlrtError):
+                    fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64,
+                               ksplit=groups, packed_only=True)
+            with pytest.raises(dlrt.DlrtError):  # any further output: whole words only
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups)
+        for groups in (-1, -6):  # halves of 4 or 24 columns: no such wave
+            with pytest.raises(dlrt.DlrtError):
+                fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=groups,
+                           packed_only=True)
+
+
+# (batch, H, W, Ci, Co, k, stride, pad, wbits, weight encoding): layers of the two batched chains that bench.py times,
+# one for every kernel and launch form the planner gives them (row kernel with a half-width tail, 32-column row
+# kernel on a strided 1x1 conv, panel kernel with one, two and four waves per tile, block kernel)
+BATCHED_CHAIN_LAYERS = [
+    (64, 56, 56, 64, 64, 3, 1, 1, 2, TWOS),       # 200704 x 64 x 576
+    (64, 56, 56, 64, 128, 3, 2, 1, 2, TWOS),      # 50176 x 128 x 576
+    (64, 28, 28, 128, 128, 3, 1, 1, 2, TWOS),     # 50176 x 128 x 1152
+    (64, 14, 14, 256, 256, 3, 1, 1, 2, TWOS),     # 12544 x 256 x 2304
+    (64, 7, 7, 512, 512, 3, 1, 1, 2, TWOS),       # 3136 x 512 x 4608
+    (64, 14, 14, 256, 512, 1, 2, 0, 2, TWOS),     # 3136 x 512 x 256
+    (16, 160, 160, 64, 128, 3, 2, 1, 1, BIPOLAR), # 102400 x 128 x 576
+    (16, 80, 80, 128, 256, 3, 2, 1, 1, BIPOLAR),  # 25600 x 256 x 1152
+]
+
+
+@pytest.mark.parametrize("layer", BATCHED_CHAIN_LAYERS)
+def test_batched_chain_layers_at_bench_size_on_sampled_images(dlrt, oracle, layer):
+    """The layers of the batched chains at the batch bench.py times them at, launched as the chain launches them
+    (planned, nothing but the packed output), against the oracle on whole images of the batch: the first, and
+    the eight whose rows fall at the end of a die's share of the launch, where the planner's half-width waves are."""
+    B, H, W, Ci, Co, k, stride, pad, wbits, ew = layer
+    x = inputs.uniform_values((B, H, W, Ci), 2, UNSIGNED, 31000 + Co + H)
+    w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 32000 + Co + H)
+    ref0 = oracle.conv2d_i32(x[:1], w, (stride, stride), (pad, pad))
+    scale, bias = calibrate(ref0)
+    Ho, Wo = ref0.shape[1], ref0.shape[2]
+    X = dlrt.dlrt_pack_bitplanes(src_tensor(x, UNSIGNED), 2, UNSIGNED)
+    Wp = dlrt.dlrt_pack_conv_weights(src_tensor(w, ew), wbits, ew)
+    packed = torch.full((B * Ho * Wo, 2, (Co + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    dlrt.dlrt_bitserial_conv2d_fused(X, Wp, dev(scale), dev(bias), B, H, W, Ci, Co, k, k, (stride, stride), (pad, pad),
+                                     2, wbits, UNSIGNED, ew, qbits=2, out_packed=packed)
+    torch.cuda.synchronize()
+    got = words(packed).reshape(B, Ho * Wo, 2, -1)
+    for img in [0] + list(range(B // 8 - 1, B, B // 8)):
+        ref = oracle.conv2d_i32(x[img:img + 1], w, (stride, stride), (pad, pad))
+        _, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=2)
+        want = oracle.pack_bitplanes(q_ref.reshape(Ho * Wo, Co).astype(np.int8), 2, UNSIGNED)
+        assert np.array_equal(got[img], want.reshape(Ho * Wo, 2, -1)), (layer, img)
+
+
 PANEL_KERNEL_SHAPES = [
     # N, H, W, Ci, Co, k, stride, pad: convs the panel kernel holds (channels a multiple of 128, so that a tap is
     # whole 16-byte groups), over one, several and ragged numbers of panels, rows beyond one wave, ragged columns
