@@ -170,7 +170,9 @@ def measure_denominators(dev):
         probe.empty()
     torch.cuda.synchronize()
     out["launch_floor_eager_us"] = round(time_events(probe.empty, 500) * 1e3, 3)
-    out["launch_floor_us"] = round(time_graph(probe.empty, reps=50, replays=10) * 1e3, 3)
+    # a floor: the lowest of three graphs (one box reported 3.6 us once where every other run reports 1.7, with the
+    # chains' own times unchanged)
+    out["launch_floor_us"] = round(min(time_graph(probe.empty, reps=50, replays=10) for _ in range(3)) * 1e3, 3)
     return out
 
 
