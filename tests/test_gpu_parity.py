@@ -507,9 +507,10 @@ def test_conv_fused_row_kernel_half_width_waves(dlrt, oracle):
     planner does this to the last units of a launch of many rounds of waves), the rest as one wave: 50 row blocks
     here, so that every die has units of both kinds.  Halves of whole words with any output, narrower ones
     on the packed-only path."""
-    N, H, W, Ci, Co, k, stride, pad = 2, 40, 40, 32, 64, 3, 1, 1
-    for idx, (abits, wbits, ea, ew, qbits) in enumerate([(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2),
-                                                         (3, 2, TWOS, UNSIGNED, 3)]):
+    cases = [(2, 2, UNSIGNED, TWOS, 2), (2, 1, UNSIGNED, BIPOLAR, 2), (3, 2, TWOS, UNSIGNED, 3)]
+    for idx, (abits, wbits, ea, ew, qbits) in enumerate(cases + cases[:2]):
+        # 3200 rows x 64 columns, then a ragged 1517 rows (the last row block a partial one) x 96 columns
+        N, H, W, Ci, Co, k, stride, pad = (2, 40, 40, 32, 64, 3, 1, 1) if idx < 3 else (1, 37, 41, 40, 96, 3, 1, 1)
         x = inputs.uniform_values((N, H, W, Ci), abits, ea, 28500 + idx)
         w = inputs.uniform_values((Co, k, k, Ci), wbits, ew, 29500 + idx)
         fused_case(dlrt, oracle, x, w, stride, pad, abits, wbits, ea, ew, qbits, tile_rows=64, ksplit=-8)
