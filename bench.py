@@ -254,7 +254,7 @@ def layer_floors(L, abits, wbits, qbits, batch=1):
     return abits * wbits * batch * L.macs / 16.0 / VALU_PEAK_LANE_OPS * 1e6, nbytes / HBM_PEAK_BYTES * 1e6
 
 
-def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_us=0.0):
+def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_us=0.0, warm=None):
     """Whole conv chain of a model-shaped stack ("resnet18": 19 convs A2W2; "yolo": 16 convs A2 / bipolar
     W1).  Scale and bias come from the closed-form mean / deviation of a uniform-input layer; timing
     does not depend on the values.  Reported: the fused chain replayed as one HIP graph (pack of the input + one fused
@@ -282,6 +282,8 @@ def stack_ms(dlrt, dev, which, iters=50, batch=1, launches_only=0, launch_floor_
                       batch=batch)
     if launches_only:  # counter-collection runs: every layer's fused kernel a few times, eagerly, nothing timed
         stack.run(x0)
+        if warm:  # to the steady clock with another kernel (see prewarm), so that a trace of this run shows these at it
+            prewarm(warm)
         for i in range(len(stack.layers)):
             xin = stack.layer_input(i)
             for _ in range(launches_only):
@@ -477,7 +479,7 @@ def main():
         return emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t)
     if args.conv_launches:
         for which, b in (("resnet18", 64), ("yolo", 16)):
-            extra[f"{which}_batch{b}_layers_launched"] = stack_ms(dlrt, dev, which, batch=b, launches_only=args.conv_launches)[1]
+            extra[f"{which}_batch{b}_layers_launched"] = stack_ms(dlrt, dev, which, batch=b, launches_only=args.conv_launches, warm=step)[1]
         return emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t)
     r18, per_layer = stack_ms(dlrt, dev, "resnet18", launch_floor_us=floor_us)
     extra["resnet18_a2w2_conv_stack_ms"] = round(r18["graph_fused_ms"], 5)
