@@ -25,19 +25,19 @@ dlrt_status enqueue(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_byte
 }
 
 // How many workgroups of `threads` threads (and `lds_bytes` of dynamic LDS) of `Kernel` one compute unit holds at
-// once, as the runtime computes it from the kernel's registers; asked once per kernel and kept.  0: not known
-// (the query failed), in which case callers plan as if they knew nothing about rounds of waves.
+// once, as the runtime computes it from the kernel's registers; the answer for the last (threads, lds_bytes) asked is
+// kept per kernel, so a layer launched again and again asks once.  0: not known (the query failed), in which case
+// callers plan as if they knew nothing about rounds of waves.
 template <auto Kernel>
 int resident_blocks(int threads, size_t lds_bytes = 0)
 {
-    static std::atomic<int> kept{0};   // (for lds_bytes = 0; a caller with LDS asks every time)
-    if (lds_bytes == 0) {
-        const int v = kept.load(std::memory_order_relaxed);
-        if (v > 0) return v;
-    }
+    static std::atomic<uint64_t> kept{0};   // (threads, lds_bytes, answer) in one word: 12 + 32 + 16 bits
+    const uint64_t key = ((uint64_t)threads << 52) | ((uint64_t)(lds_bytes & 0xffffffffu) << 16);
+    const uint64_t v = kept.load(std::memory_order_relaxed);
+    if ((v & ~0xffffULL) == key && (v & 0xffff) != 0) return (int)(v & 0xffff);
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, Kernel, threads, lds_bytes) != hipSuccess || n <= 0) return 0;
-    if (lds_bytes == 0) kept.store(n, std::memory_order_relaxed);
+    kept.store(key | (uint64_t)(n & 0xffff), std::memory_order_relaxed);
     return n;
 }
 
