@@ -395,6 +395,9 @@ def main():
     ap.add_argument("--conv-launches", type=int, default=0, metavar="R",
                     help="instead of timing the conv stacks, launch every layer of the batch-64 ResNet-18 and batch-16 "
                          "YOLO-style chains R times (for rocprofv3 --pmc runs: counters per layer kernel)")
+    ap.add_argument("--planner-regret", metavar="STACK:BATCH:PAIRS", action="append", default=[],
+                    help="instead of the benchmark: planned launch against the best hinted launch for every layer shape of "
+                         "a stack (resnet18 or yolo) at a batch and bit-width pairs, e.g. resnet18:64:22,11,44 (may be repeated)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy three times (a kernel of known HBM traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -412,6 +415,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.planner_regret:
+        print(json.dumps({"planner_regret": [planner_regret(dlrt, dev, spec) for spec in args.planner_regret]}), flush=True)
+        return
     if args.calibrate_copy:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
@@ -600,6 +606,64 @@ def main():
         extra["sweep_4096"] = sweep
 
     emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t)
+
+
+def planner_regret(dlrt, dev, spec):
+    """How far the planned launch of a fused conv layer is from the best launch that the tile hints can name.
+    spec: "stack:batch:pairs", e.g. "resnet18:64:22,11,44" (pairs are abits wbits digits; 1-bit weights are bipolar).
+    Every distinct layer shape of the stack, each pair: the planned call and every hinted one (per-wave kernel 4 to
+    32 rows x 1 to 8 waves, row kernel 8 to 64 columns, panel kernel 1 to 4 waves x 8 or 16 columns; the per-wave
+    kernel is not tried on layers of more than 4 M outputs) timed as 5 (batch 1: 20) launches back to back from a
+    HIP graph; hints that a kernel does not have are skipped.  The results do not depend on the hints."""
+    import torch
+
+    from paper_2207_08820_amd import inputs
+
+    which, batch, pairs = spec.split(":")
+    batch = int(batch)
+    layers = inputs.resnet18_stack() if which == "resnet18" else inputs.yolo_style_stack()
+    shapes = sorted({(L.H, L.W, L.Ci, L.Co, L.k, L.stride, L.pad) for L in layers}, key=lambda v: (-v[0], v[3], v[4]))
+    cands = [(tr, ks) for tr in (4, 8, 16, 32) for ks in (1, 2, 4, 8)] + [(64, c) for c in (1, 2, 4, 8)] + \
+            [(128 * s, g) for s in (1, 2, 3, 4) for g in (1, 2)]
+    rows = []
+    for (H, W, Ci, Co, k, stride, pad) in shapes:
+        for pair in pairs.split(","):
+            ab, wb = int(pair[0]), int(pair[1])
+            ew = inputs.BIPOLAR if wb == 1 else inputs.TWOS
+            x = torch.as_tensor(inputs.uniform_values((batch, H, W, Ci), ab, inputs.UNSIGNED, 1).astype("uint8"), device=dev)
+            w = torch.as_tensor(inputs.uniform_values((Co, k, k, Ci), wb, ew, 2), device=dev)
+            X, Wp = dlrt.dlrt_pack_bitplanes(x, ab, inputs.UNSIGNED), dlrt.dlrt_pack_conv_weights(w, wb, ew)
+            scale, bias = torch.full((Co,), 0.01, device=dev), torch.full((Co,), 1.5, device=dev)
+            Ho, Wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+            M = batch * Ho * Wo
+            out = torch.empty((M, 2, (Co + 31) // 32), dtype=torch.int32, device=dev)
+
+            def timed(tr, ks):
+                def run():
+                    dlrt.dlrt_bitserial_conv2d_fused(X, Wp, scale, bias, batch, H, W, Ci, Co, k, k, (stride, stride), (pad, pad),
+                                                     ab, wb, inputs.UNSIGNED, ew, qbits=2, out_packed=out, tile_rows=tr, ksplit=ks)
+                return time_graph(run, reps=20 if batch == 1 else 5, replays=3) * 1e3
+
+            planned = timed(0, 0)
+            best, best_us = (0, 0), planned
+            for tr, ks in cands:
+                if tr <= 32 and M * Co > 4e6:
+                    continue
+                try:
+                    us = timed(tr, ks)
+                except dlrt.DlrtError:
+                    continue
+                if us < best_us:
+                    best, best_us = (tr, ks), us
+            planned = min(planned, timed(0, 0))  # (once more at the end: the first timing after new tensors runs high)
+            best_us = min(best_us, planned)
+            rows.append({"M": M, "N": Co, "K": k * k * Ci, "abits": ab, "wbits": wb, "planned_us": round(planned, 2),
+                         "best_hint": list(best) if best_us < planned else [0, 0], "best_us": round(best_us, 2),
+                         "regret": round(planned / best_us - 1, 3)})
+            log(rows[-1])
+    total_p, total_b = sum(r["planned_us"] for r in rows), sum(r["best_us"] for r in rows)
+    return {"spec": spec, "layers": rows, "sum_planned_us": round(total_p, 1), "sum_best_us": round(total_b, 1),
+            "regret_of_the_sum": round(total_p / total_b - 1, 4), "worst": max(r["regret"] for r in rows)}
 
 
 def emit(args, c, abits, wbits, value, ms_per_step, roofline, extra, t):

@@ -169,6 +169,10 @@ WavePlan plan_wave(int M, int N, int Kw, int abits, int wbits, int tile_rows_hin
             const int spw = (steps + ks - 1) / ks;
             // a lone wave keeps a SIMD about 70 % busy; with several waves per SIMD they cover each other
             const double over = (double)tiles * ks / 1024;
+            // With more waves than SIMDs a wave's own cost (addresses, the exchange of partial sums: about a thousand
+            // issue cycles) is no longer hidden behind idle SIMDs, and a split down to one or two steps per wave adds
+            // more of it than it saves: 400 x 512 x 512 at A2W2 and A4W1 measured 4.2 us unsplit, 5.0 in two, 6.6 in four.
+            if (ks > 1 && over > 1 && spw < 3 && ksplit_hint == 0) break;
             const double eff = over <= 1 ? 0.7 : (0.7 + 0.12 * (over - 1) < 0.95 ? 0.7 + 0.12 * (over - 1) : 0.95);
             const double valu = (double)spw * 4 * tmv * tn * abits * wbits * 2 * 4 / eff;
             const double load = (double)spw * (abits * rows + wbits * 32) * 16 / 32;
@@ -194,12 +198,14 @@ int64_t row_kernel_waves(int64_t M, int N) { return ((M + 63) / 64) * ((N + 31) 
 // single images: from 800 waves of 8 columns on it measured 5 to 25 % faster than the tiled kernels on every
 // layer tried with a reduction of up to 9 words, or 18 (6400 .. 25600 pixels x 32 .. 128 channels, A2W1), slower
 // below (1600 pixels x 128 channels, 3136 x 64 at 18 words).
-bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits, bool halves)
+bool prefer_rows_kernel(int64_t M, int N, int Kw, int abits, int wbits, bool halves)
 {
-    if (!dlrt::row_kernel_has(Kw) || (Kw > 16 && wbits > 2)) return false;
+    // (18 words: 1- and 2-bit weights, or 2-bit activations with 4-bit weights, which measured 24 to 38 % ahead of the
+    // block kernel on two layers of 50176 and 200704 pixels; A3W3 and A4W4 stay behind it)
+    if (!dlrt::row_kernel_has(Kw) || (Kw > 16 && wbits > 2 && abits * wbits > 8)) return false;
     if (M < 2048) return false;  // lanes idle on few rows (none measured below 3136)
     if (((M + 63) / 64 + 7) * ((N + 7) / 8) > 0x7fffffffLL) return false;  // more blocks than a grid holds
-    if (halves && N % 32 == 0 && (Kw <= 9 || Kw == 18) && ((M + 63) / 64) * (N / 8) >= 800) return true;
+    if (halves && N % 32 == 0 && (Kw <= 9 || (Kw == 18 && abits <= 2)) && ((M + 63) / 64) * (N / 8) >= 800) return true;
     const int64_t from = Kw == 1 ? 256 : Kw == 2 ? 384 : Kw <= 4 ? 1024 : Kw <= 9 ? 1536 : Kw <= 16 ? 12288 : 3072;
     return row_kernel_waves(M, N) >= from;
 }
@@ -215,8 +221,11 @@ bool prefer_rows_kernel(int64_t M, int N, int Kw, int wbits, bool halves)
 // LDS broadcasts and per-panel address arithmetic hold it below 0.8).
 bool prefer_panel_kernel(int64_t M, int N, int Kw, int abits, int wbits)
 {
-    return abits >= 2 && abits * wbits == 4 && Kw >= 32 && M >= 2048 && ((M + 63) / 64) * ((N + 7) / 8) >= 3072 &&
-           block_tiles((int)M, N, abits, wbits) < 2048;
+    const int64_t tiles = block_tiles((int)M, N, abits, wbits);
+    // (A1W1: only where the block kernel has fewer than two of its 64 x 64 tiles per compute unit; 392 of them measured
+    // 16 to 22 % behind the panel kernel, 1568 level with it)
+    const bool widths = (abits >= 2 && abits * wbits == 4 && tiles < 2048) || (abits * wbits == 1 && tiles < 512);
+    return widths && Kw >= 32 && M >= 2048 && ((M + 63) / 64) * ((N + 7) / 8) >= 3072;
 }
 
 // Panel kernel: how many waves of a block share a tile's reduction.  One wave per 64 x 8 tile is the least
@@ -260,7 +269,7 @@ int plan_rows(int64_t M, int N, int Kw, int abits, int wbits, bool halves, bool 
 {
     const int64_t row_blocks = (M + 63) / 64;
     int ncols = 32;
-    if (halves && N % 32 == 0 && row_blocks * (N / 32) < 1024) {
+    if (halves && N % 32 == 0 && row_blocks * (N / 32) < 4096) {
         // a launch that cannot fill the chip with 32-column waves (single images): the widest waves that still make
         // about 1500 of them, else the narrowest (measured on eight such layers: the best or within 3 % of it)
         ncols = row_blocks * (N / 16) >= 1536 ? 16 : 8;
@@ -285,7 +294,7 @@ void query_plan(int M, int N, int Kw, int abits, int wbits, int *block_kernel, i
     const bool wave = prefer_wave_kernel(M, N, abits, wbits) && (int64_t)M * abits * Kw * 4 <= (1LL << 31) &&
                       (int64_t)N * wbits * Kw * 4 <= (1LL << 31);  // (its operands are addressed with 32-bit offsets)
     int rows = block_tile(abits), cols = block_tile(wbits), ks = 1;
-    if (prefer_rows_kernel(M, N, Kw, wbits, true)) {  // (as for a chained layer: packed output only)
+    if (prefer_rows_kernel(M, N, Kw, abits, wbits, true)) {  // (as for a chained layer: packed output only)
         if (block_kernel) *block_kernel = 2;
         if (tile_rows) *tile_rows = 64;
         if (tile_cols) *tile_cols = plan_rows(M, N, Kw, abits, wbits, true, true);  // as for a chained conv layer (packed output only)
@@ -321,7 +330,7 @@ dlrt_status launch_gemm(const uint32_t *A, const uint32_t *W, int M, int N, int 
     const int va = widest_vec(A, Kw), vw = widest_vec(W, Kw);
     g.vec = va < vw ? va : vw;
     const bool halves = o.packed && !o.acc && !o.y && !o.q && !a_msb_neg;
-    if (prefer_rows_kernel(M, N, Kw, wbits, halves))
+    if (prefer_rows_kernel(M, N, Kw, abits, wbits, halves))
         return launch_rows(g, o, abits, wbits, bipolar, false, plan_rows(M, N, Kw, abits, wbits, halves, false), -1, stream);
     const int64_t a_bytes = (int64_t)M * abits * Kw * 4;
     if (prefer_panel_kernel(M, N, Kw, abits, wbits) && panel_kernel_has(g, abits, wbits, false, 8, a_bytes)) {
@@ -386,7 +395,7 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     for (int i = 0; i < 2; ++i) {
         const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
         const int Kw = c[i].KH * c[i].KW * c[i].Cw;
-        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw, wbits, o[i].packed && !o[i].acc && !o[i].y && !o[i].q && !a_msb_neg);
+        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw, abits, wbits, o[i].packed && !o[i].acc && !o[i].y && !o[i].q && !a_msb_neg);
     }
     if (!pairable) {
         for (int i = 0; i < 2; ++i) {
@@ -427,7 +436,7 @@ dlrt_status launch_conv(const uint32_t *X, const uint32_t *Wp, const ConvShape &
         return launch_rows(g, o, abits, wbits, bipolar, conv, ksplit > 0 ? 8 * ksplit : ksplit < 0 ? -8 * ksplit : rows_ncols,
                            ksplit < 0 ? -2 : 0, stream);
     }
-    if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, wbits, halves))
+    if (tile_rows == 0 && ksplit == 0 && prefer_rows_kernel(g.M, g.N, g.Kw, abits, wbits, halves))
         return launch_rows(g, o, abits, wbits, bipolar, conv, rows_ncols, -1, stream);
     if (tile_rows == 0 && ksplit == 0 && prefer_panel_kernel(g.M, g.N, g.Kw, abits, wbits) &&
         panel_kernel_has(g, abits, wbits, conv, 8, x_bytes)) {

@@ -207,7 +207,7 @@ def test_planner_always_returns_a_tile_the_kernels_have(lib):
         tn = 4 if w <= 2 else 2
         assert kind in (WAVE, BLOCK, ROWS, PANELS)
         if kind == ROWS:    # the whole reduction in a lane's registers; whole output words per wave, or halves
-            assert Kw <= 16 or (Kw == 18 and w <= 2)   # of them where N fills whole words and waves are few
+            assert Kw <= 16 or (Kw == 18 and (w <= 2 or a * w <= 8))   # of them where N fills whole words and waves are few
             assert rows == 64 and ks == 1 and (cols in (32, 64, 128) or (cols in (8, 16) and N % 32 == 0))
         elif kind == PANELS:  # accumulators per lane, the wave's weights in LDS, whole 16-byte groups
             assert rows == 64 and 1 <= ks <= 4 and cols in (8, 16, 32)   # ks waves share a tile's reduction
