@@ -233,9 +233,11 @@ bool prefer_panel_kernel(int64_t M, int N, int Kw, int abits, int wbits)
 // on 1024 SIMDs are four on some and three on most, a third more time than work.  With the reduction shared by
 // s waves the units are s times as many and 1 / s as long; each further wave costs about 200 instructions (its
 // own addresses and start, the exchange of partial sums) against the tile's 2 * abits * wbits * 8 * Kw.
-// A SIMD holds eight of these waves at once and issues at full rate only with several of them: the waves beyond
-// a multiple of eight run as a last, thinner round, at the rate the register-only AND + popcount loop measured
-// for that many waves per SIMD (0.72 of the full rate for one wave, 0.85 for two, 0.94 for four).
+// The model: a SIMD takes eight waves at once and issues at full rate only with several of them, and the waves
+// beyond a multiple of eight run as a last, thinner round, at the rate the register-only AND + popcount loop
+// measured for that many waves per SIMD (0.72 of the full rate for one wave, 0.85 for two, 0.94 for four).  (Eight is
+// the model's round, not every instantiation's occupancy - A2W2 keeps five waves per SIMD resident - but it is with
+// eight that the model orders the measured layer shapes correctly.)
 int plan_panel_waves(int64_t M, int N, int Kw, int abits, int wbits)
 {
     static const double rate[9] = {1.0, 0.715, 0.85, 0.90, 0.94, 0.955, 0.97, 0.985, 1.0};
