@@ -15,7 +15,9 @@
 //
 // A wave covers 64 rows x `ncols` columns: a multiple of 32, so that waves own whole output words, or, on the
 // packed-only path and when N fills whole words, 16 or 8, written as halves or bytes of the words (finer units
-// for launches of only a few waves per SIMD).  The grid is one wave per (64 rows, ncols columns), four to a block.
+// for launches of only a few waves per SIMD).  The grid is one wave per (64 rows, ncols columns) unit, four to a
+// block; every die gets an eighth of the units, and the last units of a launch of many rounds of waves may go out
+// as two waves of half the columns each (planned_fine_units below).
 // int32 / float / uint8 outputs are written one
 // element per lane with a row stride between lanes: correct, but only the packed output is a fast path.
 //
