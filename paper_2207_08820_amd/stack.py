@@ -140,25 +140,32 @@ class ConvStack:
                                     out_packed=pl.out_packed)
 
     def pairs(self):
-        """Launch schedule of the fused chain: a layer goes out together with a later layer that reads the
-        same input and has the same bit widths (a stride-2 conv with the 1x1 conv beside it, two 1x1 convs
-        on one tensor); the later one simply runs early, its readers still come after it.  Everything else
-        is a launch of its own."""
+        """Launch schedule of the fused chain.  Layers go out in list order, each as soon as its input exists, and
+        two layers of the same bit widths that are both ready share a launch: first choice a later layer that
+        reads the same input (a stride-2 conv with the 1x1 conv beside it, two 1x1 convs on one tensor), else the
+        next ready layer on another tensor (the inner 1x1 conv of one stage beside the stride-2 conv that opens the
+        next).  The later one simply runs early; its readers still come after it.  Whether the two really share a
+        launch is the library's decision (layers that fill the chip on their own go out one after the other)."""
         plan, done, n = [], set(), len(self.layers)
+        widths = lambda i: (self.abits[i], self.wbits[i], self.enc_w[i])
+        ready = lambda j: self.layers[j].spec.src < 0 or self.layers[j].spec.src in done
         for i in range(n):
             if i in done:
                 continue
             if i in self.f32_layers:
                 plan.append((i,))
+                done.add(i)
                 continue
-            key = (self.layers[i].spec.src, self.abits[i], self.wbits[i], self.enc_w[i])
-            mate = next((j for j in range(i + 1, n) if j not in done and j not in self.f32_layers and
-                         (self.layers[j].spec.src, self.abits[j], self.wbits[j], self.enc_w[j]) == key), None)
+            later = [j for j in range(i + 1, n) if j not in done and j not in self.f32_layers and ready(j) and
+                     widths(j) == widths(i)]
+            same = [j for j in later if self.layers[j].spec.src == self.layers[i].spec.src]
+            mate = same[0] if same else later[0] if later else None
             if mate is None:
                 plan.append((i,))
             else:
                 plan.append((i, mate))
                 done.add(mate)
+            done.add(i)
         return plan
 
     def layer_input(self, i: int):
