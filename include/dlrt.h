@@ -178,8 +178,10 @@ dlrt_status dlrt_bitserial_conv2d_fused(const uint32_t *X, const uint32_t *Wp, c
  * the same activations, like a stride-2 3x3 conv and the 1x1 downsample conv beside it) share the fixed
  * cost of a launch, which dominates batch-1 layers.  Each problem computes exactly what
  * dlrt_bitserial_conv2d_fused computes for the same fields; both use the latency-oriented kernel with its
- * smallest tile.  If either problem is large enough for the throughput kernel (large batches), sharing a
- * launch no longer pays and the pair is enqueued as two ordinary launches on `stream`, first then second.
+ * smallest tile, or, two 1x1 stride-1 convolutions over at most 256 channels each that both take the row kernel
+ * and whose reductions fill register rows of the same length (1, 2, 4 or 8 words), one row-kernel launch.  If
+ * either problem is large enough for the throughput kernel (large batches), or the two fit neither form, sharing
+ * a launch no longer pays and the pair is enqueued as two ordinary launches on `stream`, first then second.
  * abits / wbits / encodings are common to both; everything else is per problem.
  * `first` and `second` are HOST structs, read before the call returns; their pointers are device pointers.
  * The two problems must not write buffers the other reads or writes.

@@ -389,6 +389,33 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
                              hipStream_t stream)
 {
     ContractArgs g[2];
+    // Two 1x1 convolutions that both take the row kernel, with register rows of the same length (at most 8 words) and
+    // together at most four waves per SIMD (single images: each alone leaves most of the chip idle and costs a
+    // dependent launch of its own), share one row-kernel launch.
+    {
+        bool rows_pair = pointwise(c[0]) && pointwise(c[1]);
+        int64_t waves = 0;
+        int ncols[2] = {32, 32};
+        for (int i = 0; i < 2 && rows_pair; ++i) {
+            const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
+            const int Kw = c[i].Cw;
+            const bool halves = o[i].packed && !o[i].acc && !o[i].y && !o[i].q && !a_msb_neg;
+            rows_pair = Kw <= 8 && prefer_rows_kernel(M, c[i].Co, Kw, abits, wbits, halves);
+            ncols[i] = plan_rows(M, c[i].Co, Kw, abits, wbits, halves, false);
+            waves += ((M + 63) / 64) * ((c[i].Co + ncols[i] - 1) / ncols[i]);
+        }
+        if (rows_pair && waves <= 4096) {
+            for (int i = 0; i < 2; ++i) g[i] = conv_args(X[i], Wp[i], c[i], a_msb_neg, w_msb_neg);
+            dlrt_status st = DLRT_ERR_BITS;
+            switch (abits) {
+            case 1: st = dlrt::launch_rows_pair_a1(g, o, wbits, bipolar, ncols, stream); break;
+            case 2: st = dlrt::launch_rows_pair_a2(g, o, wbits, bipolar, ncols, stream); break;
+            case 3: st = dlrt::launch_rows_pair_a3(g, o, wbits, bipolar, ncols, stream); break;
+            case 4: st = dlrt::launch_rows_pair_a4(g, o, wbits, bipolar, ncols, stream); break;
+            }
+            if (st != DLRT_ERR_SHAPE) return st;  // (rows of different lengths: two launches, below)
+        }
+    }
     int ksplit = 1;
     const int rows = wbits <= 2 ? 8 : 4;  // both problems on the smallest wave tile
     // sharing a launch (on the smallest wave tile) pays while neither problem can fill the chip; larger ones

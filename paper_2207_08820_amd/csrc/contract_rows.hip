@@ -112,298 +112,41 @@ __device__ __forceinline__ uint32_t byte_from_float(float v, uint32_t x)
 #endif
 }
 
+// The work of one block of a problem (`block`: its index among that problem's blocks), for the two-problem kernel.
+template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
+__device__ __forceinline__ void rows_block(const ContractArgs g, const FusedOut o, const int ncols_full, const int fine_units,
+                                           const uint32_t *__restrict__ Wp, const float *__restrict__ scale,
+                                           const float *__restrict__ bias, const unsigned block)
+{
+#include "contract_rows_body.inc"
+}
+
 // The longest register rows (16 and 18 words) are compiled for six resident waves per SIMD: left alone the compiler
 // takes 108 registers (four waves) for its prologue's address arithmetic; at 80 nothing spills and the layers of
 // 200704 x 64 x 576 and 50176 x 128 x 576 run 2 % faster (the last, thin round of waves is fuller).  Seven would spill.
 template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
 __global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock, (KW >= 16 && WB <= 2 ? 6 : 1)) void contract_rows_kernel(const ContractArgs g, const FusedOut o,
-                                                                       const int ncols_full,
-                                                                       const int fine_units /* per die, at most the fewest units a die has */,
+                                                                       const int ncols_full, const int fine_units,
                                                                        const uint32_t *__restrict__ Wp,
                                                                        const float *__restrict__ scale,
                                                                        const float *__restrict__ bias)
 {
-    // Wp / scale / bias repeat g.W / o.scale / o.bias as parameters of their own: only a read-only
-    // pointer that provably aliases none of the stores is loaded through the scalar unit.
-    // Wave -> unit (row block, column group).  Consecutive blocks go to the chip's 8 dies in turn, each with an L2
-    // of its own: die d takes the d-th eighth of the units in row-major order, so that the column groups of one row
-    // block run on the same die one after the other (the row's activations come from HBM once however the grid
-    // divides) and the dies get the same number of units to within one.  The waves beyond a die's units leave here.
-    const int col_groups = (g.N + ncols_full - 1) / ncols_full;
-    const int64_t units = (int64_t)((g.M + kRowsPerBlock - 1) / kRowsPerBlock) * col_groups;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform, and known to be
-    const int die = blockIdx.x & 7, local = (blockIdx.x >> 3) * kWavesPerBlock + wave;
-    const int first = (int)((units * die) >> 3), mine = (int)((units * (die + 1)) >> 3) - first;
-    // the die's last `fine_units` units are two waves of half the columns each, the others one wave: the blocks
-    // handed out last are the small ones, and the launch's last round of waves a short one
-    const int coarse = mine - fine_units, fine = local - coarse;
-    if (fine >= 2 * fine_units) return;
-    const int unit = first + (fine < 0 ? local : coarse + (fine >> 1));
-    const int ncols = fine < 0 ? ncols_full : ncols_full >> 1;
-    const int row_block = unit / col_groups, col_group = unit - row_block * col_groups;
-    const int m = row_block * kRowsPerBlock + (threadIdx.x & 63);
-    const int mc = min(m, g.M - 1);  // rows beyond the matrix are computed on the last row, never stored
-    const int n0 = col_group * ncols_full + (fine < 0 ? 0 : (fine & 1) * ncols), n1 = min(n0 + ncols, g.N);
+    const unsigned block = blockIdx.x;
+#include "contract_rows_body.inc"
+}
 
-    // ---- this lane's activation row: abits planes of Kw words, zero beyond Kw.  For a convolution the
-    // row is the im2col row of the lane's output pixel: word k is channel word c of tap (kh, kw), zero where
-    // the tap lies outside the image (the address is clamped into the image and the word discarded). ----
-    uint32_t a[AB][KW];
-    int rowpc[AB];
-#pragma unroll
-    for (int j = 0; j < AB; ++j) rowpc[j] = 0;
-    if (CONV) {
-        const int hw = g.Ho * g.Wo;
-        const int img = checked_div(mc, hw, g.magicHW), rem = mc - img * hw;
-        const int oh = checked_div(rem, g.Wo, g.magicWo), ow = rem - oh * g.Wo;
-        const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
-        const uint32_t *image = g.A + (size_t)img * g.H * g.Wd * (AB * g.Cw);
-        // One pixel's words, [plane][Cw], are contiguous.  When a tap is CW words wide and the reduction is a whole
-        // number of taps, a tap is fetched as that one run with the widest loads its size allows, instead of a
-        // 4-byte load per word: the lanes of a wave read 64 different pixels, so what a load instruction costs
-        // the cache is its 64 separate lines, and the fewer instructions the better (measured: a 3x3 conv
-        // over 64 channels took a third of its time in these loads).
-        auto load_taps = [&](auto cw_tag) {
-            constexpr int CW = decltype(cw_tag)::value, TAPS = KW / CW, RUN = AB * CW;
-#pragma unroll
-            for (int t = 0; t < TAPS; ++t) {
-                const int kh = fast_div(t, g.magicKW), kw = t - kh * g.KW;  // uniform: the scalar unit's work
-                const int ih = ih0 + kh, iw = iw0 + kw;
-                const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
-                const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
-                const uint32_t *pixel = image + (size_t)(ihc * g.Wd + iwc) * RUN;
-                uint32_t v[RUN];
-                if constexpr (RUN % 4 == 0) {  // the image base is 16-byte aligned, so every run of 4n words is
-#pragma unroll
-                    for (int e = 0; e < RUN; e += 4) {
-                        const uint4 q = *reinterpret_cast<const uint4 *>(pixel + e);
-                        v[e] = q.x; v[e + 1] = q.y; v[e + 2] = q.z; v[e + 3] = q.w;
-                    }
-                } else if constexpr (RUN % 2 == 0) {
-#pragma unroll
-                    for (int e = 0; e < RUN; e += 2) {
-                        const uint2 q = *reinterpret_cast<const uint2 *>(pixel + e);
-                        v[e] = q.x; v[e + 1] = q.y;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < RUN; ++e) v[e] = pixel[e];
-                }
-#pragma unroll
-                for (int j = 0; j < AB; ++j)
-#pragma unroll
-                    for (int c = 0; c < CW; ++c) a[j][t * CW + c] = ok ? v[j * CW + c] : 0u;
-            }
-        };
-        if (g.Kw == KW && g.Cw == 1) {
-            load_taps(std::integral_constant<int, 1>{});
-        } else if (g.Kw == KW && g.Cw == 2 && KW % 2 == 0) {
-            load_taps(std::integral_constant<int, KW % 2 == 0 ? 2 : 1>{});
-        } else if (g.Kw == KW && g.Cw == 4 && KW % 4 == 0) {
-            load_taps(std::integral_constant<int, KW % 4 == 0 ? 4 : 1>{});
-        } else if (g.Kw == KW && g.Cw == KW) {  // one tap (a strided 1x1 convolution)
-            load_taps(std::integral_constant<int, KW>{});
-        } else {
-#pragma unroll
-            for (int k = 0; k < KW; ++k) {
-                const int kc = k < g.Kw ? k : 0;
-                const int tap = fast_div(kc, g.magicCw), c = kc - tap * g.Cw;
-                const int kh = fast_div(tap, g.magicKW), kw = tap - kh * g.KW;
-                const int ih = ih0 + kh, iw = iw0 + kw;
-                const bool ok = k < g.Kw && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.Wd;
-                const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.Wd - 1);
-                const uint32_t *pixel = image + (size_t)(ihc * g.Wd + iwc) * (AB * g.Cw) + c;
-#pragma unroll
-                for (int j = 0; j < AB; ++j) {
-                    const uint32_t v = pixel[j * g.Cw];
-                    a[j][k] = ok ? v : 0u;
-                }
-            }
-        }
-    } else {
-        const uint32_t *arow = g.A + (size_t)mc * (AB * g.Kw);
-        if (g.Kw == KW) {  // compile-time offsets: the row's AB * KW words are fetched with wide loads
-#pragma unroll
-            for (int j = 0; j < AB; ++j)
-#pragma unroll
-                for (int k = 0; k < KW; ++k) a[j][k] = arow[j * KW + k];
-        } else {
-#pragma unroll
-            for (int j = 0; j < AB; ++j)
-#pragma unroll
-                for (int k = 0; k < KW; ++k) a[j][k] = k < g.Kw ? arow[j * g.Kw + k] : 0u;
-        }
-    }
-    if (BIPOLAR) {
-#pragma unroll
-        for (int j = 0; j < AB; ++j)
-#pragma unroll
-            for (int k = 0; k < KW; ++k) rowpc[j] += __popc(a[j][k]);
-    }
-
-    // Plane weights with their signs (Section V's double sum): +-2^i, +-2^j, negative for the MSB plane of a
-    // two's-complement operand.  Popcount sums stay below 2^10 and partial sums below 2^14 here, so the
-    // combine is a chain of 24-bit multiply-adds (one full-rate instruction each).
-    int wcoef[WB], acoef[AB];
-#pragma unroll
-    for (int i = 0; i < WB; ++i) wcoef[i] = (g.w_msb_neg && i == WB - 1) ? -(1 << i) : (1 << i);
-#pragma unroll
-    for (int j = 0; j < AB; ++j) acoef[j] = (g.a_msb_neg && j == AB - 1) ? -(1 << j) : (1 << j);
-    // bipolar: sum_j 2^j (2 pc(A[j] & W) - pc(A[j])) = 2 sum_j 2^j pc(A[j] & W) - R with one constant R per row
-    int neg_row_sum = 0;
-#pragma unroll
-    for (int j = 0; j < AB; ++j) neg_row_sum -= rowpc[j] << j;
-    const float qmax = (float)((1 << o.qbits) - 1);
-    const int Cwo = (g.N + 31) / 32;
-    const bool row_ok = m < g.M;
-    int lane_zero = 0;  // zero, but opaque to the compiler: an index with it is loaded per lane
-#if defined(__HIP_DEVICE_COMPILE__)
-    asm("v_mov_b32 %0, 0" : "=v"(lane_zero));
-#endif
-    const bool packed_only = !o.acc && !o.y && !o.q;  // the chained-layer case: nothing but the packed words
-
-    // One output.  n is uniform over the wave, so the weight words, scale and bias come through
-    // scalar loads and the AND takes them as scalar operands.  EXACT: the reduction has exactly KW words,
-    // so every weight index is a compile-time offset from n * WB * KW and the loads of neighbouring
-    // columns merge into wide scalar loads.
-    // HORNER (unsigned activations): the activation planes of one weight plane share ONE accumulator, most
-    // significant plane first, doubled between planes: the accumulating popcount then leaves
-    // sum_j 2^j popcount(A[j] & W[i]) with one shift per further plane and no separate adds.  Two's-complement
-    // activations (a negative MSB plane cannot be accumulated) take one accumulator per plane pair, on the
-    // general path below, as does any call that wants more than the packed output.
-    auto output = [&](int n, auto exact_tag, auto horner_tag) {
-        constexpr bool EXACT = decltype(exact_tag)::value, HORNER = decltype(horner_tag)::value;
-        const int kw = EXACT ? KW : g.Kw;
-        const uint32_t *w = Wp + (size_t)n * (WB * kw);
-        int total = 0;
-        if (HORNER) {
-#pragma unroll
-            for (int i = 0; i < WB; ++i) {
-                int acc = 0;
-#pragma unroll
-                for (int j = AB - 1; j >= 0; --j) {
-                    if (j < AB - 1) acc <<= 1;
-#pragma unroll
-                    for (int k = 0; k < KW; ++k) {  // words beyond Kw: a[j][k] is zero, the weight index is clamped in bounds
-                        acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
-                        keep_chain(acc);
-                    }
-                }
-                total = BIPOLAR ? (acc << 1) + neg_row_sum : mad24(acc, wcoef[i], total);
-            }
-            return total;
-        }
-#pragma unroll
-        for (int j = 0; j < AB; ++j) {
-            int part = BIPOLAR ? -rowpc[j] : 0;
-#pragma unroll
-            for (int i = 0; i < WB; ++i) {
-                int acc = 0;
-#pragma unroll
-                for (int k = 0; k < KW; ++k) {
-                    acc += __popc(a[j][k] & w[i * kw + (EXACT || k < kw ? k : kw - 1)]);
-                    keep_chain(acc);
-                }
-                part = BIPOLAR ? part + 2 * acc : mad24(acc, wcoef[i], part);
-            }
-            total = mad24(part, acoef[j], total);
-        }
-        return total;
-    };
-
-    uint32_t word[4] = {0u, 0u, 0u, 0u};
-    auto add_bits = [&](int n, uint32_t q) {
-        const int bit = n & 31;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) word[p] |= ((q >> p) & 1u) << bit;
-        if (bit == 31 || n == n1 - 1) {  // uniform: this row's word is complete (or the row ends)
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                if (p < o.qbits && row_ok) o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)] = word[p];
-                word[p] = 0u;
-            }
-        }
-    };
-    // min(y, qmax) with y = fma(float(acc), scale, bias): the upper clamp of the requantization, applied before the
-    // rounding (the same number, qmax being an integer); byte_from_float() then rounds and clamps at zero.  With
-    // no bias the product alone rounds to the same number as the fused multiply-add with +0 (up to the sign of a
-    // zero, which the clamp removes).  A column's bias is the same for every lane but has to sit in a vector
-    // register (an instruction reads at most one scalar register, and that is the scale): it comes through a
-    // vector load of one address, which costs the VALUs nothing, instead of a register move per output.
-    auto upper_clamped = [&](int total, int n, auto bias_tag) {
-        constexpr bool HAS_BIAS = decltype(bias_tag)::value;
-        const float y = HAS_BIAS ? __fmaf_rn((float)total, scale[n], bias[n + lane_zero]) : (float)total * scale[n];
-        return fminf(y, qmax);
-    };
-    auto requantized = [&](int total, int n, auto bias_tag) { return clamp0(rintf(upper_clamped(total, n, bias_tag)), qmax); };
-    auto packed_columns = [&](auto exact_tag, auto horner_tag, auto bias_tag) {
-        // Eight columns at a time, in groups of CB with no branch inside a group: the scalar loads of a
-        // group (weights, scale, bias) are issued together and waited for once, instead of one round trip
-        // to the scalar cache per column.  The eight results land in the nibbles of four bytes (columns c and
-        // c + 4 share a byte); bit p of every nibble is then one byte of plane p's word, gathered by ONE dot
-        // product with the byte vector {1, 2, 4, 8}: sum_c 2^c (bit(q_c) + 16 bit(q_{c+4})).
-        constexpr int CB = WB * KW <= 8 ? 4 : WB * KW <= 16 ? 2 : 1;
-        int n = n0;
-        for (; n + 8 <= n1; n += 8) {
-            uint32_t x[2] = {0u, 0u};
-#pragma unroll
-            for (int c0 = 0; c0 < 8; c0 += CB) {
-#pragma unroll
-                for (int c = c0; c < c0 + CB; ++c) {
-                    const float r = upper_clamped(output(n + c, exact_tag, horner_tag), n + c, bias_tag);
-                    x[c >> 2] = (c & 3) == 0 ? byte_from_float<0>(r, x[c >> 2]) : (c & 3) == 1 ? byte_from_float<1>(r, x[c >> 2])
-                              : (c & 3) == 2 ? byte_from_float<2>(r, x[c >> 2]) : byte_from_float<3>(r, x[c >> 2]);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // keep the next group's scalar loads out of this group
-            }
-            const uint32_t nib = x[0] | (x[1] << 4);
-            const int shift = n & 24;  // which byte of the 32-column word these eight columns are
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                if (p < o.qbits) word[p] |= dot4((nib >> p) & 0x11111111u, 0x08040201u, 0u) << shift;
-            }
-            if (shift == 24 || n + 8 == n1) {
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    if (p < o.qbits && row_ok) {
-                        uint32_t *dst = &o.packed[((size_t)m * o.qbits + p) * Cwo + (n >> 5)];
-                        // a wave of 16 or 8 columns owns a half or a byte of the word (N is then a multiple of 32,
-                        // so that every byte of every word has an owner)
-                        if (ncols >= 32) *dst = word[p];
-                        else if (ncols == 16) reinterpret_cast<uint16_t *>(dst)[(n >> 4) & 1] = (uint16_t)(word[p] >> (n & 16));
-                        else reinterpret_cast<uint8_t *>(dst)[(n >> 3) & 3] = (uint8_t)(word[p] >> shift);
-                    }
-                    word[p] = 0u;
-                }
-            }
-        }
-        for (; n < n1; ++n)  // the last columns of a ragged N (whole-word waves only)
-            add_bits(n, (uint32_t)requantized(output(n, exact_tag, horner_tag), n, bias_tag));
-    };
-    if (packed_only && !g.a_msb_neg) {
-        // uniform over the launch; each combination is a loop of its own so that none pays for the others
-        if (g.Kw == KW) {
-            if (bias) packed_columns(std::true_type{}, std::true_type{}, std::true_type{});
-            else packed_columns(std::true_type{}, std::true_type{}, std::false_type{});
-        } else {
-            if (bias) packed_columns(std::false_type{}, std::true_type{}, std::true_type{});
-            else packed_columns(std::false_type{}, std::true_type{}, std::false_type{});
-        }
-    } else {
-        for (int n = n0; n < n1; ++n) {
-            const int total = output(n, std::false_type{}, std::false_type{});
-            const size_t idx = (size_t)m * g.N + n;
-            uint32_t q = 0;
-            if (o.acc && row_ok) o.acc[idx] = total;
-            if (scale) {
-                const float y = __fmaf_rn((float)total, scale[n], bias ? bias[n] : 0.0f);
-                q = (uint32_t)clamp0(rintf(y), qmax);
-                if (o.y && row_ok) o.y[idx] = y;
-                if (o.q && row_ok) o.q[idx] = (uint8_t)q;
-            }
-            if (o.packed) add_bits(n, q);
-        }
-    }
+// Two independent problems of the same bit widths and register-row length in one launch (two 1x1 convolutions of a
+// single image, each too small to fill the chip and each a dependent launch of 3 us otherwise): the first
+// `blocks0` blocks (a multiple of 8, so that the blocks of the second problem meet the dies as they would alone)
+// are the first problem's.
+template <int AB, int WB, int KW, bool BIPOLAR, bool CONV>
+__global__ __launch_bounds__(kRowsPerBlock * kWavesPerBlock) void contract_rows_pair_kernel(
+    const ContractArgs g0, const FusedOut o0, const int ncols0, const uint32_t *__restrict__ Wp0, const float *__restrict__ scale0,
+    const float *__restrict__ bias0, const ContractArgs g1, const FusedOut o1, const int ncols1, const uint32_t *__restrict__ Wp1,
+    const float *__restrict__ scale1, const float *__restrict__ bias1, const unsigned blocks0)
+{
+    if (blockIdx.x < blocks0) rows_block<AB, WB, KW, BIPOLAR, CONV>(g0, o0, ncols0, 0, Wp0, scale0, bias0, blockIdx.x);
+    else rows_block<AB, WB, KW, BIPOLAR, CONV>(g1, o1, ncols1, 0, Wp1, scale1, bias1, blockIdx.x - blocks0);
 }
 
 // Whether waves of `ncols` columns exist for this call: whole output words, or, on the path that writes nothing but
@@ -466,6 +209,38 @@ dlrt_status launch_conv_or_gemm(const ContractArgs &g, const FusedOut &o, bool c
                 : launch_one<AB, WB, KW, BIPOLAR, false>(g, o, ncols, fine_units, stream);
 }
 
+// Two GEMM-shaped problems (1x1 convolutions) with register rows of the same length in one launch.
+template <int AB, int WB, int KW, bool BIPOLAR>
+dlrt_status launch_pair(const ContractArgs g[2], const FusedOut o[2], const int ncols[2], hipStream_t stream)
+{
+    int64_t blocks[2];
+    for (int i = 0; i < 2; ++i) {
+        if (!has_width(g[i], o[i], ncols[i])) return DLRT_ERR_SHAPE;
+        const int64_t bx = ((int64_t)g[i].M + kRowsPerBlock - 1) / kRowsPerBlock, by = (g[i].N + ncols[i] - 1) / ncols[i];
+        blocks[i] = 8 * (((bx * by + 7) / 8 + kWavesPerBlock - 1) / kWavesPerBlock);
+    }
+    if ((blocks[0] + blocks[1]) * kWavesPerBlock > 0x7fffffffLL) return DLRT_ERR_SHAPE;
+    return dlrt::enqueue(contract_rows_pair_kernel<AB, WB, KW, BIPOLAR, false>, dim3((unsigned)(blocks[0] + blocks[1])),
+                         dim3(kRowsPerBlock * kWavesPerBlock), 0, stream, g[0], o[0], ncols[0], g[0].W, o[0].scale, o[0].bias,
+                         g[1], o[1], ncols[1], g[1].W, o[1].scale, o[1].bias, (unsigned)blocks[0]);
+}
+
+// register-row length that a reduction of Kw words is compiled for (0: none)
+inline int row_length(int Kw) { return Kw <= 1 ? 1 : Kw <= 2 ? 2 : Kw <= 4 ? 4 : Kw <= 8 ? 8 : Kw == 9 ? 9 : Kw <= 16 ? 16 : Kw == 18 ? 18 : 0; }
+
+template <int AB, int WB, bool BIPOLAR>
+dlrt_status pick_pair_kw(const ContractArgs g[2], const FusedOut o[2], const int ncols[2], hipStream_t stream)
+{
+    if (row_length(g[0].Kw) != row_length(g[1].Kw)) return DLRT_ERR_SHAPE;
+    switch (row_length(g[0].Kw)) {  // (pairs exist for the short rows of 1x1 convolutions only)
+    case 1: return launch_pair<AB, WB, 1, BIPOLAR>(g, o, ncols, stream);
+    case 2: return launch_pair<AB, WB, 2, BIPOLAR>(g, o, ncols, stream);
+    case 4: return launch_pair<AB, WB, 4, BIPOLAR>(g, o, ncols, stream);
+    case 8: return launch_pair<AB, WB, 8, BIPOLAR>(g, o, ncols, stream);
+    }
+    return DLRT_ERR_SHAPE;
+}
+
 template <int AB, int WB, bool BIPOLAR>
 dlrt_status pick_kw(const ContractArgs &g, const FusedOut &o, bool conv, int ncols, int fine_units, hipStream_t stream)
 {
@@ -504,6 +279,19 @@ dlrt_status DLRT_CAT(launch_rows_a, DLRT_ABITS)(const ContractArgs &g, const Fus
                                                  bool conv, int ncols, int fine_units, hipStream_t stream)
 {
     return pick_wbits<DLRT_ABITS>(g, o, wbits, bipolar, conv, ncols, fine_units, stream);
+}
+
+dlrt_status DLRT_CAT(launch_rows_pair_a, DLRT_ABITS)(const ContractArgs g[2], const FusedOut o[2], int wbits, bool bipolar,
+                                                      const int ncols[2], hipStream_t stream)
+{
+    constexpr int AB = DLRT_ABITS;
+    switch (wbits) {
+    case 1: return bipolar ? pick_pair_kw<AB, 1, true>(g, o, ncols, stream) : pick_pair_kw<AB, 1, false>(g, o, ncols, stream);
+    case 2: return pick_pair_kw<AB, 2, false>(g, o, ncols, stream);
+    case 3: return pick_pair_kw<AB, 3, false>(g, o, ncols, stream);
+    case 4: return pick_pair_kw<AB, 4, false>(g, o, ncols, stream);
+    }
+    return DLRT_ERR_BITS;
 }
 
 }  // namespace dlrt

@@ -128,6 +128,12 @@ dlrt_status launch_rows_a1(const ContractArgs &g, const FusedOut &o, int wbits, 
 dlrt_status launch_rows_a2(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
 dlrt_status launch_rows_a3(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
 dlrt_status launch_rows_a4(const ContractArgs &g, const FusedOut &o, int wbits, bool bipolar, bool conv, int ncols, int fine_units, hipStream_t stream);
+// Two GEMM-shaped problems (1x1 convolutions) of the same bit widths and register-row length (1, 2, 4 or 8 words) in
+// one launch; DLRT_ERR_SHAPE where no such kernel exists.
+dlrt_status launch_rows_pair_a1(const ContractArgs g[2], const FusedOut o[2], int wbits, bool bipolar, const int ncols[2], hipStream_t stream);
+dlrt_status launch_rows_pair_a2(const ContractArgs g[2], const FusedOut o[2], int wbits, bool bipolar, const int ncols[2], hipStream_t stream);
+dlrt_status launch_rows_pair_a3(const ContractArgs g[2], const FusedOut o[2], int wbits, bool bipolar, const int ncols[2], hipStream_t stream);
+dlrt_status launch_rows_pair_a4(const ContractArgs g[2], const FusedOut o[2], int wbits, bool bipolar, const int ncols[2], hipStream_t stream);
 
 // Panel kernel (contract_panels.hip): one output row per lane, 64 rows x ncols columns per block, the reduction
 // walked in panels of 12 or 16 words against weights held in LDS; for long reductions with many rows.  ncols is

@@ -703,6 +703,46 @@ def test_conv_fused_every_tile_height_and_reduction_split_gives_the_same_result(
         fused_case(dlrt, oracle, x1, w1, 1, 1, 1, 1, UNSIGNED, TWOS, 1, 4, ksplit)   # two accumulators per activation word
 
 
+@pytest.mark.parametrize("widths", [(2, 1, BIPOLAR), (2, 2, TWOS), (1, 1, TWOS), (4, 4, TWOS)])
+def test_conv_fused_pair_of_row_kernel_layers(dlrt, oracle, widths):
+    """Two 1x1 convs on one image that both take the row kernel share a row-kernel launch when their reductions fill
+    register rows of the same length: the YOLO-style split / merge pair (25600 pixels, 64 -> 32 and 64 -> 64 channels),
+    a pair on different tensors with ragged shapes (32761 pixels x 40 channels over 100, 22500 x 96 over 128: rows of 4 words),
+    and a pair whose rows differ in length, which goes out as two launches.  Packed output only, as in a chain, and
+    every output kind."""
+    abits, wbits, ew = widths
+    cases = [((1, 160, 160, 64), 32, (1, 160, 160, 64), 64), ((1, 181, 181, 100), 40, (1, 150, 150, 128), 96),
+             ((1, 80, 80, 128), 64, (1, 80, 80, 64), 64)]
+    for idx, (xs0, co0, xs1, co1) in enumerate(cases):
+        for packed_only in (True, False):
+            probs, refs, keep = [], [], []
+            for k, (xs, Co) in enumerate(((xs0, co0), (xs1, co1))):
+                x = inputs.uniform_values(xs, abits, UNSIGNED, 63000 + 10 * idx + k)
+                w = inputs.uniform_values((Co, 1, 1, xs[3]), wbits, ew, 64000 + 10 * idx + k)
+                ref = oracle.conv2d_i32(x, w, (1, 1), (0, 0))
+                scale, bias = calibrate(ref)
+                y_ref, q_ref = oracle.epilogue_f32(ref, scale, bias, qbits=2)
+                X = dlrt.dlrt_pack_bitplanes(src_tensor(x, UNSIGNED), abits, UNSIGNED)
+                Wp = dlrt.dlrt_pack_conv_weights(src_tensor(w, ew), wbits, ew)
+                Mo = ref.shape[0] * ref.shape[1] * ref.shape[2]
+                acc = torch.full(ref.shape, -7, dtype=torch.int32, device=DEV)
+                y = torch.full(ref.shape, -7.0, dtype=torch.float32, device=DEV)
+                packed = torch.full((Mo, 2, (Co + 31) // 32), -1, dtype=torch.int32, device=DEV)
+                sc, bs = dev(scale), dev(bias)
+                probs.append(dlrt.conv_problem(X, Wp, sc, bs, xs[0], xs[1], xs[2], xs[3], Co, 1, 1, (1, 1), (0, 0), abits, wbits,
+                                               qbits=2, out_acc=None if packed_only else acc, out_f32=None if packed_only else y,
+                                               out_packed=packed))
+                refs.append((ref, y_ref, oracle.pack_bitplanes(q_ref.reshape(Mo, Co).astype(np.int8), 2, UNSIGNED)))
+                keep.append((X, Wp, sc, bs, acc, y, packed))
+            dlrt.dlrt_bitserial_conv2d_fused_pair(probs[0], probs[1], abits, wbits, UNSIGNED, ew)
+            torch.cuda.synchronize()
+            for (ref, y_ref, p_ref), (_, _, _, _, acc, y, packed) in zip(refs, keep):
+                assert np.array_equal(words(packed), p_ref), (idx, packed_only)
+                if not packed_only:
+                    assert np.array_equal(acc.cpu().numpy(), ref), idx
+                    assert np.array_equal(y.cpu().numpy(), y_ref), idx
+
+
 def test_conv_fused_pair_two_problems_in_one_launch(dlrt, oracle):
     """A stride-2 3x3 conv and the 1x1 stride-2 conv beside it (different reduction depths, so different
     numbers of waves would be planned), then two unrelated problems with ragged shapes; bipolar too."""
