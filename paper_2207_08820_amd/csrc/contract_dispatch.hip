@@ -419,12 +419,18 @@ dlrt_status launch_conv_pair(const uint32_t *const X[2], const uint32_t *const W
     int ksplit = 1;
     const int rows = wbits <= 2 ? 8 : 4;  // both problems on the smallest wave tile
     // sharing a launch (on the smallest wave tile) pays while neither problem can fill the chip; larger ones
-    // run faster on a kernel and tile of their own, so such a pair goes out as two ordinary launches
+    // run faster on a kernel and tile of their own, so such a pair goes out as two ordinary launches.  A problem of
+    // at most 2^20 outputs shares a launch even where it would take the row kernel alone: the dependent launch
+    // it saves (3 us) is worth more than the row kernel's lead on it (25600 x 32 x 32: 3.3 against 4.4 us; the
+    // YOLO-style batch-1 chain 61.6 -> 60.3 us with the two pairs this adds).
     bool pairable = true;
     for (int i = 0; i < 2; ++i) {
         const int64_t M = (int64_t)c[i].N * c[i].Ho * c[i].Wo;
         const int Kw = c[i].KH * c[i].KW * c[i].Cw;
-        pairable = pairable && block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) && !prefer_rows_kernel(M, c[i].Co, Kw, abits, wbits, o[i].packed && !o[i].acc && !o[i].y && !o[i].q && !a_msb_neg);
+        const bool halves = o[i].packed && !o[i].acc && !o[i].y && !o[i].q && !a_msb_neg;
+        const bool wave_layer = block_tiles((int)M, c[i].Co, abits, wbits) < wave_below(abits) &&
+                                !prefer_rows_kernel(M, c[i].Co, Kw, abits, wbits, halves);
+        pairable = pairable && (wave_layer || M * c[i].Co <= (1 << 20));
     }
     if (!pairable) {
         for (int i = 0; i < 2; ++i) {
